@@ -1,0 +1,184 @@
+/*
+ * coda.h -- C ABI of the MI355X (gfx950) GEMM-plus-epilogue library.
+ *
+ * One call, coda_gemm, runs a dense bf16 GEMM with fp32 accumulation and then,
+ * while the output tile is still in registers, an ordered list of epilogue
+ * primitives ("epilogue program") before anything is written to memory.  This
+ * is the paper's statement of the method: a fixed GEMM mainloop plus a small
+ * set of composable epilogue primitives for scaling, reductions, pairwise
+ * transforms and accumulation (Section 3.1), applied in list order like the
+ * ordered primitive list of the paper's kernel example (Appendix "Epilogue
+ * Example").  The remaining entry points are the lightweight auxiliary
+ * reduction of Section 3.2.1 and one-time weight preparation.
+ *
+ * Conventions (all entry points)
+ *  - Every pointer is a DEVICE pointer unless the comment says "host".  The
+ *    caller owns all buffers; the library allocates nothing, keeps no state
+ *    beyond a last-HIP-error slot, never synchronises, and only enqueues work
+ *    on the given stream (`stream` is a hipStream_t passed as void*; NULL is
+ *    the default stream).
+ *  - Matrices are row-major.  `ld` is the row pitch in ELEMENTS.  bf16 is the
+ *    upper half of an IEEE binary32, stored as 16-bit words.
+ *  - "row" means a row of the GEMM output (a token): a row scale multiplies
+ *    row i by r[i], a row reduction sums over the columns of row i.
+ *  - Alignment: every matrix pointer 16-byte aligned, every ld a multiple of 8
+ *    elements; vectors 4-byte aligned.
+ *  - Errors are return codes; on any error nothing has been enqueued.
+ *  - Outputs must not alias inputs, except the in/out buffer of ACCUM_F32.
+ */
+#ifndef CODA_H
+#define CODA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum coda_status {
+    CODA_OK = 0,
+    CODA_ERR_NULL = 1,      /* a required pointer is NULL                          */
+    CODA_ERR_SHAPE = 2,     /* negative / inconsistent / unsupported sizes         */
+    CODA_ERR_ALIGN = 3,     /* pointer or leading dimension not aligned            */
+    CODA_ERR_DTYPE = 4,     /* operand dtype not supported in that position        */
+    CODA_ERR_PROGRAM = 5,   /* epilogue op list is not a supported program         */
+    CODA_ERR_WORKSPACE = 6, /* workspace too small                                 */
+    CODA_ERR_LAUNCH = 7     /* HIP reported an error; see coda_last_hip_error()    */
+} coda_status;
+
+typedef enum coda_dtype { CODA_BF16 = 0, CODA_F32 = 1 } coda_dtype;
+
+/*
+ * A GEMM operand.  rows/cols/ld describe the matrix AS STORED.
+ * trans == 0: the GEMM uses it as stored; trans != 0: the GEMM uses its
+ * transpose (no data is moved).  coda_gemm computes op(A)[M x K] * op(B)[K x N];
+ * the forms D = A B, D = A B^T and D = A^T B of the paper's kernel list are the
+ * trans combinations (0,0), (0,1), (1,0).
+ */
+typedef struct coda_mat {
+    const void *ptr; /* device */
+    int64_t rows, cols, ld;
+    int32_t trans;
+    int32_t dtype; /* coda_dtype; operands must be CODA_BF16 */
+} coda_mat;
+
+/*
+ * Epilogue primitives (Section 3.1: elementwise and pairwise maps, vector loads,
+ * tile loads and stores, tile reductions; Appendix "List of Kernels").
+ * "v" is the running fp32 value of output element (i, j); W is the current
+ * width (N until a pairwise op changes it).
+ */
+typedef enum coda_epi_kind {
+    /* v *= r[i].               in: f32[M]            (Kernel 5: O = D (.) r)          */
+    CODA_EPI_ROW_SCALE = 0,
+    /* side output, v unchanged: out[i][j] = bf16(v * gamma[j]).
+       in: f32[N] gamma, out: bf16[M x N] (ld_out)   (Kernel 4: O = D (.) gamma)      */
+    CODA_EPI_COL_SCALE_SIDE = 1,
+    /* v += float(C[i][j]).     in: bf16[M x N] (ld_in)  (Kernel 4: D = A B + C)      */
+    CODA_EPI_ADD_TILE = 2,
+    /* Pairwise, width N -> N/2 (Kernels 2, 6): g = v[i][2p], u = v[i][2p+1],
+       v'[i][p] = silu(g) * u.  Optional out: bf16[M x N] (ld_out) receives the
+       pre-activation v (what Kernel 10 later reads as Z).  N must be even.            */
+    CODA_EPI_SWIGLU_FWD = 3,
+    /* Pairwise, width N -> 2N (Kernel 10): with d = v[i][j], g = Z[i][2j],
+       u = Z[i][2j+1]:  v'[i][2j] = d*u*(sigma(g) + silu(g)*(1 - sigma(g))),
+       v'[i][2j+1] = d*silu(g).   in: bf16[M x 2N] Z (ld_in).
+       Optional out: bf16[M x N] (ld_out) receives silu(g)*u (the recomputed
+       forward activation).  Optional out2: f32 row statistic
+       sum_j (g*dG + u*dU), laid out per `flags` like ROW_SUMSQ.                       */
+    CODA_EPI_SWIGLU_BWD = 4,
+    /* Row reduction of v*v over the columns of this tile, taken on the fp32
+       value before any rounding (Kernel 4: reduceTile_cols(D (.) D)).
+       out: f32, layout chosen by `flags`:
+         CODA_REDUCE_PARTIALS: out is [nblk x M] (block-major: out[b*M + i]),
+             nblk = coda_row_partial_blocks(N); every entry is overwritten;
+             combine with coda_row_finalize.  Deterministic.
+         CODA_REDUCE_ATOMIC:   out is f32[M], pre-zeroed by the caller; tiles add
+             into it with fp32 atomics (summation order varies run to run).            */
+    CODA_EPI_ROW_SUMSQ = 5,
+    /* Final op: round v to `flags & CODA_STORE_F32 ? f32 : bf16` (nearest even)
+       and write out[i][j], width W (ld_out).                                          */
+    CODA_EPI_STORE = 6,
+    /* Final op: out[i][j] += v in fp32, in place (the weight-gradient GEMM of
+       Theorem 1 accumulated into an existing gradient buffer). out: f32[M x N].       */
+    CODA_EPI_ACCUM_F32 = 7
+} coda_epi_kind;
+
+#define CODA_REDUCE_PARTIALS 0u
+#define CODA_REDUCE_ATOMIC 1u
+#define CODA_STORE_F32 2u
+
+typedef struct coda_epi_op {
+    int32_t kind;   /* coda_epi_kind */
+    uint32_t flags; /* see the op */
+    const void *in; /* device */
+    void *out;      /* device */
+    void *out2;     /* device */
+    int64_t ld_in, ld_out;
+} coda_epi_op;
+
+/*
+ * D = op(A) op(B) (bf16 in, fp32 accumulate), then `prog[0..n_ops)` in order.
+ *
+ * Supported programs (anything else -> CODA_ERR_PROGRAM): ops must appear in
+ * the order
+ *     [ROW_SCALE] [ADD_TILE] [ROW_SUMSQ] [COL_SCALE_SIDE] STORE
+ *     [ROW_SCALE] SWIGLU_FWD STORE
+ *     SWIGLU_BWD STORE
+ *     ACCUM_F32
+ * with bracketed ops optional and each at most once.  These cover Kernels 2, 4,
+ * 5, 6, 10, the plain GEMM (STORE alone) and the accumulating weight gradient.
+ *
+ * Sizes: M, N, K >= 0 must equal the op() shapes of A and B.  M == 0 or N == 0
+ * is a no-op; K == 0 runs the program on D = 0.  K must be a multiple of 8; N a
+ * multiple of 8; and M a multiple of 8 when A is used transposed.  No other
+ * divisibility is required (edge tiles are predicated).
+ *
+ * workspace / workspace_bytes: scratch of at least
+ * coda_gemm_workspace_bytes(...) bytes (currently always 0; may be NULL).
+ */
+coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_mat *A,
+                      const coda_mat *B, const coda_epi_op *prog /* host */, int32_t n_ops,
+                      void *workspace, size_t workspace_bytes);
+
+size_t coda_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, const coda_epi_op *prog /* host */,
+                                 int32_t n_ops);
+
+/* Number of column blocks nblk of a CODA_REDUCE_PARTIALS buffer for output width N
+   (the partial buffer is f32[nblk x M]). */
+int64_t coda_row_partial_blocks(int64_t N);
+
+/*
+ * Lightweight auxiliary reduction (Section 3.2.1): combine tile partials and
+ * optionally form r = 1/sqrt(reduce(partials)/d + eps).
+ * partials: f32[nblk x M] (block-major).  sum_out, rstd_out: f32[M], either may
+ * be NULL (not both).  d > 0 is the hidden size the mean is taken over.
+ */
+coda_status coda_row_finalize(void *stream, const float *partials, int64_t M, int64_t nblk,
+                              float *sum_out, float *rstd_out, int64_t d, float eps);
+
+/* ss[i] = sum_k X[i][k]^2 in fp32 for a bf16 matrix not produced by coda_gemm
+   (the first layer's input).  X->trans must be 0.  sum_out: f32[X->rows]. */
+coda_status coda_row_sumsq(void *stream, const coda_mat *X, float *sum_out);
+
+/* One-time weight preparation: W_out[k][j] = bf16(gamma[k] * W[k][j]) so that
+   RMSNorm(x, gamma) W == diag(r) (x W_out).  W is [K x N] as stored (trans 0);
+   gamma f32[K]; W_out bf16 [K x N] with pitch ld_out. */
+coda_status coda_fold_gamma(void *stream, const coda_mat *W, const float *gamma, void *W_out,
+                            int64_t ld_out);
+
+/* One-time weight preparation: interleave the columns of two [K x N] bf16
+   matrices: W_out[k][2j] = Wa[k][j] (gate), W_out[k][2j+1] = Wb[k][j] (up).
+   W_out is bf16 [K x 2N] with pitch ld_out. */
+coda_status coda_interleave_pairs(void *stream, const coda_mat *Wa, const coda_mat *Wb, void *W_out,
+                                  int64_t ld_out);
+
+const char *coda_status_string(coda_status s);
+/* The hipError_t (as int) recorded by the most recent CODA_ERR_LAUNCH on this thread. */
+int coda_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CODA_H */

@@ -1,0 +1,197 @@
+"""ctypes binding of libcoda.so -- argument marshalling only.
+
+Every function here has the name of the C entry point it forwards to (include/coda.h)
+and does nothing but turn torch tensors into raw device pointers, sizes and pitches.
+All arithmetic happens in the HIP kernels.  If the library has not been built the
+import of this module fails loudly; there is no fallback path of any kind.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcoda.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libcoda.so is not built (%s). Build it with `python -m paper_2605_19269_amd.build`; "
+        "there is no fallback implementation." % LIB_PATH)
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+# status codes / enums (mirrors of include/coda.h)
+CODA_OK, CODA_ERR_NULL, CODA_ERR_SHAPE, CODA_ERR_ALIGN, CODA_ERR_DTYPE, CODA_ERR_PROGRAM, \
+    CODA_ERR_WORKSPACE, CODA_ERR_LAUNCH = range(8)
+CODA_BF16, CODA_F32 = 0, 1
+(CODA_EPI_ROW_SCALE, CODA_EPI_COL_SCALE_SIDE, CODA_EPI_ADD_TILE, CODA_EPI_SWIGLU_FWD, CODA_EPI_SWIGLU_BWD,
+ CODA_EPI_ROW_SUMSQ, CODA_EPI_STORE, CODA_EPI_ACCUM_F32) = range(8)
+CODA_REDUCE_PARTIALS, CODA_REDUCE_ATOMIC, CODA_STORE_F32 = 0, 1, 2
+
+EXPORTS = ["coda_gemm", "coda_gemm_workspace_bytes", "coda_row_partial_blocks", "coda_row_finalize",
+           "coda_row_sumsq", "coda_fold_gamma", "coda_interleave_pairs", "coda_status_string",
+           "coda_last_hip_error"]
+
+
+class coda_mat(ctypes.Structure):
+    _fields_ = [("ptr", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("ld", ctypes.c_int64), ("trans", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class coda_epi_op(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("flags", ctypes.c_uint32), ("in_", ctypes.c_void_p),
+                ("out", ctypes.c_void_p), ("out2", ctypes.c_void_p), ("ld_in", ctypes.c_int64),
+                ("ld_out", ctypes.c_int64)]
+
+
+_vp, _i64, _i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+_lib.coda_gemm.restype = ctypes.c_int
+_lib.coda_gemm.argtypes = [_vp, _i64, _i64, _i64, ctypes.POINTER(coda_mat), ctypes.POINTER(coda_mat),
+                           ctypes.POINTER(coda_epi_op), _i32, _vp, ctypes.c_size_t]
+_lib.coda_gemm_workspace_bytes.restype = ctypes.c_size_t
+_lib.coda_gemm_workspace_bytes.argtypes = [_i64, _i64, _i64, ctypes.POINTER(coda_epi_op), _i32]
+_lib.coda_row_partial_blocks.restype = _i64
+_lib.coda_row_partial_blocks.argtypes = [_i64]
+_lib.coda_row_finalize.restype = ctypes.c_int
+_lib.coda_row_finalize.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _i64, ctypes.c_float]
+_lib.coda_row_sumsq.restype = ctypes.c_int
+_lib.coda_row_sumsq.argtypes = [_vp, ctypes.POINTER(coda_mat), _vp]
+_lib.coda_fold_gamma.restype = ctypes.c_int
+_lib.coda_fold_gamma.argtypes = [_vp, ctypes.POINTER(coda_mat), _vp, _vp, _i64]
+_lib.coda_interleave_pairs.restype = ctypes.c_int
+_lib.coda_interleave_pairs.argtypes = [_vp, ctypes.POINTER(coda_mat), ctypes.POINTER(coda_mat), _vp, _i64]
+_lib.coda_status_string.restype = ctypes.c_char_p
+_lib.coda_status_string.argtypes = [ctypes.c_int]
+_lib.coda_last_hip_error.restype = ctypes.c_int
+_lib.coda_last_hip_error.argtypes = []
+
+
+class CodaError(RuntimeError):
+    def __init__(self, status):
+        self.status = status
+        msg = _lib.coda_status_string(status).decode()
+        if status == CODA_ERR_LAUNCH:
+            msg += " (hipError %d)" % _lib.coda_last_hip_error()
+        super().__init__("coda status %d: %s" % (status, msg))
+
+
+def _check(status):
+    if status != CODA_OK:
+        raise CodaError(status)
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _ld(t):
+    return 0 if t is None else (t.stride(0) if t.dim() == 2 else 0)
+
+
+def mat(t, trans=False):
+    """coda_mat describing a 2-D torch tensor as stored (row-major, unit column stride)."""
+    import torch
+    assert t.dim() == 2 and (t.shape[1] <= 1 or t.stride(1) == 1), "row-major 2-D tensor expected"
+    dt = CODA_BF16 if t.dtype == torch.bfloat16 else CODA_F32
+    return coda_mat(t.data_ptr(), t.shape[0], t.shape[1], t.stride(0), 1 if trans else 0, dt)
+
+
+def _op(kind, flags=0, in_=None, out=None, out2=None):
+    return coda_epi_op(kind, flags, _ptr(in_), _ptr(out), _ptr(out2), _ld(in_), _ld(out))
+
+
+# --- epilogue op constructors (keep the tensors alive until the call returns) ----------------
+def row_scale(r):
+    return _op(CODA_EPI_ROW_SCALE, in_=r)
+
+
+def col_scale_side(gamma, out):
+    return _op(CODA_EPI_COL_SCALE_SIDE, in_=gamma, out=out)
+
+
+def add_tile(C):
+    return _op(CODA_EPI_ADD_TILE, in_=C)
+
+
+def swiglu_fwd(preact_out=None):
+    return _op(CODA_EPI_SWIGLU_FWD, out=preact_out)
+
+
+def swiglu_bwd(Z, act_out=None, stat_out=None, atomic=False):
+    return _op(CODA_EPI_SWIGLU_BWD, CODA_REDUCE_ATOMIC if atomic else CODA_REDUCE_PARTIALS, in_=Z,
+               out=act_out, out2=stat_out)
+
+
+def row_sumsq(out, atomic=False):
+    return _op(CODA_EPI_ROW_SUMSQ, CODA_REDUCE_ATOMIC if atomic else CODA_REDUCE_PARTIALS, out=out)
+
+
+def store(out, f32=False):
+    return _op(CODA_EPI_STORE, CODA_STORE_F32 if f32 else 0, out=out)
+
+
+def accum_f32(G):
+    return _op(CODA_EPI_ACCUM_F32, out=G)
+
+
+def _prog(ops):
+    arr = (coda_epi_op * max(1, len(ops)))(*ops)
+    return arr, len(ops)
+
+
+# --- entry points -------------------------------------------------------------------------------
+def coda_gemm_raw(stream, M, N, K, A, B, ops, workspace=None, workspace_bytes=0):
+    """Forward coda_mat / coda_epi_op values unchanged; returns the status code."""
+    arr, n = _prog(ops)
+    return _lib.coda_gemm(stream, M, N, K, ctypes.byref(A) if A is not None else None,
+                          ctypes.byref(B) if B is not None else None, arr if ops is not None else None, n,
+                          workspace, workspace_bytes)
+
+
+def coda_gemm(A, B, ops, transA=False, transB=False, stream=None):
+    """D = op(A) op(B), then the epilogue ops in order.  A, B: 2-D bf16 CUDA tensors as stored."""
+    a, b = mat(A, transA), mat(B, transB)
+    M, K = (A.shape[1], A.shape[0]) if transA else (A.shape[0], A.shape[1])
+    N = B.shape[0] if transB else B.shape[1]
+    _check(coda_gemm_raw(_stream(stream), M, N, K, a, b, list(ops)))
+
+
+def coda_gemm_workspace_bytes(M, N, K, ops):
+    arr, n = _prog(list(ops))
+    return _lib.coda_gemm_workspace_bytes(M, N, K, arr, n)
+
+
+def coda_row_partial_blocks(N):
+    return _lib.coda_row_partial_blocks(N)
+
+
+def coda_row_finalize(partials, M, nblk, sum_out=None, rstd_out=None, d=1, eps=0.0, stream=None):
+    _check(_lib.coda_row_finalize(_stream(stream), _ptr(partials), M, nblk, _ptr(sum_out), _ptr(rstd_out), d, eps))
+
+
+def coda_row_sumsq(X, sum_out, stream=None):
+    m = mat(X)
+    _check(_lib.coda_row_sumsq(_stream(stream), ctypes.byref(m), _ptr(sum_out)))
+
+
+def coda_fold_gamma(W, gamma, W_out, stream=None):
+    m = mat(W)
+    _check(_lib.coda_fold_gamma(_stream(stream), ctypes.byref(m), _ptr(gamma), _ptr(W_out), W_out.stride(0)))
+
+
+def coda_interleave_pairs(Wa, Wb, W_out, stream=None):
+    a, b = mat(Wa), mat(Wb)
+    _check(_lib.coda_interleave_pairs(_stream(stream), ctypes.byref(a), ctypes.byref(b), _ptr(W_out), W_out.stride(0)))
+
+
+def coda_status_string(status):
+    return _lib.coda_status_string(status).decode()
+
+
+def coda_last_hip_error():
+    return _lib.coda_last_hip_error()

@@ -1,0 +1,302 @@
+// coda_api.hip -- the C ABI (include/coda.h): argument validation, canonicalisation of
+// the epilogue program into one of the pre-instantiated kernel variants, launch.
+// Nothing here allocates, synchronises or keeps state beyond the last HIP error.
+#include "../../include/coda.h"
+
+#include "aux_kernels.hpp"
+#include "gemm_launch.hpp"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+coda_status launch_status(hipError_t e)
+{
+    if (e == hipSuccess) return CODA_OK;
+    g_last_hip_error = (int)e;
+    return CODA_ERR_LAUNCH;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+
+// Shape / alignment checks of a bf16 operand whose op() shape must be [r x c].
+coda_status check_operand(const coda_mat *X, int64_t r, int64_t c)
+{
+    if (!X) return CODA_ERR_NULL;
+    if (X->dtype != CODA_BF16) return CODA_ERR_DTYPE;
+    const int64_t sr = X->trans ? c : r, sc = X->trans ? r : c;
+    if (X->rows != sr || X->cols != sc || X->ld < sc) return CODA_ERR_SHAPE;
+    if (sr > 0 && sc > 0 && !X->ptr) return CODA_ERR_NULL;
+    if (!aligned16(X->ptr) || (X->ld & 7)) return CODA_ERR_ALIGN;
+    return CODA_OK;
+}
+
+coda_status check_tile(const void *p, int64_t ld, int64_t width)
+{
+    if (!p) return CODA_ERR_NULL;
+    if (ld < width) return CODA_ERR_SHAPE;
+    if (!aligned16(p) || (ld & 7)) return CODA_ERR_ALIGN;
+    return CODA_OK;
+}
+
+coda_status check_vec(const void *p)
+{
+    if (!p) return CODA_ERR_NULL;
+    return aligned4(p) ? CODA_OK : CODA_ERR_ALIGN;
+}
+
+struct Parsed {
+    int mode = -1;
+    coda::GemmParams p{};
+};
+
+// Canonical order: ROW_SCALE < ADD_TILE < ROW_SUMSQ < COL_SCALE_SIDE < final.
+coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Parsed &out)
+{
+    if (n_ops < 0 || (n_ops > 0 && !prog)) return CODA_ERR_NULL;
+    coda::GemmParams &p = out.p;
+    int stage = 0;           // next admissible position in the canonical order
+    int pair = 0;            // 0 none, 1 swiglu fwd, 2 swiglu bwd
+    bool final_seen = false;
+    bool linear_only = false;  // an op that only the linear program supports was used
+    for (int i = 0; i < n_ops; ++i) {
+        const coda_epi_op &op = prog[i];
+        if (final_seen) return CODA_ERR_PROGRAM;
+        coda_status st;
+        switch (op.kind) {
+        case CODA_EPI_ROW_SCALE:
+            if (stage > 0 || pair) return CODA_ERR_PROGRAM;
+            if ((st = check_vec(op.in)) != CODA_OK) return st;
+            p.row_scale = static_cast<const float *>(op.in);
+            stage = 1;
+            break;
+        case CODA_EPI_ADD_TILE:
+            if (stage > 1 || pair) return CODA_ERR_PROGRAM;
+            if ((st = check_tile(op.in, op.ld_in, N)) != CODA_OK) return st;
+            p.add = static_cast<const uint16_t *>(op.in);
+            p.ld_add = op.ld_in;
+            stage = 2;
+            linear_only = true;
+            break;
+        case CODA_EPI_ROW_SUMSQ:
+            if (stage > 2 || pair) return CODA_ERR_PROGRAM;
+            if ((st = check_vec(op.out)) != CODA_OK) return st;
+            if (op.flags != CODA_REDUCE_PARTIALS && op.flags != CODA_REDUCE_ATOMIC) return CODA_ERR_PROGRAM;
+            p.rowred = static_cast<float *>(op.out);
+            p.rowred_mode = op.flags == CODA_REDUCE_ATOMIC ? coda::ROWRED_ATOMIC : coda::ROWRED_PARTIALS;
+            stage = 3;
+            linear_only = true;
+            break;
+        case CODA_EPI_COL_SCALE_SIDE:
+            if (stage > 3 || pair) return CODA_ERR_PROGRAM;
+            if ((st = check_vec(op.in)) != CODA_OK) return st;
+            if (!aligned16(op.in)) return CODA_ERR_ALIGN;
+            if ((st = check_tile(op.out, op.ld_out, N)) != CODA_OK) return st;
+            p.col_scale = static_cast<const float *>(op.in);
+            p.side = static_cast<uint16_t *>(op.out);
+            p.ld_side = op.ld_out;
+            stage = 4;
+            linear_only = true;
+            break;
+        case CODA_EPI_SWIGLU_FWD:
+            if (pair || linear_only || (N & 1)) return CODA_ERR_PROGRAM;
+            if (op.out) {
+                if ((st = check_tile(op.out, op.ld_out, N)) != CODA_OK) return st;
+                p.out2 = static_cast<uint16_t *>(op.out);
+                p.ld_out2 = op.ld_out;
+            }
+            pair = 1;
+            stage = 5;
+            break;
+        case CODA_EPI_SWIGLU_BWD:
+            if (pair || linear_only || stage > 0) return CODA_ERR_PROGRAM;
+            if ((st = check_tile(op.in, op.ld_in, 2 * N)) != CODA_OK) return st;
+            p.Z = static_cast<const uint16_t *>(op.in);
+            p.ldz = op.ld_in;
+            if (op.out) {
+                if ((st = check_tile(op.out, op.ld_out, N)) != CODA_OK) return st;
+                p.out2 = static_cast<uint16_t *>(op.out);
+                p.ld_out2 = op.ld_out;
+            }
+            if (op.out2) {
+                if ((st = check_vec(op.out2)) != CODA_OK) return st;
+                if ((op.flags & ~1u) != 0) return CODA_ERR_PROGRAM;
+                p.rowred = static_cast<float *>(op.out2);
+                p.rowred_mode = (op.flags & CODA_REDUCE_ATOMIC) ? coda::ROWRED_ATOMIC : coda::ROWRED_PARTIALS;
+            }
+            pair = 2;
+            stage = 5;
+            break;
+        case CODA_EPI_STORE: {
+            const bool f32 = (op.flags & CODA_STORE_F32) != 0;
+            if ((op.flags & ~CODA_STORE_F32) != 0) return CODA_ERR_PROGRAM;
+            if (pair && f32) return CODA_ERR_PROGRAM;
+            const int64_t width = pair == 1 ? N / 2 : pair == 2 ? 2 * N : N;
+            if (!op.out) return CODA_ERR_NULL;
+            if (op.ld_out < width) return CODA_ERR_SHAPE;
+            if (!aligned16(op.out) || (op.ld_out & (f32 ? 3 : 7))) return CODA_ERR_ALIGN;
+            p.out = op.out;
+            p.ld_out = op.ld_out;
+            p.out_f32 = f32 ? 1 : 0;
+            out.mode = pair == 1 ? coda::EPI_SWIGLU_FWD : pair == 2 ? coda::EPI_SWIGLU_BWD : coda::EPI_LINEAR;
+            final_seen = true;
+            break;
+        }
+        case CODA_EPI_ACCUM_F32:
+            if (stage > 0 || pair) return CODA_ERR_PROGRAM;
+            if (!op.out) return CODA_ERR_NULL;
+            if (op.ld_out < N) return CODA_ERR_SHAPE;
+            if (!aligned16(op.out) || (op.ld_out & 3)) return CODA_ERR_ALIGN;
+            p.out = op.out;
+            p.ld_out = op.ld_out;
+            out.mode = coda::EPI_ACCUM;
+            final_seen = true;
+            break;
+        default:
+            return CODA_ERR_PROGRAM;
+        }
+    }
+    return final_seen ? CODA_OK : CODA_ERR_PROGRAM;
+}
+
+template <bool AK, bool BKC>
+hipError_t dispatch_mode(int mode, bool edge, const coda::GemmParams &p, hipStream_t s)
+{
+    using namespace coda;
+    switch (mode) {
+    case EPI_LINEAR:
+        return edge ? launch_gemm<AK, BKC, EPI_LINEAR, true>(p, s) : launch_gemm<AK, BKC, EPI_LINEAR, false>(p, s);
+    case EPI_SWIGLU_FWD:
+        return edge ? launch_gemm<AK, BKC, EPI_SWIGLU_FWD, true>(p, s) : launch_gemm<AK, BKC, EPI_SWIGLU_FWD, false>(p, s);
+    case EPI_SWIGLU_BWD:
+        return edge ? launch_gemm<AK, BKC, EPI_SWIGLU_BWD, true>(p, s) : launch_gemm<AK, BKC, EPI_SWIGLU_BWD, false>(p, s);
+    default:
+        return edge ? launch_gemm<AK, BKC, EPI_ACCUM, true>(p, s) : launch_gemm<AK, BKC, EPI_ACCUM, false>(p, s);
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_mat *A, const coda_mat *B,
+                      const coda_epi_op *prog, int32_t n_ops, void *workspace, size_t workspace_bytes)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    if (M < 0 || N < 0 || K < 0 || M > INT32_MAX || N > INT32_MAX / 2 || K > INT32_MAX) return CODA_ERR_SHAPE;
+    coda_status st;
+    if ((st = check_operand(A, M, K)) != CODA_OK) return st;
+    if ((st = check_operand(B, K, N)) != CODA_OK) return st;
+    if ((K & 7) || (N & 7) || (A->trans && (M & 7))) return CODA_ERR_SHAPE;
+    Parsed ps;
+    if ((st = parse_program(prog, n_ops, N, ps)) != CODA_OK) return st;
+    if (M == 0 || N == 0) return CODA_OK;
+
+    using C = coda::MainCfg;
+    coda::GemmParams &p = ps.p;
+    p.A = static_cast<const uint16_t *>(A->ptr);
+    p.B = static_cast<const uint16_t *>(B->ptr);
+    p.lda = A->ld;
+    p.ldb = B->ld;
+    p.M = (int)M;
+    p.N = (int)N;
+    p.K = (int)K;
+    p.tiles_m = (int)((M + C::BM - 1) / C::BM);
+    p.tiles_n = (int)((N + C::BN - 1) / C::BN);
+    if ((int64_t)p.tiles_m * p.tiles_n > INT32_MAX) return CODA_ERR_SHAPE;
+    const bool edge = (M % C::BM) || (N % C::BN) || (K % C::BK);
+    const bool ak = !A->trans;   // A stored [M x K]: contraction index contiguous
+    const bool bkc = B->trans;   // B stored [N x K]: contraction index contiguous
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (ak && !bkc)
+        e = dispatch_mode<true, false>(ps.mode, edge, p, s);
+    else if (ak && bkc)
+        e = dispatch_mode<true, true>(ps.mode, edge, p, s);
+    else if (!ak && !bkc)
+        e = dispatch_mode<false, false>(ps.mode, edge, p, s);
+    else
+        e = dispatch_mode<false, true>(ps.mode, edge, p, s);
+    return launch_status(e);
+}
+
+size_t coda_gemm_workspace_bytes(int64_t, int64_t, int64_t, const coda_epi_op *, int32_t) { return 0; }
+
+int64_t coda_row_partial_blocks(int64_t N)
+{
+    return N <= 0 ? 0 : (N + coda::MainCfg::BN - 1) / coda::MainCfg::BN;
+}
+
+coda_status coda_row_finalize(void *stream, const float *partials, int64_t M, int64_t nblk, float *sum_out,
+                              float *rstd_out, int64_t d, float eps)
+{
+    if (M < 0 || nblk < 0 || d <= 0) return CODA_ERR_SHAPE;
+    if (!sum_out && !rstd_out) return CODA_ERR_NULL;
+    if (M == 0) return CODA_OK;
+    if (nblk > 0 && !partials) return CODA_ERR_NULL;
+    if (!aligned4(partials) || !aligned4(sum_out) || !aligned4(rstd_out)) return CODA_ERR_ALIGN;
+    return launch_status(coda::launch_row_finalize(static_cast<hipStream_t>(stream), partials, M, nblk, sum_out,
+                                                   rstd_out, 1.0f / (float)d, eps));
+}
+
+coda_status coda_row_sumsq(void *stream, const coda_mat *X, float *sum_out)
+{
+    if (!X || !sum_out) return CODA_ERR_NULL;
+    if (X->dtype != CODA_BF16) return CODA_ERR_DTYPE;
+    if (X->trans || X->rows < 0 || X->cols < 0 || X->ld < X->cols || (X->cols & 7)) return CODA_ERR_SHAPE;
+    if (X->rows == 0) return CODA_OK;
+    if (!X->ptr) return CODA_ERR_NULL;
+    if (!aligned16(X->ptr) || (X->ld & 7) || !aligned4(sum_out)) return CODA_ERR_ALIGN;
+    return launch_status(coda::launch_row_sumsq(static_cast<hipStream_t>(stream), static_cast<const uint16_t *>(X->ptr),
+                                                X->rows, X->cols, X->ld, sum_out));
+}
+
+coda_status coda_fold_gamma(void *stream, const coda_mat *W, const float *gamma, void *W_out, int64_t ld_out)
+{
+    if (!W || !gamma || !W_out) return CODA_ERR_NULL;
+    if (W->dtype != CODA_BF16) return CODA_ERR_DTYPE;
+    if (W->trans || W->rows < 0 || W->cols < 0 || W->ld < W->cols || ld_out < W->cols || (W->cols & 7))
+        return CODA_ERR_SHAPE;
+    if (W->rows == 0 || W->cols == 0) return CODA_OK;
+    if (!W->ptr) return CODA_ERR_NULL;
+    if (!aligned16(W->ptr) || !aligned16(W_out) || (W->ld & 7) || (ld_out & 7) || !aligned4(gamma)) return CODA_ERR_ALIGN;
+    return launch_status(coda::launch_fold_gamma(static_cast<hipStream_t>(stream), static_cast<const uint16_t *>(W->ptr),
+                                                 W->rows, W->cols, W->ld, gamma, static_cast<uint16_t *>(W_out), ld_out));
+}
+
+coda_status coda_interleave_pairs(void *stream, const coda_mat *Wa, const coda_mat *Wb, void *W_out, int64_t ld_out)
+{
+    if (!Wa || !Wb || !W_out) return CODA_ERR_NULL;
+    if (Wa->dtype != CODA_BF16 || Wb->dtype != CODA_BF16) return CODA_ERR_DTYPE;
+    if (Wa->trans || Wb->trans || Wa->rows != Wb->rows || Wa->cols != Wb->cols || Wa->rows < 0 || Wa->cols < 0 ||
+        Wa->ld < Wa->cols || Wb->ld < Wb->cols || ld_out < 2 * Wa->cols || (Wa->cols & 7))
+        return CODA_ERR_SHAPE;
+    if (Wa->rows == 0 || Wa->cols == 0) return CODA_OK;
+    if (!Wa->ptr || !Wb->ptr) return CODA_ERR_NULL;
+    if (!aligned16(Wa->ptr) || !aligned16(Wb->ptr) || !aligned16(W_out) || (Wa->ld & 7) || (Wb->ld & 7) || (ld_out & 7))
+        return CODA_ERR_ALIGN;
+    return launch_status(coda::launch_interleave_pairs(
+        static_cast<hipStream_t>(stream), static_cast<const uint16_t *>(Wa->ptr), Wa->ld,
+        static_cast<const uint16_t *>(Wb->ptr), Wb->ld, Wa->rows, Wa->cols, static_cast<uint16_t *>(W_out), ld_out));
+}
+
+const char *coda_status_string(coda_status s)
+{
+    switch (s) {
+    case CODA_OK: return "ok";
+    case CODA_ERR_NULL: return "required pointer is null";
+    case CODA_ERR_SHAPE: return "unsupported or inconsistent shape";
+    case CODA_ERR_ALIGN: return "pointer or leading dimension misaligned";
+    case CODA_ERR_DTYPE: return "unsupported dtype";
+    case CODA_ERR_PROGRAM: return "unsupported epilogue program";
+    case CODA_ERR_WORKSPACE: return "workspace too small";
+    case CODA_ERR_LAUNCH: return "HIP launch error";
+    }
+    return "unknown status";
+}
+
+int coda_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,6 @@
+// GEMM+epilogue kernel instantiations for one operand-layout pair:
+// A stored [M x K] (K-contiguous), B stored [N x K] (K-contiguous).
+#include "gemm_launch.hpp"
+namespace coda {
+CODA_INSTANTIATE_LAYOUT(true, true)
+}

@@ -1,0 +1,302 @@
+"""GPU parity: every entry point of libcoda.so, called through the C ABI, against the CPU
+oracle on the same seeded inputs, element by element.  Sizes span several 256x256x64 tiles
+plus ragged tails in every dimension; outputs sit in sentinel-guarded buffers."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_19269_amd import synth
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+coda = None
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    global coda
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2605_19269_amd import coda as _c
+    coda = _c
+    yield
+    torch.cuda.synchronize()
+
+
+def rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def operands(g, M, N, K, transA, transB, a_std=1.0, b_std=0.5):
+    """Random bf16 operands as stored for the requested layout; returns (A_bits, B_bits)."""
+    A = synth.normal_bf16(g, (K, M) if transA else (M, K), a_std)
+    B = synth.normal_bf16(g, (N, K) if transB else (K, N), b_std)
+    return A, B
+
+
+SHAPES = [(256, 256, 64), (512, 768, 192), (520, 776, 200), (8, 8, 8), (264, 40, 72)]
+LAYOUTS = [(False, False), (False, True), (True, False), (True, True)]
+
+
+@pytest.mark.parametrize("transA,transB", LAYOUTS)
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_plain_gemm_store_bf16(oracle, M, N, K, transA, transB):
+    g = rng(100 + M + N + K)
+    A, B = operands(g, M, N, K, transA, transB)
+    out = G.Guarded(M, N, torch.bfloat16)
+    dA, dB = G.dev_bf16(A), G.dev_bf16(B)
+    coda.coda_gemm(dA, dB, [coda.store(out.t)], transA=transA, transB=transB)
+    torch.cuda.synchronize()
+    ref = oracle.gemm_rowscale(A, B, transA=transA, transB=transB)
+    out.check_guards(); out.written()
+    G.assert_bf16_close(G.host_f64(out.t), ref, "plain gemm")
+
+
+@pytest.mark.parametrize("transA,transB", [(False, False), (True, False)])
+def test_plain_gemm_store_f32(oracle, transA, transB):
+    M, N, K = 520, 264, 136
+    g = rng(7)
+    A, B = operands(g, M, N, K, transA, transB)
+    out = G.Guarded(M, N, torch.float32, pad_cols=4)
+    coda.coda_gemm(G.dev_bf16(A), G.dev_bf16(B), [coda.store(out.t, f32=True)], transA=transA, transB=transB)
+    torch.cuda.synchronize()
+    ref = oracle.gemm_rowscale(A, B, transA=transA, transB=transB)
+    out.check_guards(); out.written()
+    G.assert_f32_signed_close(G.host_f64(out.t), ref, "f32 store")
+
+
+@pytest.mark.parametrize("M,N,K", [(512, 512, 128), (520, 776, 200)])
+@pytest.mark.parametrize("transB", [False, True])
+def test_kernel5_row_scale(oracle, M, N, K, transB):
+    g = rng(11)
+    A, B = operands(g, M, N, K, False, transB)
+    r = synth.uniform_f32(g, (M,), 0.25, 2.0)
+    out = G.Guarded(M, N, torch.bfloat16)
+    coda.coda_gemm(G.dev_bf16(A), G.dev_bf16(B), [coda.row_scale(G.dev_f32(r)), coda.store(out.t)], transB=transB)
+    torch.cuda.synchronize()
+    ref = oracle.gemm_rowscale(A, B, r=r.astype(np.float64), transB=transB)
+    out.check_guards(); out.written()
+    G.assert_bf16_close(G.host_f64(out.t), ref, "row scale")
+
+
+@pytest.mark.parametrize("M,N,K", [(512, 512, 128), (520, 776, 200)])
+@pytest.mark.parametrize("with_r,with_preact", [(True, False), (False, True), (True, True)])
+def test_kernel6_swiglu_forward(oracle, M, N, K, with_r, with_preact):
+    g = rng(12)
+    A, B = operands(g, M, N, K, False, False, b_std=0.2)
+    r = synth.uniform_f32(g, (M,), 0.5, 1.5) if with_r else None
+    H = G.Guarded(M, N // 2, torch.bfloat16)
+    Z = G.Guarded(M, N, torch.bfloat16) if with_preact else None
+    ops = ([coda.row_scale(dr := G.dev_f32(r))] if with_r else []) + \
+          [coda.swiglu_fwd(Z.t if Z else None), coda.store(H.t)]
+    coda.coda_gemm(G.dev_bf16(A), G.dev_bf16(B), ops)
+    torch.cuda.synchronize()
+    refH, refZ = oracle.gemm_rowscale_swiglu(A, B, r=None if r is None else r.astype(np.float64), want_preact=True)
+    H.check_guards(); H.written()
+    G.assert_bf16_close(G.host_f64(H.t), refH, "swiglu fwd")
+    if Z:
+        Z.check_guards(); Z.written()
+        G.assert_bf16_close(G.host_f64(Z.t), refZ, "pre-activation side output")
+
+
+@pytest.mark.parametrize("M,N,K", [(512, 512, 128), (520, 776, 200)])
+@pytest.mark.parametrize("atomic", [False, True])
+@pytest.mark.parametrize("transB", [False, True])
+def test_kernel4_residual_sumsq_gamma(oracle, M, N, K, atomic, transB):
+    g = rng(13)
+    A, B = operands(g, M, N, K, False, transB, b_std=0.1)
+    C = synth.normal_bf16(g, (M, N), 1.0)
+    gamma = synth.uniform_f32(g, (N,), 0.5, 1.5)
+    r = synth.uniform_f32(g, (M,), 0.5, 1.5)
+    Y = G.Guarded(M, N, torch.bfloat16)
+    O = G.Guarded(M, N, torch.bfloat16)
+    nblk = coda.coda_row_partial_blocks(N)
+    red = torch.zeros(M, dtype=torch.float32, device="cuda") if atomic else \
+        torch.full((nblk, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    dr, dC, dg = G.dev_f32(r), G.dev_bf16(C), G.dev_f32(gamma)
+    ops = [coda.row_scale(dr), coda.add_tile(dC), coda.row_sumsq(red, atomic=atomic),
+           coda.col_scale_side(dg, O.t), coda.store(Y.t)]
+    coda.coda_gemm(G.dev_bf16(A), G.dev_bf16(B), ops, transB=transB)
+    if atomic:
+        ss = red
+    else:
+        ss = torch.empty(M, dtype=torch.float32, device="cuda")
+        coda.coda_row_finalize(red, M, nblk, sum_out=ss, d=N, eps=0.0)
+    torch.cuda.synchronize()
+    refD, refss, refO = oracle.gemm_residual_sumsq(A, B, r=r.astype(np.float64), C=C, gamma=gamma.astype(np.float64),
+                                                   transB=transB, want_scaled=True)
+    Y.check_guards(); Y.written(); O.check_guards(); O.written()
+    G.assert_bf16_close(G.host_f64(Y.t), refD, "residual output")
+    G.assert_bf16_close(G.host_f64(O.t), refO, "gamma-scaled side output")
+    G.assert_sumsq_close(G.host_f64(ss), refss, "row sum of squares")
+
+
+@pytest.mark.parametrize("M,N,K", [(512, 256, 128), (520, 264, 200)])
+@pytest.mark.parametrize("extras", [False, True])
+def test_kernel10_swiglu_backward(oracle, M, N, K, extras):
+    g = rng(14)
+    A = synth.normal_bf16(g, (M, K), 1e-2)
+    Bt = synth.normal_bf16(g, (N, K), 0.02)          # W_down stored [F x d], used transposed
+    Z = synth.normal_bf16(g, (M, 2 * N), 1.0)
+    dZ = G.Guarded(M, 2 * N, torch.bfloat16)
+    O = G.Guarded(M, N, torch.bfloat16) if extras else None
+    nblk = coda.coda_row_partial_blocks(N)
+    part = torch.full((nblk, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda") if extras else None
+    dZin = G.dev_bf16(Z)
+    ops = [coda.swiglu_bwd(dZin, act_out=O.t if O else None, stat_out=part), coda.store(dZ.t)]
+    coda.coda_gemm(G.dev_bf16(A), G.dev_bf16(Bt), ops, transB=True)
+    torch.cuda.synchronize()
+    refdZ, refO, refstat = oracle.gemm_swiglu_bwd(A, Bt, Z, transB=True)
+    dZ.check_guards(); dZ.written()
+    G.assert_bf16_close(G.host_f64(dZ.t), refdZ, "dZ")
+    if extras:
+        O.check_guards(); O.written()
+        G.assert_bf16_close(G.host_f64(O.t), refO, "recomputed activation")
+        stat = torch.empty(M, dtype=torch.float32, device="cuda")
+        coda.coda_row_finalize(part, M, nblk, sum_out=stat, d=1, eps=0.0)
+        torch.cuda.synchronize()
+        G.assert_f32_signed_close(G.host_f64(stat), refstat, "row statistic")
+
+
+@pytest.mark.parametrize("M,N,K", [(512, 256, 256), (264, 520, 200)])
+def test_weight_gradient_accumulate(oracle, M, N, K):
+    g = rng(15)
+    H = synth.normal_bf16(g, (K, M), 1.0)             # activations [tokens x in], used transposed
+    dY = synth.normal_bf16(g, (K, N), 1e-2)
+    Gin = synth.normal_f32(g, (M, N), 1e-3)
+    buf = G.Guarded(M, N, torch.float32, pad_cols=4)
+    buf.t.copy_(torch.from_numpy(Gin))
+    buf.ref = buf.full.clone()
+    coda.coda_gemm(G.dev_bf16(H), G.dev_bf16(dY), [coda.accum_f32(buf.t)], transA=True)
+    torch.cuda.synchronize()
+    ref = oracle.gemm_accumulate(H, dY, Gin, transA=True)
+    buf.check_guards()
+    G.assert_f32_signed_close(G.host_f64(buf.t), ref, "accumulated weight gradient")
+    # second accumulation on top of the first (in-place semantics)
+    coda.coda_gemm(G.dev_bf16(H), G.dev_bf16(dY), [coda.accum_f32(buf.t)], transA=True)
+    torch.cuda.synchronize()
+    ref2 = ref + oracle.gemm_accumulate(H, dY, None, transA=True)
+    G.assert_f32_signed_close(G.host_f64(buf.t), ref2, "second accumulation")
+
+
+def test_tiny_rmsnorm_gemm_configuration(oracle):
+    """The tiny configuration end to end on the GPU: row_sumsq -> finalize(rstd) ; fold_gamma ;
+    GEMM with [row scale, residual add, sum of squares, store]; against the canonical
+    RMSNorm -> GEMM -> residual chain of the oracle."""
+    c = synth.tiny_rmsnorm_gemm(seed=0)
+    M, K = c["X"].shape
+    N = c["W"].shape[1]
+    X, W, R, gamma = G.dev_bf16(c["X"]), G.dev_bf16(c["W"]), G.dev_bf16(c["R"]), G.dev_f32(c["gamma"])
+    ssx = torch.empty(M, dtype=torch.float32, device="cuda")
+    rstd = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_row_sumsq(X, ssx)
+    coda.coda_row_finalize(ssx.view(1, M), M, 1, rstd_out=rstd, d=K, eps=c["eps"])
+    Wp = torch.empty_like(W)
+    coda.coda_fold_gamma(W, gamma, Wp)
+    Y = G.Guarded(M, N, torch.bfloat16)
+    nblk = coda.coda_row_partial_blocks(N)
+    part = torch.empty((nblk, M), dtype=torch.float32, device="cuda")
+    ss = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_gemm(X, Wp, [coda.row_scale(rstd), coda.add_tile(R), coda.row_sumsq(part), coda.store(Y.t)])
+    coda.coda_row_finalize(part, M, nblk, sum_out=ss, d=N, eps=0.0)
+    torch.cuda.synchronize()
+    refY, refss = oracle.rmsnorm_linear_unfused(c["X"], c["gamma"].astype(np.float64), c["eps"], c["W"], c["R"])
+    Y.check_guards(); Y.written()
+    G.assert_sumsq_close(G.host_f64(rstd), oracle.rstd(c["X"], c["eps"]), "rstd")
+    G.assert_bf16_close(G.host_f64(Y.t), refY, "Y")
+    G.assert_sumsq_close(G.host_f64(ss), refss, "sum of squares of Y")
+
+
+def test_mlp_block_chain(oracle):
+    """RMSNorm -> up-projection+SwiGLU -> down-projection+residual+sum of squares, three fused
+    launches plus the auxiliary reductions, against the unfused fp64 operator chain."""
+    g = rng(21)
+    M, d, F = 384, 256, 512
+    Xb = synth.normal_bf16(g, (M, d), 1.0)
+    gamma = synth.uniform_f32(g, (d,), 0.5, 1.5)
+    W1 = synth.normal_bf16(g, (d, 2 * F), 0.08)
+    W2 = synth.normal_bf16(g, (F, d), 0.08)
+    X, dW1, dW2, dg = G.dev_bf16(Xb), G.dev_bf16(W1), G.dev_bf16(W2), G.dev_f32(gamma)
+    ssx = torch.empty(M, dtype=torch.float32, device="cuda")
+    rstd = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_row_sumsq(X, ssx)
+    coda.coda_row_finalize(ssx.view(1, M), M, 1, rstd_out=rstd, d=d, eps=1e-6)
+    W1p = torch.empty_like(dW1)
+    coda.coda_fold_gamma(dW1, dg, W1p)
+    H = torch.empty((M, F), dtype=torch.bfloat16, device="cuda")
+    coda.coda_gemm(X, W1p, [coda.row_scale(rstd), coda.swiglu_fwd(), coda.store(H)])
+    Y = torch.empty((M, d), dtype=torch.bfloat16, device="cuda")
+    nblk = coda.coda_row_partial_blocks(d)
+    part = torch.empty((nblk, M), dtype=torch.float32, device="cuda")
+    ss = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_gemm(H, dW2, [coda.add_tile(X), coda.row_sumsq(part), coda.store(Y)])
+    coda.coda_row_finalize(part, M, nblk, sum_out=ss, d=d, eps=0.0)
+    torch.cuda.synchronize()
+    refY, refss = oracle.mlp_block(Xb, gamma.astype(np.float64), 1e-6, W1, W2, R=Xb, reparam=False)
+    # two bf16 intermediates (folded weight, H) lie between the input and Y: chain tolerance
+    G.assert_chain_close(G.host_f64(Y), refY, "block output")
+    G.assert_sumsq_close(G.host_f64(ss), refss, "block sum of squares")
+
+
+def test_aux_kernels(oracle):
+    g = rng(31)
+    M, K = 37, 264
+    Xb = synth.normal_bf16(g, (M, K + 8), 1.0)[:, :K]    # pitch > width
+    X = G.dev_bf16(np.ascontiguousarray(synth.normal_bf16(g, (M, K + 8), 1.0)))
+    Xv = X[:, :K]
+    ss = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_row_sumsq(Xv, ss)
+    torch.cuda.synchronize()
+    G.assert_sumsq_close(G.host_f64(ss), oracle.row_sumsq(np.ascontiguousarray(G.host_bits(Xv))), "row_sumsq")
+    # finalize over several blocks
+    nblk = 5
+    part = synth.uniform_f32(g, (nblk, M), 0.0, 4.0)
+    s_out = torch.empty(M, dtype=torch.float32, device="cuda")
+    r_out = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_row_finalize(G.dev_f32(part), M, nblk, sum_out=s_out, rstd_out=r_out, d=K, eps=1e-6)
+    torch.cuda.synchronize()
+    tot = part.astype(np.float64).sum(0)
+    G.assert_sumsq_close(G.host_f64(s_out), tot, "finalize sum")
+    G.assert_sumsq_close(G.host_f64(r_out), oracle.rstd_from_sumsq(tot, K, 1e-6), "finalize rstd")
+    # weight preparation
+    Wa, Wb = synth.normal_bf16(g, (24, 40), 1.0), synth.normal_bf16(g, (24, 40), 1.0)
+    out = G.Guarded(24, 80, torch.bfloat16)
+    coda.coda_interleave_pairs(G.dev_bf16(Wa), G.dev_bf16(Wb), out.t)
+    torch.cuda.synchronize()
+    out.check_guards()
+    assert np.array_equal(G.host_bits(out.t), oracle.interleave_pairs(Wa, Wb))       # bit-exact
+    gamma = synth.uniform_f32(g, (24,), 0.5, 1.5)
+    fo = G.Guarded(24, 40, torch.bfloat16)
+    coda.coda_fold_gamma(G.dev_bf16(Wa), G.dev_f32(gamma), fo.t)
+    torch.cuda.synchronize()
+    fo.check_guards()
+    want = synth.f32_to_bf16_bits(oracle.fold_gamma(Wa, gamma.astype(np.float64)).astype(np.float32))
+    # product of a bf16 and an fp32 value is exact in fp64 and needs <= 32 significant bits, so
+    # rounding it through fp32 first can differ from direct rounding only at double-rounding ties
+    got = G.host_bits(fo.t)
+    assert (got != want).mean() < 1e-3
+    G.assert_bf16_close(G.bits_to_f64(got), oracle.fold_gamma(Wa, gamma.astype(np.float64)), "fold_gamma")
+    del Xb
+
+
+def test_degenerate_sizes(oracle):
+    g = rng(41)
+    # K == 0: the program runs on D = 0  ->  Y = R, ss = rowsum(R^2)
+    M, N = 264, 264
+    A = torch.empty((M, 0), dtype=torch.bfloat16, device="cuda")
+    B = torch.empty((0, N), dtype=torch.bfloat16, device="cuda")
+    Rb = synth.normal_bf16(g, (M, N), 1.0)
+    Y = G.Guarded(M, N, torch.bfloat16)
+    ss = torch.zeros(M, dtype=torch.float32, device="cuda")
+    st = coda.coda_gemm_raw(0, M, N, 0, coda.coda_mat(A.data_ptr(), M, 0, 8, 0, 0), coda.coda_mat(B.data_ptr(), 0, N, N, 0, 0),
+                            [coda.add_tile(dR := G.dev_bf16(Rb)), coda.row_sumsq(ss, atomic=True), coda.store(Y.t)])
+    assert st == coda.CODA_OK
+    torch.cuda.synchronize()
+    Y.check_guards(); Y.written()
+    assert np.array_equal(G.host_bits(Y.t), Rb)
+    G.assert_sumsq_close(G.host_f64(ss), (G.bits_to_f64(Rb) ** 2).sum(1), "K=0 sumsq")
+    # M == 0 and N == 0 are no-ops that still validate
+    out = torch.empty((8, 8), dtype=torch.bfloat16, device="cuda")
+    a0 = coda.coda_mat(out.data_ptr(), 0, 8, 8, 0, 0)
+    b0 = coda.coda_mat(out.data_ptr(), 8, 8, 8, 0, 0)
+    assert coda.coda_gemm_raw(0, 0, 8, 8, a0, b0, [coda.store(out)]) == coda.CODA_OK
