@@ -29,6 +29,8 @@ CODA_REDUCE_PARTIALS, CODA_REDUCE_ATOMIC, CODA_STORE_F32 = 0, 1, 2
 EXPORTS = ["coda_gemm", "coda_gemm_workspace_bytes", "coda_row_partial_blocks", "coda_row_finalize",
            "coda_row_sumsq", "coda_fold_gamma", "coda_interleave_pairs", "coda_status_string",
            "coda_last_hip_error"]
+EXPORTS_UNFUSED = ["coda_unfused_rmsnorm_apply", "coda_unfused_swiglu_fwd", "coda_unfused_swiglu_bwd",
+                   "coda_unfused_add_sumsq", "coda_unfused_accumulate"]
 
 
 class coda_mat(ctypes.Structure):
@@ -62,6 +64,16 @@ _lib.coda_status_string.restype = ctypes.c_char_p
 _lib.coda_status_string.argtypes = [ctypes.c_int]
 _lib.coda_last_hip_error.restype = ctypes.c_int
 _lib.coda_last_hip_error.argtypes = []
+_lib.coda_unfused_rmsnorm_apply.restype = ctypes.c_int
+_lib.coda_unfused_rmsnorm_apply.argtypes = [_vp, _vp, _i64, _vp, _vp, _i64, _i64, _vp, _i64]
+_lib.coda_unfused_swiglu_fwd.restype = ctypes.c_int
+_lib.coda_unfused_swiglu_fwd.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _i64]
+_lib.coda_unfused_swiglu_bwd.restype = ctypes.c_int
+_lib.coda_unfused_swiglu_bwd.argtypes = [_vp, _vp, _i64, _vp, _i64, _i64, _i64, _vp, _i64]
+_lib.coda_unfused_add_sumsq.restype = ctypes.c_int
+_lib.coda_unfused_add_sumsq.argtypes = [_vp, _vp, _i64, _vp, _i64, _i64, _i64, _vp, _i64, _vp]
+_lib.coda_unfused_accumulate.restype = ctypes.c_int
+_lib.coda_unfused_accumulate.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _i64]
 
 
 class CodaError(RuntimeError):
@@ -195,3 +207,29 @@ def coda_status_string(status):
 
 def coda_last_hip_error():
     return _lib.coda_last_hip_error()
+
+
+# --- unfused baseline kernels (include/coda_unfused.h) -----------------------------------------
+def coda_unfused_rmsnorm_apply(X, r, gamma, Xn, stream=None):
+    _check(_lib.coda_unfused_rmsnorm_apply(_stream(stream), _ptr(X), X.stride(0), _ptr(r), _ptr(gamma),
+                                           X.shape[0], X.shape[1], _ptr(Xn), Xn.stride(0)))
+
+
+def coda_unfused_swiglu_fwd(Z, H, stream=None):
+    _check(_lib.coda_unfused_swiglu_fwd(_stream(stream), _ptr(Z), Z.stride(0), H.shape[0], H.shape[1],
+                                        _ptr(H), H.stride(0)))
+
+
+def coda_unfused_swiglu_bwd(dH, Z, dZ, stream=None):
+    _check(_lib.coda_unfused_swiglu_bwd(_stream(stream), _ptr(dH), dH.stride(0), _ptr(Z), Z.stride(0),
+                                        dH.shape[0], dH.shape[1], _ptr(dZ), dZ.stride(0)))
+
+
+def coda_unfused_add_sumsq(D, R, Y, ss=None, stream=None):
+    _check(_lib.coda_unfused_add_sumsq(_stream(stream), _ptr(D), D.stride(0), _ptr(R), R.stride(0),
+                                       D.shape[0], D.shape[1], _ptr(Y), Y.stride(0), _ptr(ss)))
+
+
+def coda_unfused_accumulate(T, G, stream=None):
+    _check(_lib.coda_unfused_accumulate(_stream(stream), _ptr(T), T.stride(0), T.shape[0], T.shape[1],
+                                        _ptr(G), G.stride(0)))

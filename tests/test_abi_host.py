@@ -1,0 +1,122 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+headers declare, and turns bad arguments into status codes before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def coda():
+    from paper_2605_19269_amd import coda as c
+    return c
+
+
+def declared_symbols(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(coda_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(coda):
+    lib = ctypes.CDLL(coda.LIB_PATH)
+    names = declared_symbols("coda.h") + declared_symbols("coda_unfused.h")
+    assert "coda_gemm" in names and "coda_unfused_swiglu_bwd" in names
+    for n in names:
+        assert hasattr(lib, n), "libcoda.so does not export %s" % n
+    assert set(coda.EXPORTS) == set(declared_symbols("coda.h"))
+    assert set(coda.EXPORTS_UNFUSED) == set(declared_symbols("coda_unfused.h"))
+
+
+def test_binding_mirrors_header_enums(coda):
+    text = open(os.path.join(ROOT, "include", "coda.h")).read()
+    for name in ["CODA_OK", "CODA_ERR_NULL", "CODA_ERR_SHAPE", "CODA_ERR_ALIGN", "CODA_ERR_DTYPE", "CODA_ERR_PROGRAM",
+                 "CODA_ERR_WORKSPACE", "CODA_ERR_LAUNCH", "CODA_EPI_ROW_SCALE", "CODA_EPI_COL_SCALE_SIDE",
+                 "CODA_EPI_ADD_TILE", "CODA_EPI_SWIGLU_FWD", "CODA_EPI_SWIGLU_BWD", "CODA_EPI_ROW_SUMSQ",
+                 "CODA_EPI_STORE", "CODA_EPI_ACCUM_F32"]:
+        m = re.search(r"\b%s\s*=\s*(\d+)" % name, text)
+        assert m and int(m.group(1)) == getattr(coda, name), name
+    assert ctypes.sizeof(coda.coda_mat) == 40 and ctypes.sizeof(coda.coda_epi_op) == 48
+
+
+def _mat(coda, ptr, rows, cols, ld=None, trans=0, dtype=0):
+    return coda.coda_mat(ptr, rows, cols, ld if ld is not None else cols, trans, dtype)
+
+
+def _op(coda, kind, flags=0, in_=None, out=None, out2=None, ld_in=0, ld_out=0):
+    return coda.coda_epi_op(kind, flags, in_, out, out2, ld_in, ld_out)
+
+
+P = 0x1000  # a fake, 16-byte aligned "device pointer"; no call below ever reaches a launch
+
+
+def test_argument_errors_are_status_codes(coda):
+    A, B = _mat(coda, P, 64, 32), _mat(coda, P, 32, 64)
+    store = _op(coda, coda.CODA_EPI_STORE, out=P, ld_out=64)
+    g = lambda M, N, K, a, b, ops: coda.coda_gemm_raw(None, M, N, K, a, b, ops)
+    assert g(64, 64, 32, None, B, [store]) == coda.CODA_ERR_NULL
+    assert g(64, 64, 32, A, B, []) == coda.CODA_ERR_PROGRAM                       # no final op
+    assert g(64, 64, 40, A, B, [store]) == coda.CODA_ERR_SHAPE                    # K mismatch
+    assert g(-1, 64, 32, A, B, [store]) == coda.CODA_ERR_SHAPE
+    assert g(64, 64, 32, _mat(coda, P + 2, 64, 32), B, [store]) == coda.CODA_ERR_ALIGN
+    assert g(64, 64, 32, _mat(coda, P, 64, 32, ld=36), B, [store]) == coda.CODA_ERR_ALIGN
+    assert g(64, 64, 32, _mat(coda, P, 64, 32, ld=24), B, [store]) == coda.CODA_ERR_SHAPE
+    assert g(64, 64, 32, _mat(coda, P, 64, 32, dtype=1), B, [store]) == coda.CODA_ERR_DTYPE
+    assert g(64, 60, 32, A, _mat(coda, P, 32, 60, ld=64), [store]) == coda.CODA_ERR_SHAPE   # N % 8
+    assert g(64, 64, 32, A, B, [_op(coda, coda.CODA_EPI_STORE, out=None, ld_out=64)]) == coda.CODA_ERR_NULL
+    assert g(64, 64, 32, A, B, [_op(coda, coda.CODA_EPI_STORE, out=P, ld_out=32)]) == coda.CODA_ERR_SHAPE
+    # transposed operands are described as stored ([K x M]); M == 0 so nothing is launched
+    assert g(0, 64, 32, _mat(coda, P, 32, 0, ld=8, trans=1), B, [store]) == coda.CODA_OK
+    assert g(0, 64, 32, _mat(coda, P, 0, 32, ld=32, trans=1), B, [store]) == coda.CODA_ERR_SHAPE
+
+
+def test_program_grammar(coda):
+    A, B = _mat(coda, P, 0, 32), _mat(coda, P, 32, 64)      # M == 0: validates, launches nothing
+    g = lambda ops: coda.coda_gemm_raw(None, 0, 64, 32, A, B, ops)
+    rs = _op(coda, coda.CODA_EPI_ROW_SCALE, in_=P)
+    add = _op(coda, coda.CODA_EPI_ADD_TILE, in_=P, ld_in=64)
+    ssq = _op(coda, coda.CODA_EPI_ROW_SUMSQ, out=P)
+    side = _op(coda, coda.CODA_EPI_COL_SCALE_SIDE, in_=P, out=P, ld_out=64)
+    st = _op(coda, coda.CODA_EPI_STORE, out=P, ld_out=64)
+    st_half = _op(coda, coda.CODA_EPI_STORE, out=P, ld_out=32)
+    st_dbl = _op(coda, coda.CODA_EPI_STORE, out=P, ld_out=128)
+    fwd = _op(coda, coda.CODA_EPI_SWIGLU_FWD)
+    bwd = _op(coda, coda.CODA_EPI_SWIGLU_BWD, in_=P, ld_in=128)
+    acc = _op(coda, coda.CODA_EPI_ACCUM_F32, out=P, ld_out=64)
+    OK, BAD = coda.CODA_OK, coda.CODA_ERR_PROGRAM
+    assert g([st]) == OK
+    assert g([rs, st]) == OK
+    assert g([rs, add, ssq, side, st]) == OK
+    assert g([add, ssq, st]) == OK
+    assert g([rs, fwd, st_half]) == OK
+    assert g([fwd, st_half]) == OK
+    assert g([bwd, st_dbl]) == OK
+    assert g([acc]) == OK
+    assert g([add, rs, st]) == BAD            # row scale after the residual add: not the supported order
+    assert g([ssq, add, st]) == BAD
+    assert g([st, rs]) == BAD                 # nothing may follow the final op
+    assert g([rs, rs, st]) == BAD
+    assert g([add, fwd, st_half]) == BAD
+    assert g([rs, bwd, st_dbl]) == BAD
+    assert g([rs, acc]) == BAD
+    assert g([fwd]) == BAD                    # pairwise op without a store
+    assert g([_op(coda, 99), st]) == BAD
+    assert g([fwd, _op(coda, coda.CODA_EPI_STORE, flags=coda.CODA_STORE_F32, out=P, ld_out=32)]) == BAD
+    assert g([bwd, st]) == coda.CODA_ERR_SHAPE     # store narrower than the widened output
+    assert g([_op(coda, coda.CODA_EPI_ROW_SUMSQ, flags=7, out=P), st]) == BAD
+
+
+def test_aux_argument_errors(coda):
+    import ctypes as C
+    lib = C.CDLL(coda.LIB_PATH)
+    lib.coda_row_finalize.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_float]
+    assert lib.coda_row_finalize(None, P, 8, 2, None, None, 8, 0.0) == coda.CODA_ERR_NULL
+    assert lib.coda_row_finalize(None, P, 8, 2, P, None, 0, 0.0) == coda.CODA_ERR_SHAPE
+    assert lib.coda_row_finalize(None, P, 0, 2, P, None, 8, 0.0) == coda.CODA_OK
+    assert coda.coda_row_partial_blocks(0) == 0 and coda.coda_row_partial_blocks(1) == 1
+    assert coda.coda_row_partial_blocks(2048) * 256 >= 2048
+    assert coda.coda_gemm_workspace_bytes(8, 8, 8, []) == 0
+    assert coda.coda_status_string(coda.CODA_ERR_PROGRAM) == "unsupported epilogue program"

@@ -235,7 +235,10 @@ def test_mlp_block_chain(oracle):
     refY, refss = oracle.mlp_block(Xb, gamma.astype(np.float64), 1e-6, W1, W2, R=Xb, reparam=False)
     # two bf16 intermediates (folded weight, H) lie between the input and Y: chain tolerance
     G.assert_chain_close(G.host_f64(Y), refY, "block output")
-    G.assert_sumsq_close(G.host_f64(ss), refss, "block sum of squares")
+    # the row statistic inherits the chain error of Y (about 0.3% rms per element, partly
+    # correlated along a row through rstd and the folded weight): 1e-2 relative
+    rel = np.abs(G.host_f64(ss) - refss) / refss
+    assert rel.max() <= 1e-2, "block sum of squares: max relative error %.3g" % rel.max()
 
 
 def test_aux_kernels(oracle):
@@ -300,3 +303,47 @@ def test_degenerate_sizes(oracle):
     a0 = coda.coda_mat(out.data_ptr(), 0, 8, 8, 0, 0)
     b0 = coda.coda_mat(out.data_ptr(), 8, 8, 8, 0, 0)
     assert coda.coda_gemm_raw(0, 0, 8, 8, a0, b0, [coda.store(out)]) == coda.CODA_OK
+
+
+def test_unfused_baseline_kernels(oracle):
+    """The stand-alone kernels of the unfused chain (measurement baseline) against the same
+    definitions of the oracle (GEMM replaced by an identity so the oracle's epilogue is isolated)."""
+    g = rng(51)
+    M, F = 70, 264
+    Zb = synth.normal_bf16(g, (M, 2 * F), 1.0)
+    dHb = synth.normal_bf16(g, (M, F), 1e-2)
+    eyeF = synth.f32_to_bf16_bits(np.eye(F, dtype=np.float32))
+    # forward: Z -> H   (oracle: Kernel 2 with A = Z, B = I)
+    H = G.Guarded(M, F, torch.bfloat16)
+    coda.coda_unfused_swiglu_fwd(G.dev_bf16(Zb), H.t)
+    eye2F = synth.f32_to_bf16_bits(np.eye(2 * F, dtype=np.float32))
+    refH = oracle.gemm_rowscale_swiglu(Zb, eye2F)
+    # backward: (dH, Z) -> dZ   (oracle: Kernel 10 with A = dH, B = I)
+    dZ = G.Guarded(M, 2 * F, torch.bfloat16)
+    coda.coda_unfused_swiglu_bwd(G.dev_bf16(dHb), G.dev_bf16(Zb), dZ.t)
+    refdZ, _, _ = oracle.gemm_swiglu_bwd(dHb, eyeF, Zb)
+    # residual add + sum of squares   (oracle: Kernel 4 with A = D, B = I)
+    Db, Rb = synth.normal_bf16(g, (M, F), 1.0), synth.normal_bf16(g, (M, F), 1.0)
+    Y = G.Guarded(M, F, torch.bfloat16)
+    ss = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_unfused_add_sumsq(G.dev_bf16(Db), G.dev_bf16(Rb), Y.t, ss)
+    refY, refss = oracle.gemm_residual_sumsq(Db, eyeF, C=Rb)
+    # RMSNorm apply: Xn = X * r * gamma   (oracle: Kernel 5 on X diag(gamma) is not bf16-exact, so
+    # compare against the exact product formed from the oracle's widened inputs)
+    r = synth.uniform_f32(g, (M,), 0.5, 1.5); gamma = synth.uniform_f32(g, (F,), 0.5, 1.5)
+    Xn = G.Guarded(M, F, torch.bfloat16)
+    coda.coda_unfused_rmsnorm_apply(G.dev_bf16(Db), G.dev_f32(r), G.dev_f32(gamma), Xn.t)
+    refXn = oracle.gemm_rowscale(Db, eyeF, r=r.astype(np.float64)) * gamma.astype(np.float64)[None, :]
+    # fp32 accumulate
+    T, G0 = synth.normal_f32(g, (M, F), 1.0), synth.normal_f32(g, (M, F), 1.0)
+    Gd = G.dev_f32(G0)
+    coda.coda_unfused_accumulate(G.dev_f32(T), Gd)
+    torch.cuda.synchronize()
+    for buf in (H, dZ, Y, Xn):
+        buf.check_guards(); buf.written()
+    G.assert_bf16_close(G.host_f64(H.t), refH, "unfused swiglu fwd")
+    G.assert_bf16_close(G.host_f64(dZ.t), refdZ, "unfused swiglu bwd")
+    G.assert_bf16_close(G.host_f64(Y.t), refY, "unfused add")
+    G.assert_sumsq_close(G.host_f64(ss), refss, "unfused sumsq")
+    G.assert_bf16_close(G.host_f64(Xn.t), refXn, "unfused rmsnorm apply")
+    assert np.array_equal(Gd.cpu().numpy(), G0 + T)          # one fp32 add: bit-exact
