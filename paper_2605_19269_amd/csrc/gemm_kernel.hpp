@@ -68,7 +68,9 @@ __device__ __forceinline__ uint32_t lds_kc(int r, int c)
     return (uint32_t)(r * (BK * 2) + (((c ^ (r >> 1)) & (BK / 8 - 1)) << 4));
 }
 // MN-contiguous tile [BK][ROWS]: 32-byte granule gr (16 elements) of k-row k.
-__device__ __forceinline__ int mn_swz(int k) { return (k & 3) | ((k >> 1) & 4); }
+// The transposing read serves 32 lanes per LDS cycle: four k-rows (k & 3) of two adjacent granules.
+// XOR-ing the granule with 2*(k & 3) sends those eight 32-byte pieces to eight different bank groups.
+__device__ __forceinline__ int mn_swz(int k) { return ((k & 3) << 1) | ((k >> 3) & 1); }
 template <int ROWS>
 __device__ __forceinline__ uint32_t lds_mn(int k, int gr)
 {
@@ -200,11 +202,393 @@ __device__ __forceinline__ bf16x8 frag_load(const unsigned char *tile, int row_b
     }
 }
 
+// ---------------------------------------------------------------------------------
+// Row staging through LDS (epilogue I/O).
+//
+// In the accumulator layout a lane owns a few bytes of 32 different rows, so direct
+// global accesses touch 32 rows per instruction with 8..32 bytes each.  Instead every
+// wave owns a private LDS region (a slice of the operand ring, free after the
+// mainloop) holding P rows of RB bytes of its tile: bf16 tiles are moved between
+// global memory and the region with row-contiguous 16-byte accesses (full cache
+// lines per row), and between the region and the accumulator layout with per-lane
+// units.  16-byte chunks are XOR-swizzled with the row index so that both access
+// patterns sweep all LDS banks.  Only lanes of one wave touch a region and a wave's
+// LDS operations execute in order, so no workgroup barrier is needed; wave_barrier()
+// only keeps the compiler from reordering the phases.
+// ---------------------------------------------------------------------------------
+// Swizzled region layout: row r occupies RB bytes; its 16-byte chunk c is stored at chunk position
+// c ^ f(r), f(r) = (r >> SH) mod NCH, with SH chosen so that 256 consecutive bytes' worth of rows see
+// different f.  All address arithmetic below is split into a per-lane part (computed once) and a
+// compile-time part (XOR-ed / added as immediates), so no per-access address has to stay in a register.
+template <int RB>
+struct Stage {
+    static constexpr int NCH = RB / 16;                             // 16-byte chunks per row
+    static constexpr int RPI = 64 / NCH;                            // rows covered by one wave-wide 16-byte access
+    static constexpr int SH = RB >= 256 ? 0 : (RB == 128 ? 1 : 2);
+    static_assert(RB == 64 || RB == 128 || RB == 256, "row sizes of the staged tiles");
+    static_assert(RPI >= (1 << SH), "row-group bits and lane-row bits of f() must not overlap");
+
+    // ---- row-contiguous phase: access `it` covers rows it*RPI .. it*RPI+RPI-1, lane -> (row lane/NCH, chunk lane%NCH)
+    __device__ static __forceinline__ uint32_t row_lane(int lane)
+    {
+        const int lr = lane / NCH, c = lane % NCH;
+        return (uint32_t)(lr * RB + ((c ^ ((lr >> SH) & (NCH - 1))) << 4));
+    }
+    __device__ static __forceinline__ uint32_t row_addr(uint32_t lane_part, int it)
+    {
+        return (uint32_t)(it * 1024) + (lane_part ^ (uint32_t)((((it * RPI) >> SH) & (NCH - 1)) << 4));
+    }
+    // ---- unit phase: lane -> row (lane & 31) of 32-row block fi, a unit of U bytes at byte column cb + (lane >> 5) * U
+    template <int U>
+    __device__ static __forceinline__ uint32_t unit_lane(int lane)
+    {
+        const int lrow = lane & 31, h = lane >> 5;
+        const int f = (lrow >> SH) & (NCH - 1);
+        return U == 16 ? (uint32_t)(lrow * RB + ((f ^ h) << 4)) : (uint32_t)(lrow * RB + (f << 4) + h * U);
+    }
+    // cb: compile-time byte column of the h = 0 unit (a multiple of 2U)
+    __device__ static __forceinline__ uint32_t unit_addr(uint32_t lane_part, int fi, int cb)
+    {
+        return (uint32_t)(fi * 32 * RB + (cb & 15)) + (lane_part ^ (uint32_t)((cb >> 4) << 4));
+    }
+};
+
+// P rows x RB bytes: global (row pitch `pitch` bytes) -> region.  rows_ok / bytes_ok bound the valid part.
+template <int RB, int P, bool EDGE>
+__device__ __forceinline__ void stage_load(unsigned char *reg, const unsigned char *g, int64_t pitch, int rows_ok,
+                                           int bytes_ok, int lane)
+{
+    using St = Stage<RB>;
+    constexpr int TOTAL = P / St::RPI, BATCH = TOTAL < 8 ? TOTAL : 8;
+    static_assert(P % St::RPI == 0 && TOTAL % BATCH == 0, "whole wave accesses");
+    const int lr = lane / St::NCH, lc = (lane % St::NCH) * 16;
+    const uint32_t goff = (uint32_t)(lr * (int)pitch + lc);        // 32-bit lane offset; rows advance via the scalar base
+    const uint32_t loff = St::row_lane(lane);
+#pragma unroll
+    for (int b = 0; b < TOTAL / BATCH; ++b) {
+        u32x4 t[BATCH];
+#pragma unroll
+        for (int q = 0; q < BATCH; ++q) {
+            const int it = b * BATCH + q;
+            const unsigned char *gi = g + (int64_t)(it * St::RPI) * pitch;
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            const bool ok = !EDGE || (it * St::RPI + lr < rows_ok && lc < bytes_ok);
+            t[q] = ok ? *reinterpret_cast<const u32x4 *>(gi + goff) : z;
+        }
+#pragma unroll
+        for (int q = 0; q < BATCH; ++q)
+            *reinterpret_cast<u32x4 *>(reg + St::row_addr(loff, b * BATCH + q)) = t[q];
+        __builtin_amdgcn_sched_barrier(0);   // keep at most one batch of loads live
+    }
+}
+
+// P rows x RB bytes: region -> global.
+template <int RB, int P, bool EDGE>
+__device__ __forceinline__ void stage_store(const unsigned char *reg, unsigned char *g, int64_t pitch, int rows_ok,
+                                            int bytes_ok, int lane)
+{
+    using St = Stage<RB>;
+    constexpr int TOTAL = P / St::RPI;
+    const int lr = lane / St::NCH, lc = (lane % St::NCH) * 16;
+    const uint32_t goff = (uint32_t)(lr * (int)pitch + lc);
+    const uint32_t loff = St::row_lane(lane);
+#pragma unroll
+    for (int it = 0; it < TOTAL; ++it) {
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(reg + St::row_addr(loff, it));
+        unsigned char *gi = g + (int64_t)(it * St::RPI) * pitch;
+        if (!EDGE) {
+            *reinterpret_cast<u32x4 *>(gi + goff) = v;
+        } else if (it * St::RPI + lr < rows_ok) {
+            // valid widths are multiples of 8 bytes (halved widths of the pairwise forward), so the last chunk may be half
+            if (lc + 16 <= bytes_ok) *reinterpret_cast<u32x4 *>(gi + goff) = v;
+            else if (lc < bytes_ok) *reinterpret_cast<u32x2 *>(gi + goff) = u32x2{v[0], v[1]};
+        }
+        if ((it & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Phase boundary inside a wave: no instruction may be moved across it.
+__device__ __forceinline__ void stage_fence()
+{
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+__device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+// ---------------------------------------------------------------------------------
+// Epilogue program on the accumulators of one workgroup tile.
+//   lane -> (row, column group):  m = mb + (lane & 31);  n = nb + 8*g + 4*(lane >> 5) + e
+// `ring` (RING bytes, 1 KiB aligned) must no longer be read by any wave as an operand
+// tile (callers synchronise); `red` is a separate [WGN][BM] float exchange buffer.
+// ---------------------------------------------------------------------------------
+template <class C, int EPI, bool EDGE, int RING>
+__device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const GemmParams &p, int m0, int n0, int tn,
+                                             unsigned char *ring, float *red, int tid)
+{
+    constexpr int BM = C::BM, FM = C::FM, FN = C::FN, WTM = C::WTM, WTN = C::WTN;
+    constexpr int REG = RING / (C::WGM * C::WGN);   // private staging bytes per wave
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % C::WGM, wn = wave / C::WGM;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int mw = m0 + wm * WTM, nw = n0 + wn * WTN;
+    unsigned char *reg = ring + wave * REG;
+    const int rows_ok = EDGE ? clampi(p.M - mw, 0, WTM) : WTM;   // valid rows / columns of this wave's tile
+    const int cols_ok = EDGE ? clampi(p.N - nw, 0, WTN) : WTN;
+    const bool want_red = (EPI == EPI_LINEAR || EPI == EPI_SWIGLU_BWD) && p.rowred_mode != ROWRED_NONE;
+    float rsum[FM];
+#pragma unroll
+    for (int i = 0; i < FM; ++i) rsum[i] = 0.0f;
+
+    if (EPI == EPI_LINEAR && !p.out_f32) {
+        // ---- row scale, residual add, row sum of squares, bf16 store: all tile I/O staged.  The gamma-scaled side
+        // output (when requested) is a second sweep that re-reads the residual and recomputes the value, so that
+        // nothing has to stay in registers between the two stores.
+        constexpr int RB = WTN * 2, P = (REG / RB) < WTM ? (REG / RB) : WTM, FPP = P / 32;
+        static_assert(P % 32 == 0 && WTM % P == 0, "staging pass");
+        const uint32_t ulane = Stage<RB>::template unit_lane<8>(lane);
+        const int sweeps = p.side ? 2 : 1;
+        for (int sw = 0; sw < sweeps; ++sw) {
+            uint16_t *dst = sw == 0 ? reinterpret_cast<uint16_t *>(p.out) : p.side;
+            const int64_t ldd = sw == 0 ? p.ld_out : p.ld_side;
+#pragma unroll
+            for (int ps = 0; ps < WTM / P; ++ps) {
+                const int r0 = ps * P;
+                if (p.add) {
+                    stage_load<RB, P, EDGE>(reg, reinterpret_cast<const unsigned char *>(p.add + (int64_t)(mw + r0) * p.ld_add + nw),
+                                            p.ld_add * 2, rows_ok - r0, cols_ok * 2, lane);
+                    stage_fence();
+                }
+#pragma unroll
+                for (int fi = 0; fi < FPP; ++fi) {
+                    const int i = ps * FPP + fi, m = mw + i * 32 + lrow;
+                    const bool mok = !EDGE || m < p.M;
+                    const float rs = p.row_scale ? (mok ? p.row_scale[m] : 0.0f) : 1.0f;
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            const int nl = j * 32 + g * 8 + lhalf * 4;
+                            const bool ok = mok && (!EDGE || nw + nl < p.N);
+                            f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                            v *= rs;
+                            u32x2 *slot = reinterpret_cast<u32x2 *>(reg + Stage<RB>::unit_addr(ulane, fi, (j * 32 + g * 8) * 2));
+                            if (p.add) {
+                                const u32x2 c = *slot;
+                                v[0] += bf16_lo(c[0]); v[1] += bf16_hi(c[0]);
+                                v[2] += bf16_lo(c[1]); v[3] += bf16_hi(c[1]);
+                            }
+                            if (sw == 0) {
+                                if (ok) rsum[i] += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+                            } else {
+                                f32x4 gm = {0.f, 0.f, 0.f, 0.f};
+                                if (ok) gm = *reinterpret_cast<const f32x4 *>(p.col_scale + nw + nl);
+                                v *= gm;
+                            }
+                            *slot = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+                            if (g == 3) {
+                                // pin the running row sum here: otherwise its whole add chain is sunk to the point of
+                                // use after the stores and every addend has to stay live (spilled) until then
+                                asm volatile("" : "+v"(rsum[i]));
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        }
+                }
+                stage_fence();
+                stage_store<RB, P, EDGE>(reg, reinterpret_cast<unsigned char *>(dst + (int64_t)(mw + r0) * ldd + nw), ldd * 2,
+                                         rows_ok - r0, cols_ok * 2, lane);
+                stage_fence();
+            }
+        }
+    } else if (EPI == EPI_SWIGLU_FWD) {
+        // ---- row scale, pairwise SwiGLU (width halves), optional pre-activation side output
+        constexpr int RBH = WTN, RBZ = WTN * 2;
+        constexpr int P = (REG / RBZ) < WTM ? (REG / RBZ) : WTM, FPP = P / 32;
+        static_assert(P % 32 == 0 && WTM % P == 0, "staging pass");
+        uint16_t *outp = reinterpret_cast<uint16_t *>(p.out);
+        const uint32_t ulane_h = Stage<RBH>::template unit_lane<4>(lane), ulane_z = Stage<RBZ>::template unit_lane<8>(lane);
+#pragma unroll
+        for (int ps = 0; ps < WTM / P; ++ps) {
+            const int r0 = ps * P;
+#pragma unroll
+            for (int fi = 0; fi < FPP; ++fi) {
+                const int i = ps * FPP + fi, m = mw + i * 32 + lrow;
+                const float rs = p.row_scale ? ((!EDGE || m < p.M) ? p.row_scale[m] : 0.0f) : 1.0f;
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const float v0 = acc[i][j][4 * g] * rs, v1 = acc[i][j][4 * g + 1] * rs;
+                        const float v2 = acc[i][j][4 * g + 2] * rs, v3 = acc[i][j][4 * g + 3] * rs;
+                        const float h0 = v0 * fast_sigmoid(v0) * v1, h1 = v2 * fast_sigmoid(v2) * v3;
+                        *reinterpret_cast<uint32_t *>(reg + Stage<RBH>::unit_addr(ulane_h, fi, j * 32 + g * 8)) = pack_bf16x2(h0, h1);
+                        if (g == 3) __builtin_amdgcn_sched_barrier(0);
+                    }
+            }
+            stage_fence();
+            stage_store<RBH, P, EDGE>(reg, reinterpret_cast<unsigned char *>(outp + (int64_t)(mw + r0) * p.ld_out + (nw >> 1)),
+                                      p.ld_out * 2, rows_ok - r0, cols_ok, lane);
+            if (p.out2) {
+                stage_fence();
+#pragma unroll
+                for (int fi = 0; fi < FPP; ++fi) {
+                    const int i = ps * FPP + fi, m = mw + i * 32 + lrow;
+                    const float rs = p.row_scale ? ((!EDGE || m < p.M) ? p.row_scale[m] : 0.0f) : 1.0f;
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            *reinterpret_cast<u32x2 *>(reg + Stage<RBZ>::unit_addr(ulane_z, fi, (j * 32 + g * 8) * 2)) =
+                                u32x2{pack_bf16x2(acc[i][j][4 * g] * rs, acc[i][j][4 * g + 1] * rs),
+                                      pack_bf16x2(acc[i][j][4 * g + 2] * rs, acc[i][j][4 * g + 3] * rs)};
+                        }
+                }
+                stage_fence();
+                stage_store<RBZ, P, EDGE>(reg, reinterpret_cast<unsigned char *>(p.out2 + (int64_t)(mw + r0) * p.ld_out2 + nw),
+                                          p.ld_out2 * 2, rows_ok - r0, cols_ok * 2, lane);
+            }
+            stage_fence();
+        }
+    } else if (EPI == EPI_SWIGLU_BWD) {
+        // ---- pairwise SwiGLU backward (width doubles): Z in and dZ out staged; row statistic; the optional
+        // recomputed activation silu(g)*u is a second sweep over 32-row blocks that re-reads Z.
+        constexpr int RB = WTN * 4, RBO = WTN * 2;
+        constexpr int P = (REG / RB) < WTM ? (REG / RB) : WTM, FPP = P / 32;
+        static_assert(P % 32 == 0 && WTM % P == 0 && 32 * (RB + RBO) <= REG, "staging pass");
+        uint16_t *outp = reinterpret_cast<uint16_t *>(p.out);
+        const uint32_t ulane = Stage<RB>::template unit_lane<16>(lane), ulane_o = Stage<RBO>::template unit_lane<8>(lane);
+#pragma unroll
+        for (int ps = 0; ps < WTM / P; ++ps) {
+            const int r0 = ps * P;
+            stage_load<RB, P, EDGE>(reg, reinterpret_cast<const unsigned char *>(p.Z + (int64_t)(mw + r0) * p.ldz + 2 * nw), p.ldz * 2,
+                                    rows_ok - r0, cols_ok * 4, lane);
+            stage_fence();
+#pragma unroll
+            for (int fi = 0; fi < FPP; ++fi) {
+                const int i = ps * FPP + fi, m = mw + i * 32 + lrow;
+                const bool mok = !EDGE || m < p.M;
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int nl = j * 32 + g * 8 + lhalf * 4;
+                        const bool ok = mok && (!EDGE || nw + nl < p.N);
+                        u32x4 *slot = reinterpret_cast<u32x4 *>(reg + Stage<RB>::unit_addr(ulane, fi, (j * 32 + g * 8) * 4));
+                        const u32x4 z = *slot;
+                        u32x4 dz;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float d = acc[i][j][4 * g + e];
+                            const float gg = bf16_lo(z[e]), uu = bf16_hi(z[e]);
+                            const float sg = fast_sigmoid(gg), sl = gg * sg;
+                            const float dU = d * sl, dG = d * uu * (sg + sl * (1.0f - sg));
+                            dz[e] = pack_bf16x2(dG, dU);
+                            if (ok) rsum[i] += gg * dG + uu * dU;
+                        }
+                        *slot = dz;
+                        asm volatile("" : "+v"(rsum[i]));   // keep the row statistic's add chain in place (see above)
+                        if (g & 1) __builtin_amdgcn_sched_barrier(0);
+                    }
+            }
+            stage_fence();
+            stage_store<RB, P, EDGE>(reg, reinterpret_cast<unsigned char *>(outp + (int64_t)(mw + r0) * p.ld_out + 2 * nw), p.ld_out * 2,
+                                     rows_ok - r0, cols_ok * 4, lane);
+            stage_fence();
+        }
+        if (p.out2) {
+            unsigned char *rego = reg + 32 * RB;   // activation rows live behind the 32 staged Z rows
+#pragma unroll
+            for (int i = 0; i < FM; ++i) {
+                const int r0 = i * 32;
+                stage_load<RB, 32, EDGE>(reg, reinterpret_cast<const unsigned char *>(p.Z + (int64_t)(mw + r0) * p.ldz + 2 * nw),
+                                         p.ldz * 2, rows_ok - r0, cols_ok * 4, lane);
+                stage_fence();
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const u32x4 z = *reinterpret_cast<const u32x4 *>(reg + Stage<RB>::unit_addr(ulane, 0, (j * 32 + g * 8) * 4));
+                        float o[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float gg = bf16_lo(z[e]);
+                            o[e] = gg * fast_sigmoid(gg) * bf16_hi(z[e]);
+                        }
+                        *reinterpret_cast<u32x2 *>(rego + Stage<RBO>::unit_addr(ulane_o, 0, (j * 32 + g * 8) * 2)) = u32x2{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+                    }
+                stage_fence();
+                stage_store<RBO, 32, EDGE>(rego, reinterpret_cast<unsigned char *>(p.out2 + (int64_t)(mw + r0) * p.ld_out2 + nw),
+                                           p.ld_out2 * 2, rows_ok - r0, cols_ok * 2, lane);
+                stage_fence();
+            }
+        }
+    } else {
+        // ---- fp32 outputs (f32 store of the linear program, in-place fp32 accumulate): 16 bytes per lane, direct
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int m = mw + i * 32 + lrow;
+            const bool mok = !EDGE || m < p.M;
+            float rs = 1.0f;
+            if (EPI == EPI_LINEAR && p.row_scale) rs = mok ? p.row_scale[m] : 0.0f;
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = nw + j * 32 + g * 8 + lhalf * 4;
+                    const bool ok = mok && (!EDGE || n < p.N);
+                    f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                    float *gp = reinterpret_cast<float *>(p.out) + (int64_t)m * p.ld_out + n;
+                    if (EPI == EPI_LINEAR) {
+                        v *= rs;
+                        if (p.add && ok) {
+                            const u32x2 c = *reinterpret_cast<const u32x2 *>(p.add + (int64_t)m * p.ld_add + n);
+                            v[0] += bf16_lo(c[0]); v[1] += bf16_hi(c[0]);
+                            v[2] += bf16_lo(c[1]); v[3] += bf16_hi(c[1]);
+                        }
+                        if (ok) rsum[i] += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+                        if (p.side && ok) {
+                            const f32x4 gm = *reinterpret_cast<const f32x4 *>(p.col_scale + n);
+                            *reinterpret_cast<u32x2 *>(p.side + (int64_t)m * p.ld_side + n) =
+                                u32x2{pack_bf16x2(v[0] * gm[0], v[1] * gm[1]), pack_bf16x2(v[2] * gm[2], v[3] * gm[3])};
+                        }
+                        if (ok) *reinterpret_cast<f32x4 *>(gp) = v;
+                        asm volatile("" : "+v"(rsum[i]));
+                    } else if (ok) {
+                        f32x4 cur = *reinterpret_cast<const f32x4 *>(gp);
+                        cur += v;
+                        *reinterpret_cast<f32x4 *>(gp) = cur;
+                    }
+                }
+        }
+    }
+
+    if (want_red) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const float s = rsum[i] + __shfl_xor(rsum[i], 32, 64);
+            if (lane < 32) red[wn * BM + wm * WTM + i * 32 + lane] = s;
+        }
+        __syncthreads();
+        for (int r = tid; r < BM; r += C::NT) {
+            const int m = m0 + r;
+            if (EDGE && m >= p.M) continue;
+            float s = 0.0f;
+#pragma unroll
+            for (int w = 0; w < C::WGN; ++w) s += red[w * BM + r];
+            if (p.rowred_mode == ROWRED_PARTIALS)
+                p.rowred[(int64_t)tn * p.M + m] = s;
+            else
+                atomicAdd(p.rowred + m, s);
+        }
+    }
+}
+
 template <class C, bool AK, bool BKC, int EPI, bool EDGE>
 __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmParams p)
 {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, FM = C::FM, FN = C::FN;
-    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * C::STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * C::STAGE_BYTES];
+    __shared__ float red[C::WGN * C::BM];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % C::WGM, wn = wave / C::WGM;
@@ -262,111 +646,186 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmParams p)
         __syncthreads();
     }
 
-    // ------------------------------------------------------------------ epilogue
-    // lane -> (row, column group):  m = mb + (lane & 31);  n = nb + 8*g + 4*(lane >> 5) + e
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    const int mw = m0 + wm * C::WTM, nw = n0 + wn * C::WTN;
-    float *red = reinterpret_cast<float *>(smem);  // [WGN][BM] row-reduction exchange
-    const bool want_red = (EPI == EPI_LINEAR || EPI == EPI_SWIGLU_BWD) && p.rowred_mode != ROWRED_NONE;
+    run_epilogue<C, EPI, EDGE, 2 * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
+}
 
-#pragma unroll
-    for (int i = 0; i < FM; ++i) {
-        const int m = mw + i * 32 + lrow;
-        const bool mok = !EDGE || m < p.M;
-        float rs = 1.0f;
-        if ((EPI == EPI_LINEAR || EPI == EPI_SWIGLU_FWD) && p.row_scale) rs = mok ? p.row_scale[m] : 0.0f;
-        float rsum = 0.0f;
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = nw + j * 32 + g * 8 + lhalf * 4;
-                const bool ok = mok && (!EDGE || n < p.N);
-                f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                if (EPI == EPI_LINEAR) {
-                    v *= rs;
-                    if (p.add && ok) {
-                        u32x2 c = *reinterpret_cast<const u32x2 *>(p.add + (int64_t)m * p.ld_add + n);
-                        v[0] += bf16_lo(c[0]); v[1] += bf16_hi(c[0]);
-                        v[2] += bf16_lo(c[1]); v[3] += bf16_hi(c[1]);
-                    }
-                    if (ok) rsum += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-                    if (p.side && ok) {
-                        f32x4 gm = *reinterpret_cast<const f32x4 *>(p.col_scale + n);
-                        u32x2 o = {pack_bf16x2(v[0] * gm[0], v[1] * gm[1]), pack_bf16x2(v[2] * gm[2], v[3] * gm[3])};
-                        *reinterpret_cast<u32x2 *>(p.side + (int64_t)m * p.ld_side + n) = o;
-                    }
-                    if (ok) {
-                        if (p.out_f32) {
-                            *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(p.out) + (int64_t)m * p.ld_out + n) = v;
-                        } else {
-                            u32x2 o = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-                            *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(p.out) + (int64_t)m * p.ld_out + n) = o;
-                        }
-                    }
-                } else if (EPI == EPI_SWIGLU_FWD) {
-                    v *= rs;
-                    if (ok) {
-                        if (p.out2) {
-                            u32x2 o = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-                            *reinterpret_cast<u32x2 *>(p.out2 + (int64_t)m * p.ld_out2 + n) = o;
-                        }
-                        const float h0 = v[0] * fast_sigmoid(v[0]) * v[1];
-                        const float h1 = v[2] * fast_sigmoid(v[2]) * v[3];
-                        *reinterpret_cast<uint32_t *>(reinterpret_cast<uint16_t *>(p.out) + (int64_t)m * p.ld_out + (n >> 1)) =
-                            pack_bf16x2(h0, h1);
-                    }
-                } else if (EPI == EPI_SWIGLU_BWD) {
-                    if (ok) {
-                        const u32x4 z = *reinterpret_cast<const u32x4 *>(p.Z + (int64_t)m * p.ldz + 2 * n);
-                        u32x4 dz;
-                        float o[4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float gg = bf16_lo(z[e]), uu = bf16_hi(z[e]);
-                            const float sg = fast_sigmoid(gg);
-                            const float sl = gg * sg;
-                            const float dU = v[e] * sl;
-                            const float dG = v[e] * uu * (sg + sl * (1.0f - sg));
-                            dz[e] = pack_bf16x2(dG, dU);
-                            o[e] = sl * uu;
-                            rsum += gg * dG + uu * dU;
-                        }
-                        *reinterpret_cast<u32x4 *>(reinterpret_cast<uint16_t *>(p.out) + (int64_t)m * p.ld_out + 2 * n) = dz;
-                        if (p.out2) {
-                            u32x2 oo = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
-                            *reinterpret_cast<u32x2 *>(p.out2 + (int64_t)m * p.ld_out2 + n) = oo;
-                        }
-                    }
-                } else {  // EPI_ACCUM
-                    if (ok) {
-                        float *gp = reinterpret_cast<float *>(p.out) + (int64_t)m * p.ld_out + n;
-                        f32x4 cur = *reinterpret_cast<const f32x4 *>(gp);
-                        cur += v;
-                        *reinterpret_cast<f32x4 *>(gp) = cur;
-                    }
-                }
-            }
-        }
-        if (want_red) {
-            rsum += __shfl_xor(rsum, 32, 64);
-            if (lane < 32) red[wn * BM + wm * C::WTM + i * 32 + lane] = rsum;
-        }
+// ---------------------------------------------------------------------------------
+// Fast path (no edge tiles): multi-stage LDS ring filled by direct-to-LDS global loads.
+//
+// global_load_lds_dwordx4 moves 16 bytes per lane from global memory straight into LDS
+// (lane L of the issuing wave lands at M0-base + 16*L), so operand tiles never pass
+// through VGPRs and there is no ds_write phase.  The LDS position of a chunk is fixed
+// by the lane, so the XOR swizzle is applied on the global side: lane L fetches the
+// chunk whose swizzled home is position L.  Per-lane global offsets are loop-invariant
+// (32-bit, in VGPRs); only the 64-bit scalar base advances along K.
+//
+// Pipeline per K-step kt of BK = 32 (two 16-wide MFMA slices), STAGES-deep ring:
+//   A  issue loads of tile kt+STAGES-1 into the slot freed by tile kt-1
+//   B  read slice-1 fragments of tile kt; 16 MFMAs on slice 0 (fragments already in VGPRs)
+//   C  wait until this wave's loads of tile kt+1 have landed; workgroup barrier
+//   D  read slice-0 fragments of tile kt+1; 16 MFMAs on slice 1
+// The barrier sits between two MFMA blocks whose operands are already in registers, so
+// LDS latency is never exposed; it orders (i) every wave's reads of tile kt before the
+// slot is refilled in step A of kt+1 and (ii) all loads of tile kt+1 before step D.
+// The loads are issued from inline asm, invisible to the compiler's waitcnt insertion;
+// vmcnt is waited on explicitly (loads retire in order).
+// ---------------------------------------------------------------------------------
+template <int BM_, int BN_, int WGM_, int WGN_, int STAGES_>
+struct DlCfg : TileCfg<BM_, BN_, 32, WGM_, WGN_> {
+    using Base = TileCfg<BM_, BN_, 32, WGM_, WGN_>;
+    static constexpr int STAGES = STAGES_;
+    static constexpr int NW = WGM_ * WGN_;
+    static constexpr int LA = Base::A_BYTES / 1024 / NW, LB = Base::B_BYTES / 1024 / NW;  // wave-loads per wave
+    static_assert(Base::A_BYTES % (1024 * NW) == 0 && Base::B_BYTES % (1024 * NW) == 0, "whole wave-loads");
+    static_assert(STAGES >= 3 && STAGES * Base::STAGE_BYTES <= 160 * 1024, "LDS ring");
+};
+
+// Byte offset (from the tile's first element in global memory) of the chunk that lane `lane`
+// of wave-load `j` must fetch so that it lands at its swizzled LDS home.
+template <class C, int ROWS, bool KCONT>
+__device__ __forceinline__ uint32_t dl_goffset(int j, int lane, int64_t ld)
+{
+    if (KCONT) {  // [ROWS][32]: 64-byte rows, 16 rows per wave-load
+        const int r = j * 16 + (lane >> 2);
+        const int c = (lane & 3) ^ ((r >> 2) & 3);
+        return (uint32_t)(((int64_t)r * ld + c * 8) * 2);
+    } else {      // [32][ROWS]: 2 k-rows per wave-load (ROWS = 256) or 4 (ROWS = 128)
+        constexpr int CPR = ROWS / 8;  // chunks per k-row
+        const int idx = j * 64 + lane;
+        const int k = idx / CPR, pc = idx % CPR;
+        const int g = (pc >> 1) ^ mn_swz(k);
+        return (uint32_t)(((int64_t)k * ld + (g * 2 + (pc & 1)) * 8) * 2);
     }
-    if (want_red) {
+}
+
+// K-contiguous fragment read for BK = 32 tiles (64-byte rows, 4 chunks, swizzle on row bits 2..3).
+template <int ROWS, bool KCONT>
+__device__ __forceinline__ bf16x8 dl_frag(const unsigned char *tile, int row_base, int ks, int lane)
+{
+    if (KCONT) {
+        const int r = row_base + (lane & 31);
+        const int c = (ks * 2 + (lane >> 5)) ^ ((r >> 2) & 3);
+        return *reinterpret_cast<const bf16x8 *>(tile + r * 64 + c * 16);
+    } else {
+        const int i = lane & 15, nh = (lane >> 4) & 1, h = lane >> 5;
+        const int gr = (row_base >> 4) + nh;
+        const int k_lo = ks * 16 + 8 * h + (i >> 2);
+        const uint32_t sub = (uint32_t)((i & 3) << 3);
+        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tile + lds_mn<ROWS>(k_lo, gr) + sub));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tile + lds_mn<ROWS>(k_lo + 4, gr) + sub));
+        typedef __attribute__((ext_vector_type(8))) short s16x8;
+        s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, v);
+    }
+}
+
+__device__ __forceinline__ void dl_load16(uint32_t voff, const void *sbase, uint32_t lds_addr)
+{
+    // M0 carries the wave-uniform LDS destination; one wait state between the M0 write and its use.
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(voff), "s"(sbase), "s"(lds_addr)
+                 : "memory");
+}
+
+template <class C, bool AK, bool BKC, int EPI>
+__global__ __launch_bounds__(C::NT) void gemm_kernel_dl(const GemmParams p)
+{
+    constexpr int BM = C::BM, BN = C::BN, BK = 32, FM = C::FM, FN = C::FN, S = C::STAGES;
+    constexpr int LA = C::LA, LB = C::LB;
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[S * C::STAGE_BYTES];
+    __shared__ float red[C::WGN * C::BM];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % C::WGM, wn = wave / C::WGM;
+    int tm, tn;
+    tile_coords(blockIdx.x, gridDim.x, p.tiles_m, p.tiles_n, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int KT = p.K / BK;
+
+    // loop-invariant per-lane byte offsets of this wave's chunks; wave w issues wave-loads w*L .. w*L+L-1
+    uint32_t offa[LA], offb[LB];
+#pragma unroll
+    for (int i = 0; i < LA; ++i) offa[i] = dl_goffset<C, BM, AK>(wave * LA + i, lane, p.lda);
+#pragma unroll
+    for (int i = 0; i < LB; ++i) offb[i] = dl_goffset<C, BN, BKC>(wave * LB + i, lane, p.ldb);
+    // scalar bases of the tile's first element; advance by one K-step per tile
+    const unsigned char *ga = reinterpret_cast<const unsigned char *>(AK ? p.A + (int64_t)m0 * p.lda : p.A + m0);
+    const unsigned char *gb = reinterpret_cast<const unsigned char *>(BKC ? p.B + (int64_t)n0 * p.ldb : p.B + n0);
+    const int64_t stepa = AK ? (int64_t)BK * 2 : (int64_t)BK * p.lda * 2;
+    const int64_t stepb = BKC ? (int64_t)BK * 2 : (int64_t)BK * p.ldb * 2;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+
+    auto issue = [&](int t) {  // loads of tile t into slot t % S
+        const uint32_t slot = lds0 + (uint32_t)(t % S) * C::STAGE_BYTES;
+        const unsigned char *sa = ga + (int64_t)t * stepa;
+        const unsigned char *sb = gb + (int64_t)t * stepb;
+#pragma unroll
+        for (int i = 0; i < LA; ++i) dl_load16(offa[i], sa, slot + (uint32_t)(wave * LA + i) * 1024u);
+#pragma unroll
+        for (int i = 0; i < LB; ++i) dl_load16(offb[i], sb, slot + C::A_BYTES + (uint32_t)(wave * LB + i) * 1024u);
+    };
+
+    bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];
+    auto read_frags = [&](bf16x8(&fa)[FM], bf16x8(&fb)[FN], int t, int ks) {
+        const unsigned char *sa = smem + (t % S) * C::STAGE_BYTES;
+        const unsigned char *sb = sa + C::A_BYTES;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) fa[i] = dl_frag<BM, AK>(sa, wm * C::WTM + i * 32, ks, lane);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) fb[j] = dl_frag<BN, BKC>(sb, wn * C::WTN + j * 32, ks, lane);
+    };
+    auto mma = [&](const bf16x8(&fa)[FM], const bf16x8(&fb)[FN]) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    };
+
+    if (KT > 0) {
+        // prologue: fill S-1 slots, wait for tile 0
+#pragma unroll
+        for (int t = 0; t < S - 1; ++t)
+            if (t < KT) issue(t);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // short prologue: wait for everything issued
         __syncthreads();
-        for (int r = tid; r < BM; r += C::NT) {
-            const int m = m0 + r;
-            if (EDGE && m >= p.M) continue;
-            float s = 0.0f;
-#pragma unroll
-            for (int w = 0; w < C::WGN; ++w) s += red[w * BM + r];
-            if (p.rowred_mode == ROWRED_PARTIALS)
-                p.rowred[(int64_t)tn * p.M + m] = s;
-            else
-                atomicAdd(p.rowred + m, s);
+        read_frags(fa0, fb0, 0, 0);
+
+        // all iterations but the last (peeled so that the loop body is branch-free around the MFMA blocks)
+        for (int kt = 0; kt < KT - 1; ++kt) {
+            const bool refill = kt + S - 1 < KT;
+            if (refill) issue(kt + S - 1);                               // A
+            read_frags(fa1, fb1, kt, 1);                                 // B
+            mma(fa0, fb0);
+            // C: this wave's loads of tile kt+1 must have landed; tiles kt+2.. may still be in flight
+            if (refill) {
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
+            } else {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+            __syncthreads();
+            read_frags(fa0, fb0, kt + 1, 0);                             // D
+            mma(fa1, fb1);
         }
+        read_frags(fa1, fb1, KT - 1, 1);
+        mma(fa0, fb0);
+        mma(fa1, fb1);
     }
+    __syncthreads();  // every wave is done with the operand ring before the epilogue reuses it
+
+    run_epilogue<C, EPI, false, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
 }
 
 // Host-side launcher, one per (operand layouts, epilogue mode, edge predication).

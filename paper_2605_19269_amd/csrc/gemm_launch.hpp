@@ -4,14 +4,21 @@
 
 namespace coda {
 
-using MainCfg = TileCfg<256, 256, 64, 2, 2>;
+using MainCfg = TileCfg<256, 256, 64, 2, 4>;   // register-staged kernel (edge tiles)
+using FastCfg = DlCfg<256, 256, 2, 4, 4>;       // direct-to-LDS ring (whole tiles only)
+static_assert(MainCfg::BM == FastCfg::BM && MainCfg::BN == FastCfg::BN, "both kernels share the tile grid");
 
 template <bool AK, bool BKC, int EPI, bool EDGE>
 hipError_t launch_gemm(const GemmParams &p, hipStream_t stream)
 {
-    using C = MainCfg;
-    const dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(C::NT);
-    hipLaunchKernelGGL((gemm_kernel<C, AK, BKC, EPI, EDGE>), grid, block, 0, stream, p);
+    const dim3 grid((unsigned)(p.tiles_m * p.tiles_n));
+    if constexpr (EDGE) {
+        using C = MainCfg;
+        hipLaunchKernelGGL((gemm_kernel<C, AK, BKC, EPI, true>), grid, dim3(C::NT), 0, stream, p);
+    } else {
+        using C = FastCfg;
+        hipLaunchKernelGGL((gemm_kernel_dl<C, AK, BKC, EPI>), grid, dim3(C::NT), 0, stream, p);
+    }
     return hipGetLastError();
 }
 
