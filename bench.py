@@ -26,9 +26,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 FLOP/clk x 2.4 GHz
 
-# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-# see profiles/; None until measured for the current kernel.
-MEASURED_TRAFFIC_BYTES = None
+# Bytes per launch of the dominant kernel (up-projection) crossing the L2 -> fabric boundary, measured with
+# rocprofv3 --pmc: FETCH_SIZE 393581 KiB x 2.0 (calibration factor from a plain copy) + WRITE_SIZE 131075 KiB x 1.0;
+# see profiles/gemm_epilogue_llama1b_mlp_block_hbm_traffic.md.  Algorithmic bytes are 234.9e6.
+MEASURED_TRAFFIC_BYTES = int(393581 * 1024 * 2.0 + 131075 * 1024)
 
 
 def main():
@@ -39,6 +40,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unfused", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (known traffic) so that rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE readings can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the kernels are single-GPU; sharding is a "
@@ -108,6 +112,13 @@ def main():
             step_fn(rec)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
+
+    if args.calibration_copy:
+        src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     rec = {k: [] for k in kernels}
     sec = run(fused_step, args.steps, args.warmup, rec)
