@@ -1,0 +1,119 @@
+"""Full-size parity: the BASELINE workloads at their real shapes, launched exactly as bench.py launches
+them (same programs, same layouts, whole-tile fast kernel), checked on a deterministic sample of output rows
+that the oracle computes one by one.  Every epilogue on the path is row-local, so sampled rows are exact; the
+weight gradient is sampled over its own output rows."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_19269_amd import synth
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+coda = None
+NSAMPLE = 48
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    global coda
+    assert torch.cuda.is_available()
+    from paper_2605_19269_amd import coda as _c
+    coda = _c
+    yield
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+
+
+def rows_of(t, rows):
+    return G.host_f64(t[torch.from_numpy(rows).cuda()])
+
+
+def gpu_rstd(X, eps=1e-6):
+    M, d = X.shape
+    ss = torch.empty(M, dtype=torch.float32, device="cuda")
+    r = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_row_sumsq(X, ss)
+    coda.coda_row_finalize(ss.view(1, M), M, 1, rstd_out=r, d=d, eps=eps)
+    return r
+
+
+def check_up(oracle, Xb, Wb, tag):
+    M, N = Xb.shape[0], Wb.shape[1]
+    rows = synth.sample_rows(M, NSAMPLE, seed=3)
+    X, W = G.dev_bf16(Xb), G.dev_bf16(Wb)
+    r = gpu_rstd(X)
+    H = torch.empty((M, N // 2), dtype=torch.bfloat16, device="cuda")
+    coda.coda_gemm(X, W, [coda.row_scale(r), coda.swiglu_fwd(), coda.store(H)])
+    torch.cuda.synchronize()
+    r_host = r.cpu().numpy()
+    G.assert_sumsq_close(r_host[rows], oracle.rstd(Xb, 1e-6, rows=rows), tag + " rstd")
+    ref = oracle.gemm_rowscale_swiglu(Xb, Wb, r=r_host.astype(np.float64), rows=rows)   # same fp32 r bytes as the GPU
+    G.assert_bf16_close(rows_of(H, rows), ref, tag + " H")
+
+
+def check_down(oracle, Hb, Wb, Rb, tag):
+    M, N = Hb.shape[0], Wb.shape[1]
+    rows = synth.sample_rows(M, NSAMPLE, seed=4)
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    nblk = coda.coda_row_partial_blocks(N)
+    part = torch.empty((nblk, M), dtype=torch.float32, device="cuda")
+    ss = torch.empty(M, dtype=torch.float32, device="cuda")
+    dR = G.dev_bf16(Rb)
+    coda.coda_gemm(G.dev_bf16(Hb), G.dev_bf16(Wb), [coda.add_tile(dR), coda.row_sumsq(part), coda.store(Y)])
+    coda.coda_row_finalize(part, M, nblk, sum_out=ss, d=N, eps=0.0)
+    torch.cuda.synchronize()
+    refY, refss = oracle.gemm_residual_sumsq(Hb, Wb, C=Rb, rows=rows)
+    G.assert_bf16_close(rows_of(Y, rows), refY, tag + " Y")
+    G.assert_sumsq_close(ss.cpu().numpy()[rows], refss, tag + " sumsq")
+
+
+def test_llama1b_up_projection(oracle):
+    c = synth.up_projection(seed=0)
+    check_up(oracle, c["X"], c["W"], "1B up")
+
+
+def test_llama1b_down_projection(oracle):
+    c = synth.down_projection(seed=1)
+    check_down(oracle, c["H"], c["W"], c["R"], "1B down")
+
+
+def test_llama1b_mlp_backward(oracle):
+    c = synth.mlp_backward(seed=2)
+    M, d = c["dY"].shape
+    F = c["W"].shape[0]
+    dY, W, Z, H = G.dev_bf16(c["dY"]), G.dev_bf16(c["W"]), G.dev_bf16(c["Z"]), G.dev_bf16(c["H"])
+    dZ = torch.empty((M, 2 * F), dtype=torch.bfloat16, device="cuda")
+    coda.coda_gemm(dY, W, [coda.swiglu_bwd(Z), coda.store(dZ)], transB=True)
+    Gb = torch.from_numpy(c["G"]).cuda()
+    coda.coda_gemm(H, dY, [coda.accum_f32(Gb)], transA=True)
+    torch.cuda.synchronize()
+    rows = synth.sample_rows(M, NSAMPLE, seed=5)
+    refdZ, _, _ = oracle.gemm_swiglu_bwd(c["dY"], c["W"], c["Z"], transB=True, rows=rows)
+    G.assert_bf16_close(rows_of(dZ, rows), refdZ, "1B dZ")
+    wrows = synth.sample_rows(F, NSAMPLE, seed=6)
+    refG = oracle.gemm_accumulate(c["H"], c["dY"], c["G"], transA=True, rows=wrows)
+    G.assert_f32_signed_close(rows_of(Gb, wrows), refG, "1B dW accumulate")
+
+
+def test_llama8b_block_shapes(oracle):
+    """LLaMA-3-8B-style shapes: QKV projection with row scale, up-projection with SwiGLU, down-projection with
+    residual add and sum of squares (M = 16384, d = 4096, F = 14336)."""
+    c = synth.block_8b(seed=7)
+    M = c["X"].shape[0]
+    rows = synth.sample_rows(M, 32, seed=8)
+    X = G.dev_bf16(c["X"])
+    r = gpu_rstd(X)
+    r_host = r.cpu().numpy().astype(np.float64)
+    Q = torch.empty((M, c["Wqkv"].shape[1]), dtype=torch.bfloat16, device="cuda")
+    coda.coda_gemm(X, G.dev_bf16(c["Wqkv"]), [coda.row_scale(r), coda.store(Q)])
+    torch.cuda.synchronize()
+    G.assert_bf16_close(rows_of(Q, rows), oracle.gemm_rowscale(c["X"], c["Wqkv"], r=r_host, rows=rows), "8B qkv")
+    del Q
+    global NSAMPLE
+    keep, NSAMPLE = NSAMPLE, 32
+    try:
+        check_up(oracle, c["X"], c["Wup"], "8B up")
+        check_down(oracle, c["H"], c["Wdown"], c["R"], "8B down")
+    finally:
+        NSAMPLE = keep
