@@ -203,9 +203,7 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
     p.M = (int)M;
     p.N = (int)N;
     p.K = (int)K;
-    p.tiles_m = (int)((M + C::BM - 1) / C::BM);
-    p.tiles_n = (int)((N + C::BN - 1) / C::BN);
-    if ((int64_t)p.tiles_m * p.tiles_n > INT32_MAX) return CODA_ERR_SHAPE;
+    if (((M + C::BM - 1) / C::BM) * ((N + C::BN - 1) / C::BN) * 2 > INT32_MAX) return CODA_ERR_SHAPE;
     const bool edge = (M % C::BM) || (N % C::BN) || (K % C::BK);
     const bool ak = !A->trans;   // A stored [M x K]: contraction index contiguous
     const bool bkc = B->trans;   // B stored [N x K]: contraction index contiguous

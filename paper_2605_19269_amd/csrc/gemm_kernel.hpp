@@ -314,6 +314,13 @@ __device__ __forceinline__ void stage_fence()
     __builtin_amdgcn_sched_barrier(0);
 }
 
+constexpr int pass_rows(int reg_bytes, int row_bytes, int max_rows)
+{
+    int p = 32;
+    while (p * 2 <= max_rows && p * 2 * row_bytes <= reg_bytes) p *= 2;
+    return p;
+}
+
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
 // ---------------------------------------------------------------------------------
@@ -340,70 +347,10 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
 #pragma unroll
     for (int i = 0; i < FM; ++i) rsum[i] = 0.0f;
 
-    if (EPI == EPI_LINEAR && !p.out_f32) {
-        // ---- row scale, residual add, row sum of squares, bf16 store: all tile I/O staged.  The gamma-scaled side
-        // output (when requested) is a second sweep that re-reads the residual and recomputes the value, so that
-        // nothing has to stay in registers between the two stores.
-        constexpr int RB = WTN * 2, P = (REG / RB) < WTM ? (REG / RB) : WTM, FPP = P / 32;
-        static_assert(P % 32 == 0 && WTM % P == 0, "staging pass");
-        const uint32_t ulane = Stage<RB>::template unit_lane<8>(lane);
-        const int sweeps = p.side ? 2 : 1;
-        for (int sw = 0; sw < sweeps; ++sw) {
-            uint16_t *dst = sw == 0 ? reinterpret_cast<uint16_t *>(p.out) : p.side;
-            const int64_t ldd = sw == 0 ? p.ld_out : p.ld_side;
-#pragma unroll
-            for (int ps = 0; ps < WTM / P; ++ps) {
-                const int r0 = ps * P;
-                if (p.add) {
-                    stage_load<RB, P, EDGE>(reg, reinterpret_cast<const unsigned char *>(p.add + (int64_t)(mw + r0) * p.ld_add + nw),
-                                            p.ld_add * 2, rows_ok - r0, cols_ok * 2, lane);
-                    stage_fence();
-                }
-#pragma unroll
-                for (int fi = 0; fi < FPP; ++fi) {
-                    const int i = ps * FPP + fi, m = mw + i * 32 + lrow;
-                    const bool mok = !EDGE || m < p.M;
-                    const float rs = p.row_scale ? (mok ? p.row_scale[m] : 0.0f) : 1.0f;
-#pragma unroll
-                    for (int j = 0; j < FN; ++j)
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            const int nl = j * 32 + g * 8 + lhalf * 4;
-                            const bool ok = mok && (!EDGE || nw + nl < p.N);
-                            f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                            v *= rs;
-                            u32x2 *slot = reinterpret_cast<u32x2 *>(reg + Stage<RB>::unit_addr(ulane, fi, (j * 32 + g * 8) * 2));
-                            if (p.add) {
-                                const u32x2 c = *slot;
-                                v[0] += bf16_lo(c[0]); v[1] += bf16_hi(c[0]);
-                                v[2] += bf16_lo(c[1]); v[3] += bf16_hi(c[1]);
-                            }
-                            if (sw == 0) {
-                                if (ok) rsum[i] += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-                            } else {
-                                f32x4 gm = {0.f, 0.f, 0.f, 0.f};
-                                if (ok) gm = *reinterpret_cast<const f32x4 *>(p.col_scale + nw + nl);
-                                v *= gm;
-                            }
-                            *slot = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-                            if (g == 3) {
-                                // pin the running row sum here: otherwise its whole add chain is sunk to the point of
-                                // use after the stores and every addend has to stay live (spilled) until then
-                                asm volatile("" : "+v"(rsum[i]));
-                                __builtin_amdgcn_sched_barrier(0);
-                            }
-                        }
-                }
-                stage_fence();
-                stage_store<RB, P, EDGE>(reg, reinterpret_cast<unsigned char *>(dst + (int64_t)(mw + r0) * ldd + nw), ldd * 2,
-                                         rows_ok - r0, cols_ok * 2, lane);
-                stage_fence();
-            }
-        }
-    } else if (EPI == EPI_SWIGLU_FWD) {
+    if constexpr (EPI == EPI_SWIGLU_FWD) {
         // ---- row scale, pairwise SwiGLU (width halves), optional pre-activation side output
         constexpr int RBH = WTN, RBZ = WTN * 2;
-        constexpr int P = (REG / RBZ) < WTM ? (REG / RBZ) : WTM, FPP = P / 32;
+        constexpr int P = pass_rows(REG, RBZ, WTM), FPP = P / 32;
         static_assert(P % 32 == 0 && WTM % P == 0, "staging pass");
         uint16_t *outp = reinterpret_cast<uint16_t *>(p.out);
         const uint32_t ulane_h = Stage<RBH>::template unit_lane<4>(lane), ulane_z = Stage<RBZ>::template unit_lane<8>(lane);
@@ -449,11 +396,11 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
             }
             stage_fence();
         }
-    } else if (EPI == EPI_SWIGLU_BWD) {
+    } else if constexpr (EPI == EPI_SWIGLU_BWD) {
         // ---- pairwise SwiGLU backward (width doubles): Z in and dZ out staged; row statistic; the optional
         // recomputed activation silu(g)*u is a second sweep over 32-row blocks that re-reads Z.
         constexpr int RB = WTN * 4, RBO = WTN * 2;
-        constexpr int P = (REG / RB) < WTM ? (REG / RB) : WTM, FPP = P / 32;
+        constexpr int P = pass_rows(REG, RB, WTM), FPP = P / 32;
         static_assert(P % 32 == 0 && WTM % P == 0 && 32 * (RB + RBO) <= REG, "staging pass");
         uint16_t *outp = reinterpret_cast<uint16_t *>(p.out);
         const uint32_t ulane = Stage<RB>::template unit_lane<16>(lane), ulane_o = Stage<RBO>::template unit_lane<8>(lane);
@@ -519,6 +466,66 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
                 stage_fence();
                 stage_store<RBO, 32, EDGE>(rego, reinterpret_cast<unsigned char *>(p.out2 + (int64_t)(mw + r0) * p.ld_out2 + nw),
                                            p.ld_out2 * 2, rows_ok - r0, cols_ok * 2, lane);
+                stage_fence();
+            }
+        }
+    } else if (EPI == EPI_LINEAR && !p.out_f32) {
+        // ---- row scale, residual add, row sum of squares, bf16 store: all tile I/O staged.  The gamma-scaled side
+        // output (when requested) is a second sweep that re-reads the residual and recomputes the value, so that
+        // nothing has to stay in registers between the two stores.
+        constexpr int RB = WTN * 2, P = pass_rows(REG, RB, WTM), FPP = P / 32;
+        static_assert(P % 32 == 0 && WTM % P == 0, "staging pass");
+        const uint32_t ulane = Stage<RB>::template unit_lane<8>(lane);
+        const int sweeps = p.side ? 2 : 1;
+        for (int sw = 0; sw < sweeps; ++sw) {
+            uint16_t *dst = sw == 0 ? reinterpret_cast<uint16_t *>(p.out) : p.side;
+            const int64_t ldd = sw == 0 ? p.ld_out : p.ld_side;
+#pragma unroll
+            for (int ps = 0; ps < WTM / P; ++ps) {
+                const int r0 = ps * P;
+                if (p.add) {
+                    stage_load<RB, P, EDGE>(reg, reinterpret_cast<const unsigned char *>(p.add + (int64_t)(mw + r0) * p.ld_add + nw),
+                                            p.ld_add * 2, rows_ok - r0, cols_ok * 2, lane);
+                    stage_fence();
+                }
+#pragma unroll
+                for (int fi = 0; fi < FPP; ++fi) {
+                    const int i = ps * FPP + fi, m = mw + i * 32 + lrow;
+                    const bool mok = !EDGE || m < p.M;
+                    const float rs = p.row_scale ? (mok ? p.row_scale[m] : 0.0f) : 1.0f;
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            const int nl = j * 32 + g * 8 + lhalf * 4;
+                            const bool ok = mok && (!EDGE || nw + nl < p.N);
+                            f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                            v *= rs;
+                            u32x2 *slot = reinterpret_cast<u32x2 *>(reg + Stage<RB>::unit_addr(ulane, fi, (j * 32 + g * 8) * 2));
+                            if (p.add) {
+                                const u32x2 c = *slot;
+                                v[0] += bf16_lo(c[0]); v[1] += bf16_hi(c[0]);
+                                v[2] += bf16_lo(c[1]); v[3] += bf16_hi(c[1]);
+                            }
+                            if (sw == 0) {
+                                if (ok) rsum[i] += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+                            } else {
+                                f32x4 gm = {0.f, 0.f, 0.f, 0.f};
+                                if (ok) gm = *reinterpret_cast<const f32x4 *>(p.col_scale + nw + nl);
+                                v *= gm;
+                            }
+                            *slot = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+                            if (g == 3) {
+                                // pin the running row sum here: otherwise its whole add chain is sunk to the point of
+                                // use after the stores and every addend has to stay live (spilled) until then
+                                asm volatile("" : "+v"(rsum[i]));
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        }
+                }
+                stage_fence();
+                stage_store<RB, P, EDGE>(reg, reinterpret_cast<unsigned char *>(dst + (int64_t)(mw + r0) * ldd + nw), ldd * 2,
+                                         rows_ok - r0, cols_ok * 2, lane);
                 stage_fence();
             }
         }
@@ -670,10 +677,11 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmParams p)
 // The loads are issued from inline asm, invisible to the compiler's waitcnt insertion;
 // vmcnt is waited on explicitly (loads retire in order).
 // ---------------------------------------------------------------------------------
-template <int BM_, int BN_, int WGM_, int WGN_, int STAGES_>
+template <int BM_, int BN_, int WGM_, int WGN_, int STAGES_, int WPE_ = 2>
 struct DlCfg : TileCfg<BM_, BN_, 32, WGM_, WGN_> {
     using Base = TileCfg<BM_, BN_, 32, WGM_, WGN_>;
     static constexpr int STAGES = STAGES_;
+    static constexpr int WPE = WPE_;   // waves per SIMD the kernel is compiled for (register budget 512 / WPE)
     static constexpr int NW = WGM_ * WGN_;
     static constexpr int LA = Base::A_BYTES / 1024 / NW, LB = Base::B_BYTES / 1024 / NW;  // wave-loads per wave
     static_assert(Base::A_BYTES % (1024 * NW) == 0 && Base::B_BYTES % (1024 * NW) == 0, "whole wave-loads");
@@ -730,7 +738,7 @@ __device__ __forceinline__ void dl_load16(uint32_t voff, const void *sbase, uint
 }
 
 template <class C, bool AK, bool BKC, int EPI>
-__global__ __launch_bounds__(C::NT) void gemm_kernel_dl(const GemmParams p)
+__global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE))) void gemm_kernel_dl(const GemmParams p)
 {
     constexpr int BM = C::BM, BN = C::BN, BK = 32, FM = C::FM, FN = C::FN, S = C::STAGES;
     constexpr int LA = C::LA, LB = C::LB;

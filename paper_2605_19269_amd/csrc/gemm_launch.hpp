@@ -2,22 +2,30 @@
 #pragma once
 #include "gemm_kernel.hpp"
 
+#include <type_traits>
+
 namespace coda {
 
 using MainCfg = TileCfg<256, 256, 64, 2, 4>;   // register-staged kernel (edge tiles)
-using FastCfg = DlCfg<256, 256, 2, 4, 4>;       // direct-to-LDS ring (whole tiles only)
-static_assert(MainCfg::BM == FastCfg::BM && MainCfg::BN == FastCfg::BN, "both kernels share the tile grid");
+using FastCfg = DlCfg<256, 256, 2, 4, 4>;       // direct-to-LDS ring (whole tiles only); 128x64 wave tiles
+static_assert(MainCfg::BM % FastCfg::BM == 0 && MainCfg::BN == FastCfg::BN, "tile grids");
 
+// `p` arrives without tile counts; they depend on the kernel chosen here.  EDGE = false promises that M, N, K
+// are whole multiples of MainCfg's tile (and therefore of the fast tile).
 template <bool AK, bool BKC, int EPI, bool EDGE>
-hipError_t launch_gemm(const GemmParams &p, hipStream_t stream)
+hipError_t launch_gemm(const GemmParams &p_in, hipStream_t stream)
 {
-    const dim3 grid((unsigned)(p.tiles_m * p.tiles_n));
+    GemmParams p = p_in;
     if constexpr (EDGE) {
         using C = MainCfg;
-        hipLaunchKernelGGL((gemm_kernel<C, AK, BKC, EPI, true>), grid, dim3(C::NT), 0, stream, p);
+        p.tiles_m = (p.M + C::BM - 1) / C::BM;
+        p.tiles_n = (p.N + C::BN - 1) / C::BN;
+        hipLaunchKernelGGL((gemm_kernel<C, AK, BKC, EPI, true>), dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(C::NT), 0, stream, p);
     } else {
         using C = FastCfg;
-        hipLaunchKernelGGL((gemm_kernel_dl<C, AK, BKC, EPI>), grid, dim3(C::NT), 0, stream, p);
+        p.tiles_m = p.M / C::BM;
+        p.tiles_n = p.N / C::BN;
+        hipLaunchKernelGGL((gemm_kernel_dl<C, AK, BKC, EPI>), dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(C::NT), 0, stream, p);
     }
     return hipGetLastError();
 }
