@@ -17,7 +17,7 @@ _lib = None
 
 __all__ = [
     "build", "lib_path", "num_threads", "bf16_bits_to_f64", "row_sumsq", "rstd", "rstd_from_sumsq",
-    "gemm_rowscale", "gemm_rowscale_swiglu", "gemm_residual_sumsq", "gemm_swiglu_bwd",
+    "gemm_rowscale", "gemm_rowscale_rope", "gemm_rowscale_swiglu", "gemm_residual_sumsq", "gemm_swiglu_bwd",
     "gemm_accumulate", "rmsnorm_linear_unfused", "rmsnorm_linear_reparam", "mlp_block",
     "fold_gamma", "interleave_pairs", "swiglu_fwd_points", "swiglu_bwd_points",
 ]
@@ -146,6 +146,25 @@ def gemm_rowscale(A, B, r=None, transA=False, transB=False, rows=None):
     _check(_load().coda_oracle_gemm_rowscale(
         _p(A), _i64(_ld(A)), _int(transA), _p(B), _i64(_ld(B)), _int(transB), _i64(M), _i64(N), _i64(K),
         _p(r), _p(rows), _i64(R), _p(O)))
+    return O
+
+
+def gemm_rowscale_rope(A, B, cos, sin, pos, head_dim, rope_cols, r=None, transA=False, transB=False, rows=None):
+    """Kernels 1 / 7: O = RoPE((op(A) op(B)) * r[:, None]) on adjacent pairs of the first rope_cols columns."""
+    A, B = _u16(A), _u16(B)
+    M, N, K = _mnk(A, transA, B, transB)
+    r = _f64(r, M)
+    cos = np.ascontiguousarray(cos, dtype=np.float32)
+    sin = np.ascontiguousarray(sin, dtype=np.float32)
+    assert cos.shape == sin.shape and cos.ndim == 2 and cos.shape[1] * 2 == head_dim
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    assert pos.shape == (M,)
+    rows, R = _rows(rows, M)
+    O = np.empty((R, N), np.float64)
+    _check(_load().coda_oracle_gemm_rowscale_rope(
+        _p(A), _i64(_ld(A)), _int(transA), _p(B), _i64(_ld(B)), _int(transB), _i64(M), _i64(N), _i64(K),
+        _p(r), _p(cos), _p(sin), _i64(cos.shape[0]), _p(pos), _i64(head_dim), _i64(rope_cols),
+        _p(rows), _i64(R), _p(O)))
     return O
 
 

@@ -28,7 +28,8 @@
  * chain (Section 3.2.1 identity); SwiGLU backward vs its closed-form derivative,
  * central finite differences and reverse-mode autodiff of the forward
  * definition; the row statistic vs sum(Z * dZ); the weight gradient vs finite
- * differences of <dY, H W>.  No function here is "parity unpinned".
+ * differences of <dY, H W>; RoPE vs complex multiplication by a library, norm preservation, the
+ * relative-position property and angle addition.  No function here is "parity unpinned".
  *
  * Naming: "row scale" multiplies row i by r[i]; "column scale" multiplies
  * column j by gamma[j]; a "row reduction" sums over columns and yields one
@@ -274,6 +275,54 @@ int coda_oracle_gemm_rowscale_swiglu(const uint16_t *A, int64_t lda, int transA,
         }
         if (Dp)
             memcpy(Dp + q * N, D + q * N, sizeof(double) * (size_t)N);
+    }
+    free(D);
+    return ORACLE_OK;
+}
+
+/*
+ * Kernels 1 and 7: D = A B,  D' = D (.) r (r == NULL: Kernel 1),  O = RoPE(D').
+ * RoPE acts on ADJACENT feature pairs of the output (columns 2p, 2p+1).  Row i has position q = pos[i]; the
+ * output is split into heads of head_dim columns and pair p uses frequency index f = p mod (head_dim/2):
+ *     O[i][2p]   = x0 * cos[q][f] - x1 * sin[q][f]
+ *     O[i][2p+1] = x0 * sin[q][f] + x1 * cos[q][f]          with (x0, x1) = (D'[i][2p], D'[i][2p+1]).
+ * Only the first rope_cols columns are rotated (query and key parts of a fused QKV projection); the remaining
+ * columns pass through unchanged.  cos / sin are precomputed fp32 tables [T x head_dim/2] given by the caller,
+ * so the oracle takes no position on how angles are generated.
+ */
+int coda_oracle_gemm_rowscale_rope(const uint16_t *A, int64_t lda, int transA, const uint16_t *B,
+                                   int64_t ldb, int transB, int64_t M, int64_t N, int64_t K,
+                                   const double *r, const float *cos_t, const float *sin_t, int64_t T,
+                                   const int32_t *pos, int64_t head_dim, int64_t rope_cols,
+                                   const int64_t *rows, int64_t nrows, double *O)
+{
+    if (!A || !B || !O || !cos_t || !sin_t || !pos || head_dim <= 0 || (head_dim & 1) || (rope_cols & 1) ||
+        rope_cols < 0 || rope_cols > N)
+        return ORACLE_ERR_ARG;
+    int64_t R = sel_count(rows, nrows, M);
+    int64_t half = head_dim / 2;
+    double *D = gemm_bf16(A, lda, transA, B, ldb, transB, N, K, rows, R);
+    if (!D)
+        return ORACLE_ERR_NOMEM;
+    for (int64_t q = 0; q < R; ++q) {
+        int64_t i = sel_row(rows, q);
+        double ri = r ? r[i] : 1.0;
+        int64_t t = pos[i];
+        if (t < 0 || t >= T) {
+            free(D);
+            return ORACLE_ERR_ARG;
+        }
+        for (int64_t j = 0; j < N; ++j)
+            D[q * N + j] *= ri;
+        for (int64_t j = 0; j < N; ++j)
+            O[q * N + j] = D[q * N + j];
+        for (int64_t p2 = 0; p2 < rope_cols / 2; ++p2) {
+            int64_t f = p2 % half;
+            double c = (double)cos_t[t * half + f], sn = (double)sin_t[t * half + f];
+            double x0 = D[q * N + 2 * p2], x1 = D[q * N + 2 * p2 + 1];
+            O[q * N + 2 * p2] = x0 * c - x1 * sn;
+            O[q * N + 2 * p2 + 1] = x0 * sn + x1 * c;
+        }
     }
     free(D);
     return ORACLE_OK;

@@ -94,6 +94,22 @@ def block_8b(seed=0, M=16384, d=4096, F=14336, n_qkv=6144, w_std=0.02):
     }
 
 
+def rope_tables(T, head_dim, base=10000.0):
+    """fp32 cos / sin tables [T x head_dim/2] for angles t * base^(-2f/head_dim) (input data for the RoPE
+    epilogue; the method itself only consumes the tables)."""
+    f = np.arange(head_dim // 2, dtype=np.float64)
+    ang = np.arange(T, dtype=np.float64)[:, None] * (base ** (-2.0 * f / head_dim))[None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
+def qkv_projection(seed=0, M=16384, K=4096, N=6144, w_std=0.02, seq_len=2048):
+    """Fused QKV projection input: X ~N(0,1) [M x K], W [K x N] ~N(0,w_std) (gamma folded), and the token
+    positions of M rows laid out as consecutive sequences of seq_len tokens."""
+    g = _rng(seed)
+    return {"X": normal_bf16(g, (M, K), 1.0), "W": normal_bf16(g, (K, N), w_std),
+            "pos": (np.arange(M) % seq_len).astype(np.int32)}
+
+
 def sample_rows(M, n, seed=0):
     """Deterministic row sample: tile-boundary rows plus a seeded draw, sorted and unique."""
     fixed = [r for r in (0, 1, 31, 32, 127, 128, 255, 256, M - 2, M - 1) if 0 <= r < M]

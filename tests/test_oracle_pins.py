@@ -363,3 +363,65 @@ def test_weight_preparation_definitions(oracle):
     assert np.array_equal(W[:, 0::2], Wa) and np.array_equal(W[:, 1::2], Wb)
     gamma = g.random(4) + 0.5
     np.testing.assert_allclose(oracle.fold_gamma(Wa, gamma), gamma[:, None] * wide(Wa), rtol=1e-15)
+
+
+# ---------------------------------------------------------------- RoPE (Kernels 1 and 7)
+def _rope_case(seed, M=9, K=6, heads=3, hd=8, extra=4, T=32):
+    g = rng(seed)
+    N = heads * hd + extra
+    A = synth.normal_bf16(g, (M, K), 1.0)
+    B = synth.normal_bf16(g, (K, N), 1.0)
+    pos = g.integers(0, T, size=M).astype(np.int32)
+    cos, sin = synth.rope_tables(T, hd)
+    return A, B, pos, cos, sin, hd, heads * hd, N
+
+
+def test_rope_vs_library_complex_multiplication(oracle):
+    A, B, pos, cos, sin, hd, rc, N = _rope_case(16)
+    got = oracle.gemm_rowscale_rope(A, B, cos, sin, pos, hd, rc)
+    D = torch.from_numpy(wide(A) @ wide(B))
+    z = torch.view_as_complex(D[:, :rc].reshape(len(pos), rc // hd, hd // 2, 2).contiguous())
+    w = torch.complex(torch.from_numpy(cos[pos].astype(np.float64)), torch.from_numpy(sin[pos].astype(np.float64)))
+    want = torch.view_as_real(z * w[:, None, :]).reshape(len(pos), rc)
+    np.testing.assert_allclose(got[:, :rc], want.numpy(), rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(got[:, rc:], D[:, rc:].numpy(), rtol=0, atol=0)          # pass-through columns
+
+
+def test_rope_invariants(oracle):
+    A, B, pos, cos, sin, hd, rc, N = _rope_case(17)
+    M = len(pos)
+    r = rng(18).random(M) + 0.5
+    plain = oracle.gemm_rowscale(A, B, r=r)
+    rot = oracle.gemm_rowscale_rope(A, B, cos, sin, pos, hd, rc, r=r)
+    # a rotation preserves the norm of every pair (cos/sin are fp32 table values: c^2+s^2 = 1 to ~1e-7)
+    n0 = plain[:, :rc].reshape(M, -1, 2)
+    n1 = rot[:, :rc].reshape(M, -1, 2)
+    np.testing.assert_allclose((n1 ** 2).sum(-1), (n0 ** 2).sum(-1), rtol=1e-6)
+    # position 0 is the identity
+    same = oracle.gemm_rowscale_rope(A, B, cos, sin, np.zeros(M, np.int32), hd, rc, r=r)
+    np.testing.assert_allclose(same, plain, rtol=0, atol=0)
+    # row selection and row scale indexed by the original row
+    sel = oracle.gemm_rowscale_rope(A, B, cos, sin, pos, hd, rc, r=r, rows=np.array([7, 2]))
+    np.testing.assert_allclose(sel, rot[[7, 2]], rtol=0, atol=0)
+    # the sign convention: one-hot x0 = 1 at angle theta gives (cos, +sin)
+    e = np.zeros((1, 2), np.float32); e[0, 0] = 1.0
+    I2 = bits(np.eye(2, dtype=np.float32))
+    c1, s1 = np.array([[0.6]], np.float32), np.array([[0.8]], np.float32)
+    out = oracle.gemm_rowscale_rope(bits(e), I2, c1, s1, np.zeros(1, np.int32), 2, 2)
+    np.testing.assert_allclose(out[0], [np.float32(0.6), np.float32(0.8)], rtol=1e-15)
+
+
+def test_rope_relative_position_property(oracle):
+    # <RoPE(q, m), RoPE(k, n)> depends on m - n only (exact-angle tables in fp64 would make this exact;
+    # with fp32 tables it holds to ~1e-6)
+    g = rng(19)
+    hd, T = 16, 64
+    cos, sin = synth.rope_tables(T, hd)
+    I = bits(np.eye(hd, dtype=np.float32))
+    q = synth.normal_bf16(g, (1, hd), 1.0); k = synth.normal_bf16(g, (1, hd), 1.0)
+    def dot(m, n):
+        a = oracle.gemm_rowscale_rope(q, I, cos, sin, np.array([m], np.int32), hd, hd)
+        b = oracle.gemm_rowscale_rope(k, I, cos, sin, np.array([n], np.int32), hd, hd)
+        return float((a * b).sum())
+    assert abs(dot(5, 2) - dot(23, 20)) < 1e-5 and abs(dot(40, 47) - dot(3, 10)) < 1e-5
+    assert abs(dot(5, 2) - dot(5, 3)) > 1e-3            # and it does depend on the offset
