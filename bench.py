@@ -35,10 +35,11 @@ MEASURED_TRAFFIC_BYTES = int(393581 * 1024 * 2.0 + 131075 * 1024)
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unfused", action="store_true")
+    ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (known traffic) so that rocprofv3 --pmc "
@@ -140,6 +141,39 @@ def main():
                      "achieved": round(kern_tflops["up"], 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(kern_tflops["up"] / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES},
     }
+
+    # ---- further GEMM+epilogue kernels measured on their own (not part of `value`) -----------------------------
+    def time_kernel(fn, reps=10, warm=3):
+        for _ in range(warm):
+            fn()
+        a, b = ev(), ev()
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    if not args.no_extras:
+        q = synth.qkv_projection(seed=3)
+        Xq, Wq = bf(q["X"]), bf(q["W"])
+        Mq, Kq, Nq = Xq.shape[0], Xq.shape[1], Wq.shape[1]
+        cos_h, sin_h = synth.rope_tables(2048, 128)
+        cos_d, sin_d, pos_d = torch.from_numpy(cos_h).to(dev), torch.from_numpy(sin_h).to(dev), torch.from_numpy(q["pos"]).to(dev)
+        rq = torch.rand(Mq, **f32) + 0.5
+        Q = torch.empty((Mq, Nq), **b16)
+        fl = 2.0 * Mq * Nq * Kq
+        f_rope = lambda: coda.coda_gemm(Xq, Wq, [coda.row_scale(rq), coda.rope(cos_d, sin_d, pos_d, 128, 5120), coda.store(Q)])
+        f_plain = lambda: coda.coda_gemm(Xq, Wq, [coda.store(Q)])
+        ms_rope, ms_plain = 1e9, 1e9
+        for _ in range(3):                      # alternate so that clock ramp / thermal drift hits both alike
+            ms_plain = min(ms_plain, time_kernel(f_plain))
+            ms_rope = min(ms_rope, time_kernel(f_rope))
+        out["extra_kernels"] = {
+            "qkv_8b_rowscale_rope": {"shape": [Mq, Nq, Kq], "ms": round(ms_rope, 4), "tflops": round(fl / ms_rope * 1e-9, 1)},
+            "qkv_8b_plain_store": {"shape": [Mq, Nq, Kq], "ms": round(ms_plain, 4), "tflops": round(fl / ms_plain * 1e-9, 1)}}
+        del Xq, Wq, Q
 
     # ---- unfused baseline: same mainloop with a plain store + separate elementwise kernels ---------------
     if not args.no_unfused:

@@ -102,7 +102,16 @@ typedef enum coda_epi_kind {
     CODA_EPI_STORE = 6,
     /* Final op: out[i][j] += v in fp32, in place (the weight-gradient GEMM of
        Theorem 1 accumulated into an existing gradient buffer). out: f32[M x N].       */
-    CODA_EPI_ACCUM_F32 = 7
+    CODA_EPI_ACCUM_F32 = 7,
+    /* Pairwise, width unchanged (Kernels 1, 7: O = RoPE(D)): rotate adjacent column pairs
+       (2p, 2p+1) of the first i1 = rope_cols columns by the angle of (position of row i,
+       frequency f = p mod (head_dim/2)):  v'[2p] = x0*cos - x1*sin,  v'[2p+1] = x0*sin + x1*cos.
+       in: f32 cos table [T x head_dim/2] (dense), in2: f32 sin table (same shape),
+       in3: int32 pos[M] with 0 <= pos < T (not checked), i0 = head_dim (multiple of 8),
+       i1 = rope_cols (multiple of 8, <= N), ld_in = T.  Columns >= rope_cols pass through.
+       The paper pre-broadcasts the tables to [M x N/2]; indexing a [T x head_dim/2] table by
+       position gives the same values without that input traffic.                       */
+    CODA_EPI_ROPE = 8
 } coda_epi_kind;
 
 #define CODA_REDUCE_PARTIALS 0u
@@ -116,6 +125,9 @@ typedef struct coda_epi_op {
     void *out;      /* device */
     void *out2;     /* device */
     int64_t ld_in, ld_out;
+    const void *in2; /* device; second / third input of ops that take several (ROPE) */
+    const void *in3; /* device */
+    int64_t i0, i1;  /* integer parameters of the op (ROPE: head_dim, rope_cols) */
 } coda_epi_op;
 
 /*
@@ -124,11 +136,12 @@ typedef struct coda_epi_op {
  * Supported programs (anything else -> CODA_ERR_PROGRAM): ops must appear in
  * the order
  *     [ROW_SCALE] [ADD_TILE] [ROW_SUMSQ] [COL_SCALE_SIDE] STORE
+ *     [ROW_SCALE] ROPE STORE
  *     [ROW_SCALE] SWIGLU_FWD STORE
  *     SWIGLU_BWD STORE
  *     ACCUM_F32
- * with bracketed ops optional and each at most once.  These cover Kernels 2, 4,
- * 5, 6, 10, the plain GEMM (STORE alone) and the accumulating weight gradient.
+ * with bracketed ops optional and each at most once.  These cover Kernels 1, 2, 4,
+ * 5, 6, 7, 10, the plain GEMM (STORE alone) and the accumulating weight gradient.
  *
  * Sizes: M, N, K >= 0 must equal the op() shapes of A and B.  M == 0 or N == 0
  * is a no-op; K == 0 runs the program on D = 0.  K must be a multiple of 8; N a

@@ -23,7 +23,7 @@ CODA_OK, CODA_ERR_NULL, CODA_ERR_SHAPE, CODA_ERR_ALIGN, CODA_ERR_DTYPE, CODA_ERR
     CODA_ERR_WORKSPACE, CODA_ERR_LAUNCH = range(8)
 CODA_BF16, CODA_F32 = 0, 1
 (CODA_EPI_ROW_SCALE, CODA_EPI_COL_SCALE_SIDE, CODA_EPI_ADD_TILE, CODA_EPI_SWIGLU_FWD, CODA_EPI_SWIGLU_BWD,
- CODA_EPI_ROW_SUMSQ, CODA_EPI_STORE, CODA_EPI_ACCUM_F32) = range(8)
+ CODA_EPI_ROW_SUMSQ, CODA_EPI_STORE, CODA_EPI_ACCUM_F32, CODA_EPI_ROPE) = range(9)
 CODA_REDUCE_PARTIALS, CODA_REDUCE_ATOMIC, CODA_STORE_F32 = 0, 1, 2
 
 EXPORTS = ["coda_gemm", "coda_gemm_workspace_bytes", "coda_row_partial_blocks", "coda_row_finalize",
@@ -41,7 +41,8 @@ class coda_mat(ctypes.Structure):
 class coda_epi_op(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("flags", ctypes.c_uint32), ("in_", ctypes.c_void_p),
                 ("out", ctypes.c_void_p), ("out2", ctypes.c_void_p), ("ld_in", ctypes.c_int64),
-                ("ld_out", ctypes.c_int64)]
+                ("ld_out", ctypes.c_int64), ("in2", ctypes.c_void_p), ("in3", ctypes.c_void_p),
+                ("i0", ctypes.c_int64), ("i1", ctypes.c_int64)]
 
 
 _vp, _i64, _i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
@@ -113,8 +114,8 @@ def mat(t, trans=False):
     return coda_mat(t.data_ptr(), t.shape[0], t.shape[1], t.stride(0), 1 if trans else 0, dt)
 
 
-def _op(kind, flags=0, in_=None, out=None, out2=None):
-    return coda_epi_op(kind, flags, _ptr(in_), _ptr(out), _ptr(out2), _ld(in_), _ld(out))
+def _op(kind, flags=0, in_=None, out=None, out2=None, in2=None, in3=None, i0=0, i1=0):
+    return coda_epi_op(kind, flags, _ptr(in_), _ptr(out), _ptr(out2), _ld(in_), _ld(out), _ptr(in2), _ptr(in3), i0, i1)
 
 
 # --- epilogue op constructors (keep the tensors alive until the call returns) ----------------
@@ -124,6 +125,11 @@ def row_scale(r):
 
 def col_scale_side(gamma, out):
     return _op(CODA_EPI_COL_SCALE_SIDE, in_=gamma, out=out)
+
+
+def rope(cos, sin, pos, head_dim, rope_cols):
+    """cos / sin: f32 [T x head_dim/2] dense tables; pos: int32 [M]."""
+    return _op(CODA_EPI_ROPE, in_=cos, in2=sin, in3=pos, i0=head_dim, i1=rope_cols)
 
 
 def add_tile(C):

@@ -51,7 +51,7 @@ struct Parsed {
     coda::GemmParams p{};
 };
 
-// Canonical order: ROW_SCALE < ADD_TILE < ROW_SUMSQ < COL_SCALE_SIDE < final.
+// Canonical order: ROW_SCALE < ADD_TILE < ROW_SUMSQ < COL_SCALE_SIDE < final; ROPE only between ROW_SCALE and STORE.
 coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Parsed &out)
 {
     if (n_ops < 0 || (n_ops > 0 && !prog)) return CODA_ERR_NULL;
@@ -71,6 +71,21 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
             p.row_scale = static_cast<const float *>(op.in);
             stage = 1;
             break;
+        case CODA_EPI_ROPE:
+            if (stage > 1 || pair) return CODA_ERR_PROGRAM;
+            if ((st = check_vec(op.in)) != CODA_OK || (st = check_vec(op.in2)) != CODA_OK || (st = check_vec(op.in3)) != CODA_OK)
+                return st;
+            if ((reinterpret_cast<uintptr_t>(op.in) & 7u) || (reinterpret_cast<uintptr_t>(op.in2) & 7u)) return CODA_ERR_ALIGN;
+            if (op.i0 <= 0 || (op.i0 & 7) || op.i0 > INT32_MAX || op.i1 < 0 || (op.i1 & 7) || op.i1 > N || op.ld_in <= 0)
+                return CODA_ERR_SHAPE;
+            p.rope_cos = static_cast<const float *>(op.in);
+            p.rope_sin = static_cast<const float *>(op.in2);
+            p.rope_pos = static_cast<const int *>(op.in3);
+            p.rope_half = (int)(op.i0 / 2);
+            p.rope_cols = (int)op.i1;
+            stage = 4;          // only STORE may follow
+            linear_only = true;
+            break;
         case CODA_EPI_ADD_TILE:
             if (stage > 1 || pair) return CODA_ERR_PROGRAM;
             if ((st = check_tile(op.in, op.ld_in, N)) != CODA_OK) return st;
@@ -89,7 +104,7 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
             linear_only = true;
             break;
         case CODA_EPI_COL_SCALE_SIDE:
-            if (stage > 3 || pair) return CODA_ERR_PROGRAM;
+            if (stage > 3 || pair || p.rope_cos) return CODA_ERR_PROGRAM;
             if ((st = check_vec(op.in)) != CODA_OK) return st;
             if (!aligned16(op.in)) return CODA_ERR_ALIGN;
             if ((st = check_tile(op.out, op.ld_out, N)) != CODA_OK) return st;

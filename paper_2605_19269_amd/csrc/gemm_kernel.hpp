@@ -56,6 +56,9 @@ struct GemmParams {
     void *out; int64_t ld_out; int out_f32;
     const uint16_t *Z; int64_t ldz;      // SWIGLU_BWD saved pre-activation [M x 2N]
     uint16_t *out2; int64_t ld_out2;     // SWIGLU_FWD: pre-activation; SWIGLU_BWD: silu(g)*u
+    const float *rope_cos, *rope_sin;    // f32 [T x rope_half] tables (linear mode; null = no rotation)
+    const int *rope_pos;                 // int32 [M]
+    int rope_half, rope_cols;            // head_dim / 2 (multiple of 4); leading columns that are rotated
 };
 
 // ---------------------------------------------------------------------------------
@@ -314,6 +317,16 @@ __device__ __forceinline__ void stage_fence()
     __builtin_amdgcn_sched_barrier(0);
 }
 
+// RoPE on the two adjacent pairs held in one unit (columns n..n+3): pair frequencies f and f+1 of position row `trow`.
+__device__ __forceinline__ void rope_unit(f32x4 &v, const GemmParams &p, int64_t trow, int f)
+{
+    const f32x2 c = *reinterpret_cast<const f32x2 *>(p.rope_cos + trow + f);
+    const f32x2 s = *reinterpret_cast<const f32x2 *>(p.rope_sin + trow + f);
+    const float a0 = v[0] * c[0] - v[1] * s[0], a1 = v[0] * s[0] + v[1] * c[0];
+    const float b0 = v[2] * c[1] - v[3] * s[1], b1 = v[2] * s[1] + v[3] * c[1];
+    v = f32x4{a0, a1, b0, b1};
+}
+
 constexpr int pass_rows(int reg_bytes, int row_bytes, int max_rows)
 {
     int p = 32;
@@ -469,6 +482,64 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
                 stage_fence();
             }
         }
+    } else if (EPI == EPI_LINEAR && !p.out_f32 && p.rope_cos && WTN == 64 && (p.rope_half & 31) == 0) {
+        // ---- row scale, RoPE, bf16 store with the cos / sin rows staged like tiles: per 32-row block the wave gathers
+        // each token's 32 table entries (128 bytes of cos, 128 of sin; the wave's 64 columns are 32 consecutive pairs
+        // inside one head because head_dim/2 is a multiple of 32) with row-contiguous 16-byte loads into its region,
+        // so the per-unit table reads come from LDS instead of 8-byte gathers from 32 different rows.
+        constexpr int RB = 128;
+        using St = Stage<RB>;
+        const uint32_t ulane = St::template unit_lane<8>(lane);
+        const uint32_t rlane = St::row_lane(lane);
+        const int f0 = (nw >> 1) % p.rope_half;                        // first frequency index of this wave's columns
+        unsigned char *rcos = reg + 32 * RB, *rsin = reg + 64 * RB;
+        uint16_t *outp = reinterpret_cast<uint16_t *>(p.out);
+        u32x4 tc[4], ts[4];
+        auto gather = [&](int i) {                                     // table slices of 32-row block i -> registers
+            const int m = mw + i * 32 + lrow;
+            const int trow = (!EDGE || m < p.M) ? p.rope_pos[m] * p.rope_half + f0 : f0;
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {                           // 8 rows x 128 bytes per access
+                const int src = __shfl(trow, it * 8 + (lane >> 3), 64) + (lane & 7) * 4;
+                tc[it] = *reinterpret_cast<const u32x4 *>(p.rope_cos + src);
+                ts[it] = *reinterpret_cast<const u32x4 *>(p.rope_sin + src);
+            }
+        };
+        gather(0);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int m = mw + i * 32 + lrow;
+            const bool mok = !EDGE || m < p.M;
+            const float rs = p.row_scale ? (mok ? p.row_scale[m] : 0.0f) : 1.0f;
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                *reinterpret_cast<u32x4 *>(rcos + St::row_addr(rlane, it)) = tc[it];
+                *reinterpret_cast<u32x4 *>(rsin + St::row_addr(rlane, it)) = ts[it];
+            }
+            stage_fence();
+            if (i + 1 < FM) gather(i + 1);                             // in flight under this block's math and stores
+            stage_fence();
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int nl = j * 32 + g * 8 + lhalf * 4;
+                    const uint32_t ua = St::unit_addr(ulane, 0, (j * 32 + g * 8) * 2);
+                    f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                    v *= rs;
+                    if (nw + nl < p.rope_cols) {
+                        const f32x2 c = *reinterpret_cast<const f32x2 *>(rcos + ua);
+                        const f32x2 sn = *reinterpret_cast<const f32x2 *>(rsin + ua);
+                        v = f32x4{v[0] * c[0] - v[1] * sn[0], v[0] * sn[0] + v[1] * c[0],
+                                  v[2] * c[1] - v[3] * sn[1], v[2] * sn[1] + v[3] * c[1]};
+                    }
+                    *reinterpret_cast<u32x2 *>(reg + ua) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+                }
+            stage_fence();
+            stage_store<RB, 32, EDGE>(reg, reinterpret_cast<unsigned char *>(outp + (int64_t)(mw + i * 32) * p.ld_out + nw), p.ld_out * 2,
+                                      rows_ok - i * 32, cols_ok * 2, lane);
+            stage_fence();
+        }
     } else if (EPI == EPI_LINEAR && !p.out_f32) {
         // ---- row scale, residual add, row sum of squares, bf16 store: all tile I/O staged.  The gamma-scaled side
         // output (when requested) is a second sweep that re-reads the residual and recomputes the value, so that
@@ -493,6 +564,10 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
                     const int i = ps * FPP + fi, m = mw + i * 32 + lrow;
                     const bool mok = !EDGE || m < p.M;
                     const float rs = p.row_scale ? (mok ? p.row_scale[m] : 0.0f) : 1.0f;
+                    // RoPE: table row of this token and the frequency index of the lane's first pair; units follow each
+                    // other 4 pairs apart and rope_half is a multiple of 4, so the index wraps at most once per step
+                    const int64_t trow = (p.rope_cos && mok) ? (int64_t)p.rope_pos[m] * p.rope_half : 0;
+                    int rf = p.rope_cos ? ((nw + lhalf * 4) >> 1) % p.rope_half : 0;
 #pragma unroll
                     for (int j = 0; j < FN; ++j)
 #pragma unroll
@@ -501,6 +576,11 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
                             const bool ok = mok && (!EDGE || nw + nl < p.N);
                             f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
                             v *= rs;
+                            if (p.rope_cos) {
+                                if (ok && nw + nl < p.rope_cols) rope_unit(v, p, trow, rf);
+                                rf += 4;
+                                if (rf >= p.rope_half) rf -= p.rope_half;
+                            }
                             u32x2 *slot = reinterpret_cast<u32x2 *>(reg + Stage<RB>::unit_addr(ulane, fi, (j * 32 + g * 8) * 2));
                             if (p.add) {
                                 const u32x2 c = *slot;
@@ -537,6 +617,9 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
             const bool mok = !EDGE || m < p.M;
             float rs = 1.0f;
             if (EPI == EPI_LINEAR && p.row_scale) rs = mok ? p.row_scale[m] : 0.0f;
+            const bool rope = EPI == EPI_LINEAR && p.rope_cos;
+            const int64_t trow = (rope && mok) ? (int64_t)p.rope_pos[m] * p.rope_half : 0;
+            int rf = rope ? ((nw + lhalf * 4) >> 1) % p.rope_half : 0;
 #pragma unroll
             for (int j = 0; j < FN; ++j)
 #pragma unroll
@@ -547,6 +630,11 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
                     float *gp = reinterpret_cast<float *>(p.out) + (int64_t)m * p.ld_out + n;
                     if (EPI == EPI_LINEAR) {
                         v *= rs;
+                        if (rope) {
+                            if (ok && n < p.rope_cols) rope_unit(v, p, trow, rf);
+                            rf += 4;
+                            if (rf >= p.rope_half) rf -= p.rope_half;
+                        }
                         if (p.add && ok) {
                             const u32x2 c = *reinterpret_cast<const u32x2 *>(p.add + (int64_t)m * p.ld_add + n);
                             v[0] += bf16_lo(c[0]); v[1] += bf16_hi(c[0]);

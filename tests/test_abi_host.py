@@ -36,18 +36,18 @@ def test_binding_mirrors_header_enums(coda):
     for name in ["CODA_OK", "CODA_ERR_NULL", "CODA_ERR_SHAPE", "CODA_ERR_ALIGN", "CODA_ERR_DTYPE", "CODA_ERR_PROGRAM",
                  "CODA_ERR_WORKSPACE", "CODA_ERR_LAUNCH", "CODA_EPI_ROW_SCALE", "CODA_EPI_COL_SCALE_SIDE",
                  "CODA_EPI_ADD_TILE", "CODA_EPI_SWIGLU_FWD", "CODA_EPI_SWIGLU_BWD", "CODA_EPI_ROW_SUMSQ",
-                 "CODA_EPI_STORE", "CODA_EPI_ACCUM_F32"]:
+                 "CODA_EPI_STORE", "CODA_EPI_ACCUM_F32", "CODA_EPI_ROPE"]:
         m = re.search(r"\b%s\s*=\s*(\d+)" % name, text)
         assert m and int(m.group(1)) == getattr(coda, name), name
-    assert ctypes.sizeof(coda.coda_mat) == 40 and ctypes.sizeof(coda.coda_epi_op) == 48
+    assert ctypes.sizeof(coda.coda_mat) == 40 and ctypes.sizeof(coda.coda_epi_op) == 80
 
 
 def _mat(coda, ptr, rows, cols, ld=None, trans=0, dtype=0):
     return coda.coda_mat(ptr, rows, cols, ld if ld is not None else cols, trans, dtype)
 
 
-def _op(coda, kind, flags=0, in_=None, out=None, out2=None, ld_in=0, ld_out=0):
-    return coda.coda_epi_op(kind, flags, in_, out, out2, ld_in, ld_out)
+def _op(coda, kind, flags=0, in_=None, out=None, out2=None, ld_in=0, ld_out=0, in2=None, in3=None, i0=0, i1=0):
+    return coda.coda_epi_op(kind, flags, in_, out, out2, ld_in, ld_out, in2, in3, i0, i1)
 
 
 P = 0x1000  # a fake, 16-byte aligned "device pointer"; no call below ever reaches a launch
@@ -107,6 +107,13 @@ def test_program_grammar(coda):
     assert g([fwd, _op(coda, coda.CODA_EPI_STORE, flags=coda.CODA_STORE_F32, out=P, ld_out=32)]) == BAD
     assert g([bwd, st]) == coda.CODA_ERR_SHAPE     # store narrower than the widened output
     assert g([_op(coda, coda.CODA_EPI_ROW_SUMSQ, flags=7, out=P), st]) == BAD
+    rope = _op(coda, coda.CODA_EPI_ROPE, in_=P, in2=P, in3=P, ld_in=128, i0=16, i1=32)
+    assert g([rope, st]) == OK and g([rs, rope, st]) == OK
+    assert g([rope, add, st]) == BAD and g([add, rope, st]) == BAD and g([rope, fwd, st_half]) == BAD
+    assert g([rope, side, st]) == BAD and g([rope, rs, st]) == BAD
+    assert g([_op(coda, coda.CODA_EPI_ROPE, in_=P, in2=P, in3=P, ld_in=128, i0=12, i1=32), st]) == coda.CODA_ERR_SHAPE
+    assert g([_op(coda, coda.CODA_EPI_ROPE, in_=P, in2=P, in3=P, ld_in=128, i0=16, i1=72), st]) == coda.CODA_ERR_SHAPE
+    assert g([_op(coda, coda.CODA_EPI_ROPE, in_=P, in2=None, in3=P, ld_in=128, i0=16, i1=32), st]) == coda.CODA_ERR_NULL
 
 
 def test_aux_argument_errors(coda):

@@ -109,6 +109,15 @@ def test_llama8b_block_shapes(oracle):
     coda.coda_gemm(X, G.dev_bf16(c["Wqkv"]), [coda.row_scale(r), coda.store(Q)])
     torch.cuda.synchronize()
     G.assert_bf16_close(rows_of(Q, rows), oracle.gemm_rowscale(c["X"], c["Wqkv"], r=r_host, rows=rows), "8B qkv")
+    # the same projection with RoPE on the query and key heads (32 + 8 heads of 128; value heads pass through)
+    hd, rc, T = 128, 5120, 2048
+    cos, sin = synth.rope_tables(T, hd)
+    pos = (np.arange(M) % T).astype(np.int32)
+    dcos, dsin, dpos = G.dev_f32(cos), G.dev_f32(sin), torch.from_numpy(pos).cuda()
+    coda.coda_gemm(X, G.dev_bf16(c["Wqkv"]), [coda.row_scale(r), coda.rope(dcos, dsin, dpos, hd, rc), coda.store(Q)])
+    torch.cuda.synchronize()
+    G.assert_bf16_close(rows_of(Q, rows), oracle.gemm_rowscale_rope(c["X"], c["Wqkv"], cos, sin, pos, hd, rc, r=r_host, rows=rows),
+                        "8B qkv + rope")
     del Q
     global NSAMPLE
     keep, NSAMPLE = NSAMPLE, 32

@@ -347,3 +347,27 @@ def test_unfused_baseline_kernels(oracle):
     G.assert_sumsq_close(G.host_f64(ss), refss, "unfused sumsq")
     G.assert_bf16_close(G.host_f64(Xn.t), refXn, "unfused rmsnorm apply")
     assert np.array_equal(Gd.cpu().numpy(), G0 + T)          # one fp32 add: bit-exact
+
+
+@pytest.mark.parametrize("M,N,K,hd,rc", [(512, 768, 128, 64, 512), (520, 776, 200, 16, 768), (256, 256, 64, 128, 256)])
+@pytest.mark.parametrize("with_r,f32", [(True, False), (False, False), (True, True)])
+def test_kernel7_rope(oracle, M, N, K, hd, rc, with_r, f32):
+    """Kernels 1 / 7: row scale, RoPE on adjacent pairs of the first rc columns, store."""
+    g = rng(61)
+    A, B = operands(g, M, N, K, False, False, b_std=0.2)
+    T = 96
+    cos, sin = synth.rope_tables(T, hd)
+    pos = g.integers(0, T, size=M).astype(np.int32)
+    r = synth.uniform_f32(g, (M,), 0.5, 1.5) if with_r else None
+    out = G.Guarded(M, N, torch.float32 if f32 else torch.bfloat16)
+    dcos, dsin, dpos = G.dev_f32(cos), G.dev_f32(sin), torch.from_numpy(pos).cuda()
+    ops = ([coda.row_scale(dr := G.dev_f32(r))] if with_r else []) + \
+          [coda.rope(dcos, dsin, dpos, hd, rc), coda.store(out.t, f32=f32)]
+    coda.coda_gemm(G.dev_bf16(A), G.dev_bf16(B), ops)
+    torch.cuda.synchronize()
+    ref = oracle.gemm_rowscale_rope(A, B, cos, sin, pos, hd, rc, r=None if r is None else r.astype(np.float64))
+    out.check_guards(); out.written()
+    if f32:
+        G.assert_f32_signed_close(G.host_f64(out.t), ref, "rope f32")
+    else:
+        G.assert_bf16_close(G.host_f64(out.t), ref, "rope")
