@@ -443,7 +443,7 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
                             const float sg = fast_sigmoid(gg), sl = gg * sg;
                             const float dU = d * sl, dG = d * uu * (sg + sl * (1.0f - sg));
                             dz[e] = pack_bf16x2(dG, dU);
-                            if (ok) rsum[i] += gg * dG + uu * dU;
+                            if (want_red && ok) rsum[i] += gg * dG + uu * dU;
                         }
                         *slot = dz;
                         asm volatile("" : "+v"(rsum[i]));   // keep the row statistic's add chain in place (see above)
