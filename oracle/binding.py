@@ -18,7 +18,7 @@ _lib = None
 __all__ = [
     "build", "lib_path", "num_threads", "bf16_bits_to_f64", "row_sumsq", "rstd", "rstd_from_sumsq",
     "gemm_rowscale", "gemm_rowscale_rope", "gemm_rowscale_swiglu", "gemm_residual_sumsq", "gemm_swiglu_bwd",
-    "gemm_accumulate", "rmsnorm_linear_unfused", "rmsnorm_linear_reparam", "mlp_block",
+    "gemm_accumulate", "gemm_rmsnorm_bwd", "rmsnorm_linear_unfused", "rmsnorm_linear_reparam", "mlp_block",
     "fold_gamma", "interleave_pairs", "swiglu_fwd_points", "swiglu_bwd_points",
 ]
 
@@ -230,6 +230,26 @@ def gemm_accumulate(A, B, Gin=None, transA=False, transB=False, rows=None):
         _p(A), _i64(_ld(A)), _int(transA), _p(B), _i64(_ld(B)), _int(transB), _i64(M), _i64(N), _i64(K),
         _p(Gin), _i64(_ld(Gin) if Gin is not None else 0), _p(rows), _i64(R), _p(G)))
     return G
+
+
+def gemm_rmsnorm_bwd(A, B, C, r, z, gamma, Oin=None, transA=False, transB=False, rows=None):
+    """Kernel 9: returns (O_out [R x N], C_out [R x N], dgamma [N] summed over the selected rows)."""
+    A, B, C = _u16(A), _u16(B), _u16(C)
+    M, N, K = _mnk(A, transA, B, transB)
+    assert C.shape == (M, N)
+    r, z, gamma = _f64(r, M), _f64(z, M), _f64(gamma, N)
+    if Oin is not None:
+        Oin = _u16(Oin)
+        assert Oin.shape == (M, N)
+    rows, R = _rows(rows, M)
+    Oout = np.empty((R, N), np.float64)
+    Cout = np.empty((R, N), np.float64)
+    dg = np.empty(N, np.float64)
+    _check(_load().coda_oracle_gemm_rmsnorm_bwd(
+        _p(A), _i64(_ld(A)), _int(transA), _p(B), _i64(_ld(B)), _int(transB), _i64(M), _i64(N), _i64(K),
+        _p(C), _i64(_ld(C)), _p(r), _p(z), _p(gamma), _p(Oin), _i64(_ld(Oin) if Oin is not None else 0),
+        _p(rows), _i64(R), _p(Oout), _p(Cout), _p(dg)))
+    return Oout, Cout, dg
 
 
 def _rms_linear(fn, X, gamma, eps, W, R, transW, rows):

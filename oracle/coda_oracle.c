@@ -29,7 +29,7 @@
  * central finite differences and reverse-mode autodiff of the forward
  * definition; the row statistic vs sum(Z * dZ); the weight gradient vs finite
  * differences of <dY, H W>; RoPE vs complex multiplication by a library, norm preservation, the
- * relative-position property and angle addition.  No function here is "parity unpinned".
+ * relative-position property; the RMSNorm-backward kernel vs reverse-mode autodiff of a library RMSNorm.  No function here is "parity unpinned".
  *
  * Naming: "row scale" multiplies row i by r[i]; "column scale" multiplies
  * column j by gamma[j]; a "row reduction" sums over columns and yields one
@@ -405,6 +405,51 @@ int coda_oracle_gemm_swiglu_bwd(const uint16_t *A, int64_t lda, int transA, cons
         }
         if (stat)
             stat[q] = s;
+    }
+    free(D);
+    return ORACLE_OK;
+}
+
+/*
+ * Kernel 9 (local part of RMSNorm backward).  D = op(A) op(B) is the gradient w.r.t. the normalised activation;
+ * C [M x N] bf16 is the RMSNorm input, r [M] its inverse-RMS factor, gamma [N] the RMSNorm weight and z [M] the
+ * row statistic z_i = (1/d) sum_j (grad_h2 * h2)[i][j] delivered by the following pattern's epilogue:
+ *     C_norm = C (.) r
+ *     O_out  = O_in + ( D (.) gamma - C_norm (.) z ) (.) r          (O_in optional, bf16 [M x N])
+ *     C_out  = C_norm (.) gamma                                      (optional: the recomputed normalised activation)
+ *     dgamma[j] = sum over the SELECTED rows i of D[i][j] * C_norm[i][j]
+ * (with rows == NULL this is the full reduceTile_rows + reduce_rows of the paper; a row subset gives the partial
+ * sum over that subset, which is what one tile row contributes).
+ */
+int coda_oracle_gemm_rmsnorm_bwd(const uint16_t *A, int64_t lda, int transA, const uint16_t *B, int64_t ldb,
+                                 int transB, int64_t M, int64_t N, int64_t K, const uint16_t *C, int64_t ldc,
+                                 const double *r, const double *z, const double *gamma, const uint16_t *Oin,
+                                 int64_t ldo, const int64_t *rows, int64_t nrows, double *Oout, double *Cout,
+                                 double *dgamma)
+{
+    if (!A || !B || !C || !r || !z || !gamma || !Oout)
+        return ORACLE_ERR_ARG;
+    int64_t R = sel_count(rows, nrows, M);
+    double *D = gemm_bf16(A, lda, transA, B, ldb, transB, N, K, rows, R);
+    if (!D)
+        return ORACLE_ERR_NOMEM;
+    if (dgamma)
+        for (int64_t j = 0; j < N; ++j)
+            dgamma[j] = 0.0;
+    for (int64_t q = 0; q < R; ++q) {
+        int64_t i = sel_row(rows, q);
+        for (int64_t j = 0; j < N; ++j) {
+            double d = D[q * N + j];
+            double cn = bf16_widen(C[i * ldc + j]) * r[i];
+            double o = (d * gamma[j] - cn * z[i]) * r[i];
+            if (Oin)
+                o += bf16_widen(Oin[i * ldo + j]);
+            Oout[q * N + j] = o;
+            if (Cout)
+                Cout[q * N + j] = cn * gamma[j];
+            if (dgamma)
+                dgamma[j] += d * cn;
+        }
     }
     free(D);
     return ORACLE_OK;

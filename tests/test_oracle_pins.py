@@ -425,3 +425,46 @@ def test_rope_relative_position_property(oracle):
         return float((a * b).sum())
     assert abs(dot(5, 2) - dot(23, 20)) < 1e-5 and abs(dot(40, 47) - dot(3, 10)) < 1e-5
     assert abs(dot(5, 2) - dot(5, 3)) > 1e-3            # and it does depend on the offset
+
+
+# ---------------------------------------------------------------- RMSNorm backward (Kernel 9)
+def test_kernel9_vs_autodiff_of_library_rmsnorm(oracle):
+    g = rng(20)
+    M, d = 7, 24
+    h1 = synth.normal_bf16(g, (M, d), 1.0)
+    G2 = synth.normal_bf16(g, (M, d), 1.0)            # gradient w.r.t. the normalised activation
+    Oin = synth.normal_bf16(g, (M, d), 1.0)
+    gamma = g.random(d) + 0.5
+    eps = 1e-6
+    I = bits(np.eye(d, dtype=np.float32))
+    th = torch.tensor(wide(h1), requires_grad=True)
+    tg = torch.tensor(gamma, requires_grad=True)
+    h2 = torch.nn.functional.rms_norm(th, (d,), weight=tg, eps=eps)
+    (h2 * torch.from_numpy(wide(G2))).sum().backward()
+    r = oracle.rstd(h1, eps)
+    z = (wide(G2) * h2.detach().numpy()).sum(1) / d      # the row statistic, from the library's h2
+    Oout, Cout, dg = oracle.gemm_rmsnorm_bwd(G2, I, h1, r, z, gamma, Oin=Oin)
+    np.testing.assert_allclose(Oout - wide(Oin), th.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(dg, tg.grad.numpy(), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(Cout, h2.detach().numpy(), rtol=1e-13, atol=1e-15)
+    O2, _, dg2 = oracle.gemm_rmsnorm_bwd(G2, I, h1, r, z, gamma, rows=np.array([5, 1]))
+    np.testing.assert_allclose(O2, (Oout - wide(Oin))[[5, 1]], rtol=1e-13, atol=1e-14)
+    want = (wide(G2) * wide(h1) * r[:, None])[[5, 1]].sum(0)
+    np.testing.assert_allclose(dg2, want, rtol=1e-13, atol=1e-14)
+
+
+def test_kernel9_uses_the_gemm_result_with_transposed_weight(oracle):
+    # D = grad_y W1^T: against an end-to-end autodiff through RMSNorm -> Linear
+    g = rng(21)
+    M, d, N = 6, 16, 10
+    h1 = synth.normal_bf16(g, (M, d), 1.0)
+    W1 = synth.normal_bf16(g, (d, N), 0.3)
+    gy = synth.normal_bf16(g, (M, N), 1.0)
+    gamma = g.random(d) + 0.5
+    th = torch.tensor(wide(h1), requires_grad=True)
+    y = torch.nn.functional.rms_norm(th, (d,), weight=torch.from_numpy(gamma), eps=1e-6) @ torch.from_numpy(wide(W1))
+    (y * torch.from_numpy(wide(gy))).sum().backward()
+    r = oracle.rstd(h1, 1e-6)
+    z = (wide(gy) * y.detach().numpy()).sum(1) / d        # statistic taken AFTER the GEMM (Section 3.2.4 identity)
+    Oout, _, _ = oracle.gemm_rmsnorm_bwd(gy, W1, h1, r, z, gamma, transB=True)
+    np.testing.assert_allclose(Oout, th.grad.numpy(), rtol=1e-10, atol=1e-12)
