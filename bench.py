@@ -174,6 +174,27 @@ def main():
             "qkv_8b_rowscale_rope": {"shape": [Mq, Nq, Kq], "ms": round(ms_rope, 4), "tflops": round(fl / ms_rope * 1e-9, 1)},
             "qkv_8b_plain_store": {"shape": [Mq, Nq, Kq], "ms": round(ms_plain, 4), "tflops": round(fl / ms_plain * 1e-9, 1)}}
         del Xq, Wq, Q
+        # Kernel 9 at the backward shape of the same projection: dY[M x 6144] Wqkv^T with RMSNorm backward,
+        # residual-gradient accumulation, recomputed normalised activation and dgamma partials
+        Mb, Nb, Kb = 16384, 4096, 6144
+        dYq = (torch.randn((Mb, Kb), device=dev) * 1e-2).to(torch.bfloat16)
+        Wt = (torch.randn((Nb, Kb), device=dev) * 0.02).to(torch.bfloat16)
+        Cq = torch.randn((Mb, Nb), device=dev).to(torch.bfloat16)
+        Oi = torch.randn((Mb, Nb), device=dev).to(torch.bfloat16)
+        rr, zz, gg = torch.rand(Mb, **f32) + 0.5, torch.randn(Mb, **f32) * 1e-3, torch.rand(Nb, **f32) + 0.5
+        Oo, Co = torch.empty((Mb, Nb), **b16), torch.empty((Mb, Nb), **b16)
+        pb = torch.empty((coda.coda_col_partial_blocks(Mb), Nb), **f32)
+        flb = 2.0 * Mb * Nb * Kb
+        f_k9 = lambda: coda.coda_gemm(dYq, Wt, [coda.rmsnorm_bwd(Cq, rr, zz, gg, c_out=Co, dgamma_out=pb), coda.add_tile(Oi),
+                                               coda.store(Oo)], transB=True)
+        f_pl = lambda: coda.coda_gemm(dYq, Wt, [coda.store(Oo)], transB=True)
+        ms_k9, ms_pl = 1e9, 1e9
+        for _ in range(3):
+            ms_pl = min(ms_pl, time_kernel(f_pl))
+            ms_k9 = min(ms_k9, time_kernel(f_k9))
+        out["extra_kernels"]["qkv_bwd_8b_rmsnorm_backward"] = {"shape": [Mb, Nb, Kb], "ms": round(ms_k9, 4), "tflops": round(flb / ms_k9 * 1e-9, 1)}
+        out["extra_kernels"]["qkv_bwd_8b_plain_store"] = {"shape": [Mb, Nb, Kb], "ms": round(ms_pl, 4), "tflops": round(flb / ms_pl * 1e-9, 1)}
+        del dYq, Wt, Cq, Oi, Oo, Co, pb
 
     # ---- unfused baseline: same mainloop with a plain store + separate elementwise kernels ---------------
     if not args.no_unfused:

@@ -111,7 +111,19 @@ typedef enum coda_epi_kind {
        i1 = rope_cols (multiple of 8, <= N), ld_in = T.  Columns >= rope_cols pass through.
        The paper pre-broadcasts the tables to [M x N/2]; indexing a [T x head_dim/2] table by
        position gives the same values without that input traffic.                       */
-    CODA_EPI_ROPE = 8
+    CODA_EPI_ROPE = 8,
+    /* Local part of RMSNorm backward (Kernel 9).  v = D is the gradient w.r.t. the normalised
+       activation.  With C the RMSNorm input, r its inverse-rms factor, z the row statistic
+       z[i] = (1/d) sum_j (grad_h2 * h2)[i][j] and cn = C (.) r:
+           v'[i][j] = ( v*gamma[j] - cn[i][j]*z[i] ) * r[i]
+       (follow with ADD_TILE to add the incoming residual gradient O_in, then STORE = O_out).
+       in: bf16 C [M x N] (ld_in); in2: f32 r[M]; in3: f32 z[M]; in4: f32 gamma[N] (16-byte aligned).
+       Optional out: bf16 [M x N] (ld_out) receives C_out = cn (.) gamma (the normalised activation).
+       Optional out2: f32 column reduction dgamma[j] = sum_i v[i][j]*cn[i][j] of this tile row, laid
+       out per `flags`: CODA_REDUCE_PARTIALS: [nblk x N] block-major (out2[b*N + j]),
+       nblk = coda_col_partial_blocks(M), combine with coda_col_finalize; CODA_REDUCE_ATOMIC: f32[N]
+       pre-zeroed by the caller.                                                           */
+    CODA_EPI_RMSNORM_BWD = 9
 } coda_epi_kind;
 
 #define CODA_REDUCE_PARTIALS 0u
@@ -127,6 +139,7 @@ typedef struct coda_epi_op {
     int64_t ld_in, ld_out;
     const void *in2; /* device; second / third input of ops that take several (ROPE) */
     const void *in3; /* device */
+    const void *in4; /* device */
     int64_t i0, i1;  /* integer parameters of the op (ROPE: head_dim, rope_cols) */
 } coda_epi_op;
 
@@ -139,9 +152,10 @@ typedef struct coda_epi_op {
  *     [ROW_SCALE] ROPE STORE
  *     [ROW_SCALE] SWIGLU_FWD STORE
  *     SWIGLU_BWD STORE
+ *     RMSNORM_BWD [ADD_TILE] STORE
  *     ACCUM_F32
  * with bracketed ops optional and each at most once.  These cover Kernels 1, 2, 4,
- * 5, 6, 7, 10, the plain GEMM (STORE alone) and the accumulating weight gradient.
+ * 5, 6, 7, 9, 10, the plain GEMM (STORE alone) and the accumulating weight gradient.
  *
  * Sizes: M, N, K >= 0 must equal the op() shapes of A and B.  M == 0 or N == 0
  * is a no-op; K == 0 runs the program on D = 0.  K must be a multiple of 8; N a
@@ -170,6 +184,13 @@ int64_t coda_row_partial_blocks(int64_t N);
  */
 coda_status coda_row_finalize(void *stream, const float *partials, int64_t M, int64_t nblk,
                               float *sum_out, float *rstd_out, int64_t d, float eps);
+
+/* Number of row blocks nblk of a column-reduction partial buffer (f32[nblk x N]) for M output rows. */
+int64_t coda_col_partial_blocks(int64_t M);
+
+/* Auxiliary reduction over column partials (the reduce_rows step of the RMSNorm weight gradient,
+   Appendix "GEMM-RMSNorm-GEMM Backward Pass"): out[j] = sum_b partials[b*N + j].  partials f32[nblk x N]. */
+coda_status coda_col_finalize(void *stream, const float *partials, int64_t N, int64_t nblk, float *out);
 
 /* ss[i] = sum_k X[i][k]^2 in fp32 for a bf16 matrix not produced by coda_gemm
    (the first layer's input).  X->trans must be 0.  sum_out: f32[X->rows]. */

@@ -23,10 +23,11 @@ CODA_OK, CODA_ERR_NULL, CODA_ERR_SHAPE, CODA_ERR_ALIGN, CODA_ERR_DTYPE, CODA_ERR
     CODA_ERR_WORKSPACE, CODA_ERR_LAUNCH = range(8)
 CODA_BF16, CODA_F32 = 0, 1
 (CODA_EPI_ROW_SCALE, CODA_EPI_COL_SCALE_SIDE, CODA_EPI_ADD_TILE, CODA_EPI_SWIGLU_FWD, CODA_EPI_SWIGLU_BWD,
- CODA_EPI_ROW_SUMSQ, CODA_EPI_STORE, CODA_EPI_ACCUM_F32, CODA_EPI_ROPE) = range(9)
+ CODA_EPI_ROW_SUMSQ, CODA_EPI_STORE, CODA_EPI_ACCUM_F32, CODA_EPI_ROPE, CODA_EPI_RMSNORM_BWD) = range(10)
 CODA_REDUCE_PARTIALS, CODA_REDUCE_ATOMIC, CODA_STORE_F32 = 0, 1, 2
 
 EXPORTS = ["coda_gemm", "coda_gemm_workspace_bytes", "coda_row_partial_blocks", "coda_row_finalize",
+           "coda_col_partial_blocks", "coda_col_finalize",
            "coda_row_sumsq", "coda_fold_gamma", "coda_interleave_pairs", "coda_status_string",
            "coda_last_hip_error"]
 EXPORTS_UNFUSED = ["coda_unfused_rmsnorm_apply", "coda_unfused_swiglu_fwd", "coda_unfused_swiglu_bwd",
@@ -42,7 +43,7 @@ class coda_epi_op(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("flags", ctypes.c_uint32), ("in_", ctypes.c_void_p),
                 ("out", ctypes.c_void_p), ("out2", ctypes.c_void_p), ("ld_in", ctypes.c_int64),
                 ("ld_out", ctypes.c_int64), ("in2", ctypes.c_void_p), ("in3", ctypes.c_void_p),
-                ("i0", ctypes.c_int64), ("i1", ctypes.c_int64)]
+                ("in4", ctypes.c_void_p), ("i0", ctypes.c_int64), ("i1", ctypes.c_int64)]
 
 
 _vp, _i64, _i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
@@ -55,6 +56,10 @@ _lib.coda_row_partial_blocks.restype = _i64
 _lib.coda_row_partial_blocks.argtypes = [_i64]
 _lib.coda_row_finalize.restype = ctypes.c_int
 _lib.coda_row_finalize.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _i64, ctypes.c_float]
+_lib.coda_col_partial_blocks.restype = _i64
+_lib.coda_col_partial_blocks.argtypes = [_i64]
+_lib.coda_col_finalize.restype = ctypes.c_int
+_lib.coda_col_finalize.argtypes = [_vp, _vp, _i64, _i64, _vp]
 _lib.coda_row_sumsq.restype = ctypes.c_int
 _lib.coda_row_sumsq.argtypes = [_vp, ctypes.POINTER(coda_mat), _vp]
 _lib.coda_fold_gamma.restype = ctypes.c_int
@@ -114,8 +119,9 @@ def mat(t, trans=False):
     return coda_mat(t.data_ptr(), t.shape[0], t.shape[1], t.stride(0), 1 if trans else 0, dt)
 
 
-def _op(kind, flags=0, in_=None, out=None, out2=None, in2=None, in3=None, i0=0, i1=0):
-    return coda_epi_op(kind, flags, _ptr(in_), _ptr(out), _ptr(out2), _ld(in_), _ld(out), _ptr(in2), _ptr(in3), i0, i1)
+def _op(kind, flags=0, in_=None, out=None, out2=None, in2=None, in3=None, in4=None, i0=0, i1=0):
+    return coda_epi_op(kind, flags, _ptr(in_), _ptr(out), _ptr(out2), _ld(in_), _ld(out), _ptr(in2), _ptr(in3),
+                       _ptr(in4), i0, i1)
 
 
 # --- epilogue op constructors (keep the tensors alive until the call returns) ----------------
@@ -130,6 +136,11 @@ def col_scale_side(gamma, out):
 def rope(cos, sin, pos, head_dim, rope_cols):
     """cos / sin: f32 [T x head_dim/2] dense tables; pos: int32 [M]."""
     return _op(CODA_EPI_ROPE, in_=cos, in2=sin, in3=pos, i0=head_dim, i1=rope_cols)
+
+
+def rmsnorm_bwd(C, r, z, gamma, c_out=None, dgamma_out=None, atomic=False):
+    return _op(CODA_EPI_RMSNORM_BWD, CODA_REDUCE_ATOMIC if atomic else CODA_REDUCE_PARTIALS, in_=C, in2=r, in3=z,
+               in4=gamma, out=c_out, out2=dgamma_out)
 
 
 def add_tile(C):
@@ -190,6 +201,14 @@ def coda_row_partial_blocks(N):
 
 def coda_row_finalize(partials, M, nblk, sum_out=None, rstd_out=None, d=1, eps=0.0, stream=None):
     _check(_lib.coda_row_finalize(_stream(stream), _ptr(partials), M, nblk, _ptr(sum_out), _ptr(rstd_out), d, eps))
+
+
+def coda_col_partial_blocks(M):
+    return _lib.coda_col_partial_blocks(M)
+
+
+def coda_col_finalize(partials, N, nblk, out, stream=None):
+    _check(_lib.coda_col_finalize(_stream(stream), _ptr(partials), N, nblk, _ptr(out)))
 
 
 def coda_row_sumsq(X, sum_out, stream=None):

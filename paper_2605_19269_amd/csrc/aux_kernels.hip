@@ -33,6 +33,17 @@ __global__ __launch_bounds__(256) void row_finalize_kernel(const float *__restri
     if (rstd_out) rstd_out[i] = 1.0f / sqrtf(s * inv_d + eps);
 }
 
+// partials is [nblk x N]; consecutive threads read consecutive columns of one block: coalesced.
+__global__ __launch_bounds__(256) void col_finalize_kernel(const float *__restrict__ partials, int64_t N, int64_t nblk,
+                                                           float *__restrict__ out)
+{
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= N) return;
+    float s = 0.0f;
+    for (int64_t b = 0; b < nblk; ++b) s += partials[b * N + j];
+    out[j] = s;
+}
+
 // One wavefront per row, 16 bytes per lane per step, butterfly reduction at the end.
 __global__ __launch_bounds__(256) void row_sumsq_kernel(const uint16_t *__restrict__ X, int64_t M, int64_t K, int64_t ld,
                                                         float *__restrict__ out)
@@ -102,6 +113,12 @@ hipError_t launch_row_finalize(hipStream_t s, const float *partials, int64_t M, 
 {
     hipLaunchKernelGGL(row_finalize_kernel, dim3(blocks_for(M, 256)), dim3(256), 0, s, partials, M, nblk, sum_out,
                        rstd_out, inv_d, eps);
+    return hipGetLastError();
+}
+
+hipError_t launch_col_finalize(hipStream_t s, const float *partials, int64_t N, int64_t nblk, float *out)
+{
+    hipLaunchKernelGGL(col_finalize_kernel, dim3(blocks_for(N, 256)), dim3(256), 0, s, partials, N, nblk, out);
     return hipGetLastError();
 }
 

@@ -9,6 +9,7 @@ namespace coda {
 
 hipError_t launch_row_finalize(hipStream_t s, const float *partials, int64_t M, int64_t nblk, float *sum_out,
                                float *rstd_out, float inv_d, float eps);
+hipError_t launch_col_finalize(hipStream_t s, const float *partials, int64_t N, int64_t nblk, float *out);
 hipError_t launch_row_sumsq(hipStream_t s, const uint16_t *X, int64_t M, int64_t K, int64_t ld, float *sum_out);
 hipError_t launch_fold_gamma(hipStream_t s, const uint16_t *W, int64_t K, int64_t N, int64_t ld, const float *gamma,
                              uint16_t *out, int64_t ld_out);

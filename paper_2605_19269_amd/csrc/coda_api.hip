@@ -60,6 +60,7 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
     int pair = 0;            // 0 none, 1 swiglu fwd, 2 swiglu bwd
     bool final_seen = false;
     bool linear_only = false;  // an op that only the linear program supports was used
+    bool rmsbwd = false;       // RMSNORM_BWD seen: only ADD_TILE and a bf16 STORE may follow
     for (int i = 0; i < n_ops; ++i) {
         const coda_epi_op &op = prog[i];
         if (final_seen) return CODA_ERR_PROGRAM;
@@ -72,7 +73,7 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
             stage = 1;
             break;
         case CODA_EPI_ROPE:
-            if (stage > 1 || pair) return CODA_ERR_PROGRAM;
+            if (stage > 1 || pair || rmsbwd) return CODA_ERR_PROGRAM;
             if ((st = check_vec(op.in)) != CODA_OK || (st = check_vec(op.in2)) != CODA_OK || (st = check_vec(op.in3)) != CODA_OK)
                 return st;
             if ((reinterpret_cast<uintptr_t>(op.in) & 7u) || (reinterpret_cast<uintptr_t>(op.in2) & 7u)) return CODA_ERR_ALIGN;
@@ -86,6 +87,31 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
             stage = 4;          // only STORE may follow
             linear_only = true;
             break;
+        case CODA_EPI_RMSNORM_BWD:
+            if (stage > 0 || pair) return CODA_ERR_PROGRAM;
+            if ((st = check_tile(op.in, op.ld_in, N)) != CODA_OK) return st;
+            if ((st = check_vec(op.in2)) != CODA_OK || (st = check_vec(op.in3)) != CODA_OK || (st = check_vec(op.in4)) != CODA_OK)
+                return st;
+            if (!aligned16(op.in4)) return CODA_ERR_ALIGN;
+            p.rn_c = static_cast<const uint16_t *>(op.in);
+            p.ld_rn_c = op.ld_in;
+            p.rn_r = static_cast<const float *>(op.in2);
+            p.rn_z = static_cast<const float *>(op.in3);
+            p.rn_gamma = static_cast<const float *>(op.in4);
+            if (op.out) {
+                if ((st = check_tile(op.out, op.ld_out, N)) != CODA_OK) return st;
+                p.out2 = static_cast<uint16_t *>(op.out);
+                p.ld_out2 = op.ld_out;
+            }
+            if (op.out2) {
+                if ((st = check_vec(op.out2)) != CODA_OK) return st;
+                if ((op.flags & ~1u) != 0) return CODA_ERR_PROGRAM;
+                p.colred = static_cast<float *>(op.out2);
+                p.colred_mode = (op.flags & CODA_REDUCE_ATOMIC) ? coda::ROWRED_ATOMIC : coda::ROWRED_PARTIALS;
+            }
+            rmsbwd = true;
+            stage = 1;          // only ADD_TILE and STORE may follow
+            break;
         case CODA_EPI_ADD_TILE:
             if (stage > 1 || pair) return CODA_ERR_PROGRAM;
             if ((st = check_tile(op.in, op.ld_in, N)) != CODA_OK) return st;
@@ -95,7 +121,7 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
             linear_only = true;
             break;
         case CODA_EPI_ROW_SUMSQ:
-            if (stage > 2 || pair) return CODA_ERR_PROGRAM;
+            if (stage > 2 || pair || rmsbwd) return CODA_ERR_PROGRAM;
             if ((st = check_vec(op.out)) != CODA_OK) return st;
             if (op.flags != CODA_REDUCE_PARTIALS && op.flags != CODA_REDUCE_ATOMIC) return CODA_ERR_PROGRAM;
             p.rowred = static_cast<float *>(op.out);
@@ -104,7 +130,7 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
             linear_only = true;
             break;
         case CODA_EPI_COL_SCALE_SIDE:
-            if (stage > 3 || pair || p.rope_cos) return CODA_ERR_PROGRAM;
+            if (stage > 3 || pair || p.rope_cos || rmsbwd) return CODA_ERR_PROGRAM;
             if ((st = check_vec(op.in)) != CODA_OK) return st;
             if (!aligned16(op.in)) return CODA_ERR_ALIGN;
             if ((st = check_tile(op.out, op.ld_out, N)) != CODA_OK) return st;
@@ -115,7 +141,7 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
             linear_only = true;
             break;
         case CODA_EPI_SWIGLU_FWD:
-            if (pair || linear_only || (N & 1)) return CODA_ERR_PROGRAM;
+            if (pair || linear_only || rmsbwd || (N & 1)) return CODA_ERR_PROGRAM;
             if (op.out) {
                 if ((st = check_tile(op.out, op.ld_out, N)) != CODA_OK) return st;
                 p.out2 = static_cast<uint16_t *>(op.out);
@@ -146,7 +172,7 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
         case CODA_EPI_STORE: {
             const bool f32 = (op.flags & CODA_STORE_F32) != 0;
             if ((op.flags & ~CODA_STORE_F32) != 0) return CODA_ERR_PROGRAM;
-            if (pair && f32) return CODA_ERR_PROGRAM;
+            if ((pair || rmsbwd) && f32) return CODA_ERR_PROGRAM;
             const int64_t width = pair == 1 ? N / 2 : pair == 2 ? 2 * N : N;
             if (!op.out) return CODA_ERR_NULL;
             if (op.ld_out < width) return CODA_ERR_SHAPE;
@@ -154,7 +180,8 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
             p.out = op.out;
             p.ld_out = op.ld_out;
             p.out_f32 = f32 ? 1 : 0;
-            out.mode = pair == 1 ? coda::EPI_SWIGLU_FWD : pair == 2 ? coda::EPI_SWIGLU_BWD : coda::EPI_LINEAR;
+            out.mode = pair == 1 ? coda::EPI_SWIGLU_FWD : pair == 2 ? coda::EPI_SWIGLU_BWD
+                     : rmsbwd  ? coda::EPI_RMSNORM_BWD : coda::EPI_LINEAR;
             final_seen = true;
             break;
         }
@@ -186,6 +213,8 @@ hipError_t dispatch_mode(int mode, bool edge, const coda::GemmParams &p, hipStre
         return edge ? launch_gemm<AK, BKC, EPI_SWIGLU_FWD, true>(p, s) : launch_gemm<AK, BKC, EPI_SWIGLU_FWD, false>(p, s);
     case EPI_SWIGLU_BWD:
         return edge ? launch_gemm<AK, BKC, EPI_SWIGLU_BWD, true>(p, s) : launch_gemm<AK, BKC, EPI_SWIGLU_BWD, false>(p, s);
+    case EPI_RMSNORM_BWD:
+        return edge ? launch_gemm<AK, BKC, EPI_RMSNORM_BWD, true>(p, s) : launch_gemm<AK, BKC, EPI_RMSNORM_BWD, false>(p, s);
     default:
         return edge ? launch_gemm<AK, BKC, EPI_ACCUM, true>(p, s) : launch_gemm<AK, BKC, EPI_ACCUM, false>(p, s);
     }
@@ -240,6 +269,21 @@ size_t coda_gemm_workspace_bytes(int64_t, int64_t, int64_t, const coda_epi_op *,
 int64_t coda_row_partial_blocks(int64_t N)
 {
     return N <= 0 ? 0 : (N + coda::MainCfg::BN - 1) / coda::MainCfg::BN;
+}
+
+int64_t coda_col_partial_blocks(int64_t M)
+{
+    return M <= 0 ? 0 : (M + coda::MainCfg::BM - 1) / coda::MainCfg::BM;
+}
+
+coda_status coda_col_finalize(void *stream, const float *partials, int64_t N, int64_t nblk, float *out)
+{
+    if (N < 0 || nblk < 0) return CODA_ERR_SHAPE;
+    if (!out) return CODA_ERR_NULL;
+    if (N == 0) return CODA_OK;
+    if (nblk > 0 && !partials) return CODA_ERR_NULL;
+    if (!aligned4(partials) || !aligned4(out)) return CODA_ERR_ALIGN;
+    return launch_status(coda::launch_col_finalize(static_cast<hipStream_t>(stream), partials, N, nblk, out));
 }
 
 coda_status coda_row_finalize(void *stream, const float *partials, int64_t M, int64_t nblk, float *sum_out,

@@ -39,7 +39,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-enum EpiMode : int { EPI_LINEAR = 0, EPI_SWIGLU_FWD = 1, EPI_SWIGLU_BWD = 2, EPI_ACCUM = 3 };
+enum EpiMode : int { EPI_LINEAR = 0, EPI_SWIGLU_FWD = 1, EPI_SWIGLU_BWD = 2, EPI_ACCUM = 3, EPI_RMSNORM_BWD = 4 };
 enum RowRedMode : int { ROWRED_NONE = 0, ROWRED_PARTIALS = 1, ROWRED_ATOMIC = 2 };
 
 struct GemmParams {
@@ -59,6 +59,11 @@ struct GemmParams {
     const float *rope_cos, *rope_sin;    // f32 [T x rope_half] tables (linear mode; null = no rotation)
     const int *rope_pos;                 // int32 [M]
     int rope_half, rope_cols;            // head_dim / 2 (multiple of 4); leading columns that are rotated
+    // RMSNORM_BWD: RMSNorm input C [M x N] bf16, inverse rms r[M], row statistic z[M], weight gamma[N];
+    // the optional O_in tile travels in `add`, the optional C_out in `out2`
+    const uint16_t *rn_c; int64_t ld_rn_c;
+    const float *rn_r, *rn_z, *rn_gamma;
+    float *colred; int colred_mode;      // dgamma: partials [tiles_m x N] (ROWRED_PARTIALS) or atomics into f32[N]
 };
 
 // ---------------------------------------------------------------------------------
@@ -360,7 +365,97 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
 #pragma unroll
     for (int i = 0; i < FM; ++i) rsum[i] = 0.0f;
 
-    if constexpr (EPI == EPI_SWIGLU_FWD) {
+    if constexpr (EPI == EPI_RMSNORM_BWD) {
+        // ---- local part of RMSNorm backward: with d the accumulator, cn = C*r:
+        //   O_out = O_in + (d*gamma - cn*z)*r,   C_out = cn*gamma,   dgamma partial = column sums of d*cn over this tile.
+        // Per 64-row pass the region holds the C rows and the O_in rows side by side; results overwrite them in place.
+        constexpr int RB = WTN * 2, P = 64, FPP = 2;
+        static_assert(WTN == 64 && WTM % P == 0 && 2 * P * RB <= REG, "staging pass");
+        using St = Stage<RB>;
+        const uint32_t ulane = St::template unit_lane<8>(lane);
+        unsigned char *rego = reg + P * RB;
+        uint16_t *outp = reinterpret_cast<uint16_t *>(p.out);
+        f32x4 dg[FN][4];
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) dg[j][g] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ps = 0; ps < WTM / P; ++ps) {
+            const int r0 = ps * P;
+            stage_load<RB, P, EDGE>(reg, reinterpret_cast<const unsigned char *>(p.rn_c + (int64_t)(mw + r0) * p.ld_rn_c + nw),
+                                    p.ld_rn_c * 2, rows_ok - r0, cols_ok * 2, lane);
+            if (p.add)
+                stage_load<RB, P, EDGE>(rego, reinterpret_cast<const unsigned char *>(p.add + (int64_t)(mw + r0) * p.ld_add + nw),
+                                        p.ld_add * 2, rows_ok - r0, cols_ok * 2, lane);
+            stage_fence();
+#pragma unroll
+            for (int fi = 0; fi < FPP; ++fi) {
+                const int i = ps * FPP + fi, m = mw + i * 32 + lrow;
+                const bool mok = !EDGE || m < p.M;
+                const float rr = mok ? p.rn_r[m] : 0.0f, zz = mok ? p.rn_z[m] : 0.0f;
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int nl = j * 32 + g * 8 + lhalf * 4;
+                        const bool ok = mok && (!EDGE || nw + nl < p.N);
+                        const uint32_t ua = St::unit_addr(ulane, fi, (j * 32 + g * 8) * 2);
+                        f32x4 gm = {0.f, 0.f, 0.f, 0.f};
+                        if (ok) gm = *reinterpret_cast<const f32x4 *>(p.rn_gamma + nw + nl);
+                        const u32x2 cw = *reinterpret_cast<const u32x2 *>(reg + ua);
+                        const f32x4 d = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                        const f32x4 cn = f32x4{bf16_lo(cw[0]), bf16_hi(cw[0]), bf16_lo(cw[1]), bf16_hi(cw[1])} * rr;
+                        f32x4 o = (d * gm - cn * zz) * rr;
+                        if (p.add) {
+                            const u32x2 ow = *reinterpret_cast<const u32x2 *>(rego + ua);
+                            o += f32x4{bf16_lo(ow[0]), bf16_hi(ow[0]), bf16_lo(ow[1]), bf16_hi(ow[1])};
+                        }
+                        if (ok) dg[j][g] += d * cn;
+                        const f32x4 co = cn * gm;
+                        *reinterpret_cast<u32x2 *>(rego + ua) = u32x2{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+                        *reinterpret_cast<u32x2 *>(reg + ua) = u32x2{pack_bf16x2(co[0], co[1]), pack_bf16x2(co[2], co[3])};
+                        if (g == 3) __builtin_amdgcn_sched_barrier(0);
+                    }
+            }
+            stage_fence();
+            stage_store<RB, P, EDGE>(rego, reinterpret_cast<unsigned char *>(outp + (int64_t)(mw + r0) * p.ld_out + nw), p.ld_out * 2,
+                                     rows_ok - r0, cols_ok * 2, lane);
+            if (p.out2)
+                stage_store<RB, P, EDGE>(reg, reinterpret_cast<unsigned char *>(p.out2 + (int64_t)(mw + r0) * p.ld_out2 + nw),
+                                         p.ld_out2 * 2, rows_ok - r0, cols_ok * 2, lane);
+            stage_fence();
+        }
+        if (p.colred_mode != ROWRED_NONE) {
+            // column reduction: the lane's 32 partial sums go to the region as a [32 rows][64 columns] f32 tile, lane l
+            // then adds up column l over the 32 rows; the two row-waves of the workgroup meet in `red`
+            using Sf = Stage<256>;
+            const uint32_t fl = Sf::template unit_lane<16>(lane);
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) *reinterpret_cast<f32x4 *>(reg + Sf::unit_addr(fl, 0, (j * 32 + g * 8) * 4)) = dg[j][g];
+            stage_fence();
+            float cs = 0.0f;
+#pragma unroll
+            for (int rr = 0; rr < 32; ++rr)
+                cs += *reinterpret_cast<const float *>(reg + rr * 256 + ((((lane >> 2) ^ rr) & 15) << 4) + (lane & 3) * 4);
+            red[wm * C::BN + wn * WTN + lane] = cs;
+            __syncthreads();
+            for (int c = tid; c < C::BN; c += C::NT) {
+                const int n = n0 + c;
+                if (EDGE && n >= p.N) continue;
+                float t = 0.0f;
+#pragma unroll
+                for (int w = 0; w < C::WGM; ++w) t += red[w * C::BN + c];
+                const int tm_idx = m0 / BM;
+                if (p.colred_mode == ROWRED_PARTIALS)
+                    p.colred[(int64_t)tm_idx * p.N + n] = t;
+                else
+                    atomicAdd(p.colred + n, t);
+            }
+        }
+    } else if constexpr (EPI == EPI_SWIGLU_FWD) {
         // ---- row scale, pairwise SwiGLU (width halves), optional pre-activation side output
         constexpr int RBH = WTN, RBZ = WTN * 2;
         constexpr int P = pass_rows(REG, RBZ, WTM), FPP = P / 32;

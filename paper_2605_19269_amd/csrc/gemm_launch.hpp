@@ -38,6 +38,7 @@ hipError_t launch_gemm(const GemmParams &p_in, hipStream_t stream)
     CODA_INSTANTIATE_ONE(AK, BKC, EPI_LINEAR)       \
     CODA_INSTANTIATE_ONE(AK, BKC, EPI_SWIGLU_FWD)   \
     CODA_INSTANTIATE_ONE(AK, BKC, EPI_SWIGLU_BWD)   \
-    CODA_INSTANTIATE_ONE(AK, BKC, EPI_ACCUM)
+    CODA_INSTANTIATE_ONE(AK, BKC, EPI_ACCUM)        \
+    CODA_INSTANTIATE_ONE(AK, BKC, EPI_RMSNORM_BWD)
 
 }  // namespace coda

@@ -126,3 +126,38 @@ def test_llama8b_block_shapes(oracle):
         check_down(oracle, c["H"], c["Wdown"], c["R"], "8B down")
     finally:
         NSAMPLE = keep
+
+
+def test_llama8b_rmsnorm_backward(oracle):
+    """Kernel 9 at the 8B QKV-projection backward shape: D = dY[M x 6144] Wqkv^T -> [M x 4096], with residual-gradient
+    accumulation, the recomputed normalised activation and the dgamma column partials.  O_out / C_out are checked on
+    sampled rows; dgamma (a reduction over ALL rows) on sampled columns, by giving the oracle the column-sliced
+    weight, C, gamma and O_in (every quantity of the kernel is column-local once D is formed)."""
+    g = np.random.Generator(np.random.PCG64(9))
+    M, N, K = 16384, 4096, 6144
+    dY = synth.normal_bf16(g, (M, K), 1e-2)
+    W = synth.normal_bf16(g, (N, K), 0.02)            # forward weight [d x 6144], used transposed
+    Cb = synth.normal_bf16(g, (M, N), 1.0)
+    Oin = synth.normal_bf16(g, (M, N), 1e-2)
+    r = synth.uniform_f32(g, (M,), 0.5, 1.5)
+    z = synth.normal_f32(g, (M,), 1e-3)
+    gamma = synth.uniform_f32(g, (N,), 0.5, 1.5)
+    Oout = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    Cout = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    nblk = coda.coda_col_partial_blocks(M)
+    part = torch.empty((nblk, N), dtype=torch.float32, device="cuda")
+    dg = torch.empty(N, dtype=torch.float32, device="cuda")
+    dC, dr, dz, dgm, dO = G.dev_bf16(Cb), G.dev_f32(r), G.dev_f32(z), G.dev_f32(gamma), G.dev_bf16(Oin)
+    coda.coda_gemm(G.dev_bf16(dY), G.dev_bf16(W),
+                   [coda.rmsnorm_bwd(dC, dr, dz, dgm, c_out=Cout, dgamma_out=part), coda.add_tile(dO), coda.store(Oout)], transB=True)
+    coda.coda_col_finalize(part, N, nblk, dg)
+    torch.cuda.synchronize()
+    rows = synth.sample_rows(M, 32, seed=10)
+    r64, z64, g64 = r.astype(np.float64), z.astype(np.float64), gamma.astype(np.float64)
+    refO, refC, _ = oracle.gemm_rmsnorm_bwd(dY, W, Cb, r64, z64, g64, Oin=Oin, transB=True, rows=rows)
+    G.assert_bf16_close(rows_of(Oout, rows), refO, "8B O_out")
+    G.assert_bf16_close(rows_of(Cout, rows), refC, "8B C_out")
+    cols = np.sort(g.choice(N, size=24, replace=False))
+    _, _, refdg = oracle.gemm_rmsnorm_bwd(dY, np.ascontiguousarray(W[cols]), np.ascontiguousarray(Cb[:, cols]), r64, z64,
+                                          g64[cols], Oin=None, transB=True)
+    G.assert_f32_signed_close(dg.cpu().numpy()[cols].astype(np.float64), refdg, "8B dgamma")

@@ -371,3 +371,40 @@ def test_kernel7_rope(oracle, M, N, K, hd, rc, with_r, f32):
         G.assert_f32_signed_close(G.host_f64(out.t), ref, "rope f32")
     else:
         G.assert_bf16_close(G.host_f64(out.t), ref, "rope")
+
+
+@pytest.mark.parametrize("M,N,K", [(512, 512, 128), (520, 264, 200)])
+@pytest.mark.parametrize("with_oin,atomic,transB", [(True, False, True), (False, True, True), (True, False, False)])
+def test_kernel9_rmsnorm_backward(oracle, M, N, K, with_oin, atomic, transB):
+    """Kernel 9: D = A op(B); O_out = O_in + (D*gamma - C*r*z)*r; C_out = C*r*gamma; dgamma = colsum(D*C*r)."""
+    g = rng(71)
+    A, B = operands(g, M, N, K, False, transB, a_std=1.0, b_std=0.1)
+    Cb = synth.normal_bf16(g, (M, N), 1.0)
+    Oin = synth.normal_bf16(g, (M, N), 1.0) if with_oin else None
+    r = synth.uniform_f32(g, (M,), 0.5, 1.5)
+    z = synth.normal_f32(g, (M,), 0.3)
+    gamma = synth.uniform_f32(g, (N,), 0.5, 1.5)
+    Oout = G.Guarded(M, N, torch.bfloat16)
+    Cout = G.Guarded(M, N, torch.bfloat16)
+    nblk = coda.coda_col_partial_blocks(M)
+    dgp = torch.zeros(N, dtype=torch.float32, device="cuda") if atomic else \
+        torch.full((nblk, N), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    dC, dr, dz, dgm = G.dev_bf16(Cb), G.dev_f32(r), G.dev_f32(z), G.dev_f32(gamma)
+    ops = [coda.rmsnorm_bwd(dC, dr, dz, dgm, c_out=Cout.t, dgamma_out=dgp, atomic=atomic)]
+    if with_oin:
+        dO = G.dev_bf16(Oin)
+        ops.append(coda.add_tile(dO))
+    ops.append(coda.store(Oout.t))
+    coda.coda_gemm(G.dev_bf16(A), G.dev_bf16(B), ops, transB=transB)
+    if atomic:
+        dg = dgp
+    else:
+        dg = torch.empty(N, dtype=torch.float32, device="cuda")
+        coda.coda_col_finalize(dgp, N, nblk, dg)
+    torch.cuda.synchronize()
+    refO, refC, refdg = oracle.gemm_rmsnorm_bwd(A, B, Cb, r.astype(np.float64), z.astype(np.float64),
+                                                gamma.astype(np.float64), Oin=Oin, transB=transB)
+    Oout.check_guards(); Oout.written(); Cout.check_guards(); Cout.written()
+    G.assert_bf16_close(G.host_f64(Oout.t), refO, "O_out")
+    G.assert_bf16_close(G.host_f64(Cout.t), refC, "C_out")
+    G.assert_f32_signed_close(G.host_f64(dg), refdg, "dgamma")
