@@ -17,7 +17,7 @@ _lib = None
 
 __all__ = [
     "build", "lib_path", "num_threads", "bf16_bits_to_f64", "row_sumsq", "rstd", "rstd_from_sumsq",
-    "gemm_rowscale", "gemm_rowscale_rope", "gemm_rowscale_swiglu", "gemm_residual_sumsq", "gemm_swiglu_bwd",
+    "gemm_rowscale", "gemm_rowscale_lse", "gemm_rowscale_rope", "gemm_rowscale_swiglu", "gemm_residual_sumsq", "gemm_swiglu_bwd",
     "gemm_accumulate", "gemm_rmsnorm_bwd", "rmsnorm_linear_unfused", "rmsnorm_linear_reparam", "mlp_block",
     "fold_gamma", "interleave_pairs", "swiglu_fwd_points", "swiglu_bwd_points",
 ]
@@ -147,6 +147,23 @@ def gemm_rowscale(A, B, r=None, transA=False, transB=False, rows=None):
         _p(A), _i64(_ld(A)), _int(transA), _p(B), _i64(_ld(B)), _int(transB), _i64(M), _i64(N), _i64(K),
         _p(r), _p(rows), _i64(R), _p(O)))
     return O
+
+
+def gemm_rowscale_lse(A, B, y, r=None, transA=False, transB=False, rows=None):
+    """Kernels 3 / 8: returns (Z [R x N], z_tgt [R], lse [R]); the per-token loss is lse - z_tgt."""
+    A, B = _u16(A), _u16(B)
+    M, N, K = _mnk(A, transA, B, transB)
+    r = _f64(r, M)
+    y = np.ascontiguousarray(y, dtype=np.int32)
+    assert y.shape == (M,)
+    rows, R = _rows(rows, M)
+    Z = np.empty((R, N), np.float64)
+    zt = np.empty(R, np.float64)
+    lse = np.empty(R, np.float64)
+    _check(_load().coda_oracle_gemm_rowscale_lse(
+        _p(A), _i64(_ld(A)), _int(transA), _p(B), _i64(_ld(B)), _int(transB), _i64(M), _i64(N), _i64(K),
+        _p(r), _p(y), _p(rows), _i64(R), _p(Z), _p(zt), _p(lse)))
+    return Z, zt, lse
 
 
 def gemm_rowscale_rope(A, B, cos, sin, pos, head_dim, rope_cols, r=None, transA=False, transB=False, rows=None):

@@ -29,7 +29,8 @@
  * central finite differences and reverse-mode autodiff of the forward
  * definition; the row statistic vs sum(Z * dZ); the weight gradient vs finite
  * differences of <dY, H W>; RoPE vs complex multiplication by a library, norm preservation, the
- * relative-position property; the RMSNorm-backward kernel vs reverse-mode autodiff of a library RMSNorm.  No function here is "parity unpinned".
+ * relative-position property; the RMSNorm-backward kernel vs reverse-mode autodiff of a library RMSNorm;
+ * the log-sum-exp kernel vs a library logsumexp / cross-entropy, shift invariance and the uniform case.  No function here is "parity unpinned".
  *
  * Naming: "row scale" multiplies row i by r[i]; "column scale" multiplies
  * column j by gamma[j]; a "row reduction" sums over columns and yields one
@@ -323,6 +324,49 @@ int coda_oracle_gemm_rowscale_rope(const uint16_t *A, int64_t lda, int transA, c
             O[q * N + 2 * p2] = x0 * c - x1 * sn;
             O[q * N + 2 * p2 + 1] = x0 * sn + x1 * c;
         }
+    }
+    free(D);
+    return ORACLE_OK;
+}
+
+/*
+ * Kernels 3 and 8 (cross-entropy as GEMM + row-wise log-sum-exp):
+ *     Z = (A B) (.) r   (r == NULL: Kernel 3),   z_tgt[i] = Z[i][y[i]],   lse[i] = log sum_k exp(Z[i][k]).
+ * The per-token loss of Section 3.2.3 is lse[i] - z_tgt[i].  The log-sum-exp is evaluated in its shift-invariant
+ * form  m + log sum_k exp(Z[i][k] - m),  m = max_k Z[i][k],  which is the same number without overflow.
+ * Zout (optional) receives the logits, which the method materialises for the backward pass.
+ */
+int coda_oracle_gemm_rowscale_lse(const uint16_t *A, int64_t lda, int transA, const uint16_t *B, int64_t ldb,
+                                  int transB, int64_t M, int64_t N, int64_t K, const double *r,
+                                  const int32_t *y, const int64_t *rows, int64_t nrows, double *Zout,
+                                  double *ztgt, double *lse)
+{
+    if (!A || !B || !y || !ztgt || !lse || N <= 0)
+        return ORACLE_ERR_ARG;
+    int64_t R = sel_count(rows, nrows, M);
+    double *D = gemm_bf16(A, lda, transA, B, ldb, transB, N, K, rows, R);
+    if (!D)
+        return ORACLE_ERR_NOMEM;
+    for (int64_t q = 0; q < R; ++q) {
+        int64_t i = sel_row(rows, q);
+        double ri = r ? r[i] : 1.0;
+        if (y[i] < 0 || y[i] >= N) {
+            free(D);
+            return ORACLE_ERR_ARG;
+        }
+        double m = -INFINITY;
+        for (int64_t j = 0; j < N; ++j) {
+            D[q * N + j] *= ri;
+            if (D[q * N + j] > m)
+                m = D[q * N + j];
+        }
+        double sum = 0.0;
+        for (int64_t j = 0; j < N; ++j)
+            sum += exp(D[q * N + j] - m);
+        lse[q] = m + log(sum);
+        ztgt[q] = D[q * N + y[i]];
+        if (Zout)
+            memcpy(Zout + q * N, D + q * N, sizeof(double) * (size_t)N);
     }
     free(D);
     return ORACLE_OK;

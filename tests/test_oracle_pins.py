@@ -468,3 +468,39 @@ def test_kernel9_uses_the_gemm_result_with_transposed_weight(oracle):
     z = (wide(gy) * y.detach().numpy()).sum(1) / d        # statistic taken AFTER the GEMM (Section 3.2.4 identity)
     Oout, _, _ = oracle.gemm_rmsnorm_bwd(gy, W1, h1, r, z, gamma, transB=True)
     np.testing.assert_allclose(Oout, th.grad.numpy(), rtol=1e-10, atol=1e-12)
+
+
+# ---------------------------------------------------------------- cross-entropy pieces (Kernels 3 and 8)
+def test_lse_kernel_vs_library_cross_entropy(oracle):
+    g = rng(22)
+    M, K, N = 9, 12, 40
+    A = synth.normal_bf16(g, (M, K), 1.0)
+    B = synth.normal_bf16(g, (K, N), 1.0)
+    y = g.integers(0, N, size=M).astype(np.int32)
+    r = g.random(M) + 0.5
+    Z, zt, lse = oracle.gemm_rowscale_lse(A, B, y, r=r)
+    Zt = torch.from_numpy((wide(A) @ wide(B)) * r[:, None])
+    np.testing.assert_allclose(Z, Zt.numpy(), rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(lse, torch.logsumexp(Zt, dim=1).numpy(), rtol=1e-13)
+    np.testing.assert_allclose(zt, Zt.numpy()[np.arange(M), y], rtol=0, atol=0)
+    loss = torch.nn.functional.cross_entropy(Zt, torch.from_numpy(y.astype(np.int64)), reduction="none").numpy()
+    np.testing.assert_allclose(lse - zt, loss, rtol=1e-12, atol=1e-13)          # Section 3.2.3: l_i = -h_{i,y_i} + log sum exp
+    sel = oracle.gemm_rowscale_lse(A, B, y, r=r, rows=np.array([8, 3]))
+    np.testing.assert_allclose(sel[2], lse[[8, 3]], rtol=0, atol=0)
+    np.testing.assert_allclose(sel[1], zt[[8, 3]], rtol=0, atol=0)
+
+
+def test_lse_closed_forms(oracle):
+    # all logits equal c  ->  lse = c + log N ; huge logits do not overflow ; one dominant logit -> lse ~ that logit
+    N = 64
+    I = bits(np.eye(N, dtype=np.float32))
+    rowc = bits(np.full((1, N), 3.0, np.float32))
+    y0 = np.zeros(1, np.int32)
+    _, zt, lse = oracle.gemm_rowscale_lse(rowc, I, y0)
+    assert abs(lse[0] - (3.0 + math.log(N))) < 1e-14 and zt[0] == 3.0
+    big = np.full((1, N), -1000.0, np.float32); big[0, 7] = 900.0
+    _, zt, lse = oracle.gemm_rowscale_lse(bits(big), I, np.array([7], np.int32))
+    assert lse[0] == 900.0 and zt[0] == 900.0            # exp(-1900) underflows to exactly 0
+    # scaling the row by r scales every logit: lse(r*z) for r = 2 on the constant row
+    _, _, lse2 = oracle.gemm_rowscale_lse(rowc, I, y0, r=np.array([2.0]))
+    assert abs(lse2[0] - (6.0 + math.log(N))) < 1e-14
