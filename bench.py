@@ -195,6 +195,29 @@ def main():
         out["extra_kernels"]["qkv_bwd_8b_rmsnorm_backward"] = {"shape": [Mb, Nb, Kb], "ms": round(ms_k9, 4), "tflops": round(flb / ms_k9 * 1e-9, 1)}
         out["extra_kernels"]["qkv_bwd_8b_plain_store"] = {"shape": [Mb, Nb, Kb], "ms": round(ms_pl, 4), "tflops": round(flb / ms_pl * 1e-9, 1)}
         del dYq, Wt, Cq, Oi, Oo, Co, pb
+        # Kernel 8 at an LM-head shape: logits + log-sum-exp partials + target logit, then the aux combine
+        Ml, Kl, Nl = 8192, 4096, 32768
+        Xl = torch.randn((Ml, Kl), device=dev).to(torch.bfloat16)
+        Wl = (torch.randn((Kl, Nl), device=dev) * 0.02).to(torch.bfloat16)
+        yl = torch.randint(0, Nl, (Ml,), device=dev, dtype=torch.int32)
+        rl = torch.rand(Ml, **f32) + 0.5
+        Zl = torch.empty((Ml, Nl), **b16)
+        nb = coda.coda_row_partial_blocks(Nl)
+        pm, psm = torch.empty((nb, Ml), **f32), torch.empty((nb, Ml), **f32)
+        ztl, lossl = torch.empty(Ml, **f32), torch.empty(Ml, **f32)
+        fll = 2.0 * Ml * Nl * Kl
+
+        def f_lse():
+            coda.coda_gemm(Xl, Wl, [coda.row_scale(rl), coda.lse_partial(yl, pm, psm, ztl), coda.store(Zl)])
+            coda.coda_lse_finalize(pm, psm, Ml, nb, ztgt=ztl, loss_out=lossl)
+        f_pll = lambda: coda.coda_gemm(Xl, Wl, [coda.store(Zl)])
+        ms_l, ms_p = 1e9, 1e9
+        for _ in range(3):
+            ms_p = min(ms_p, time_kernel(f_pll, reps=5))
+            ms_l = min(ms_l, time_kernel(f_lse, reps=5))
+        out["extra_kernels"]["lm_head_logits_lse_loss"] = {"shape": [Ml, Nl, Kl], "ms": round(ms_l, 4), "tflops": round(fll / ms_l * 1e-9, 1)}
+        out["extra_kernels"]["lm_head_plain_store"] = {"shape": [Ml, Nl, Kl], "ms": round(ms_p, 4), "tflops": round(fll / ms_p * 1e-9, 1)}
+        del Xl, Wl, Zl, pm, psm
 
     # ---- unfused baseline: same mainloop with a plain store + separate elementwise kernels ---------------
     if not args.no_unfused:

@@ -123,7 +123,14 @@ typedef enum coda_epi_kind {
        out per `flags`: CODA_REDUCE_PARTIALS: [nblk x N] block-major (out2[b*N + j]),
        nblk = coda_col_partial_blocks(M), combine with coda_col_finalize; CODA_REDUCE_ATOMIC: f32[N]
        pre-zeroed by the caller.                                                           */
-    CODA_EPI_RMSNORM_BWD = 9
+    CODA_EPI_RMSNORM_BWD = 9,
+    /* Cross-entropy pieces (Kernels 3, 8): v unchanged (follow with STORE to materialise the logits).
+       Per 256-column tile b and row i, on the fp32 value before rounding:
+           out [b*M + i] = max_j v[i][j],   out2[b*M + i] = sum_j exp(v[i][j] - max)      (f32 [nblk x M] each,
+           nblk = coda_row_partial_blocks(N), every entry overwritten; combine with coda_lse_finalize)
+           out3[i] = v[i][y[i]]  (f32[M], the target logit; written by the tile that holds column y[i]).
+       in3: int32 y[M] with 0 <= y < N (not checked; an out-of-range y leaves out3[i] unwritten).       */
+    CODA_EPI_LSE_PARTIAL = 10
 } coda_epi_kind;
 
 #define CODA_REDUCE_PARTIALS 0u
@@ -140,6 +147,7 @@ typedef struct coda_epi_op {
     const void *in2; /* device; second / third input of ops that take several (ROPE) */
     const void *in3; /* device */
     const void *in4; /* device */
+    void *out3;      /* device */
     int64_t i0, i1;  /* integer parameters of the op (ROPE: head_dim, rope_cols) */
 } coda_epi_op;
 
@@ -150,12 +158,12 @@ typedef struct coda_epi_op {
  * the order
  *     [ROW_SCALE] [ADD_TILE] [ROW_SUMSQ] [COL_SCALE_SIDE] STORE
  *     [ROW_SCALE] ROPE STORE
+ *     [ROW_SCALE] LSE_PARTIAL STORE
  *     [ROW_SCALE] SWIGLU_FWD STORE
  *     SWIGLU_BWD STORE
  *     RMSNORM_BWD [ADD_TILE] STORE
  *     ACCUM_F32
- * with bracketed ops optional and each at most once.  These cover Kernels 1, 2, 4,
- * 5, 6, 7, 9, 10, the plain GEMM (STORE alone) and the accumulating weight gradient.
+ * with bracketed ops optional and each at most once.  These cover Kernels 1 to 10, the plain GEMM (STORE alone) and the accumulating weight gradient.
  *
  * Sizes: M, N, K >= 0 must equal the op() shapes of A and B.  M == 0 or N == 0
  * is a no-op; K == 0 runs the program on D = 0.  K must be a multiple of 8; N a
@@ -184,6 +192,13 @@ int64_t coda_row_partial_blocks(int64_t N);
  */
 coda_status coda_row_finalize(void *stream, const float *partials, int64_t M, int64_t nblk,
                               float *sum_out, float *rstd_out, int64_t d, float eps);
+
+/* Auxiliary reduction of the log-sum-exp partials (Section 3.2.3: "a small auxiliary reduction then combines these
+   statistics across tiles"): lse[i] = M_i + log sum_b psum[b][i] exp(pmax[b][i] - M_i), M_i = max_b pmax[b][i];
+   loss[i] = lse[i] - ztgt[i].  pmax, psum: f32[nblk x M]; ztgt f32[M] (needed only for loss_out);
+   lse_out, loss_out: f32[M], either may be NULL (not both). */
+coda_status coda_lse_finalize(void *stream, const float *pmax, const float *psum, int64_t M, int64_t nblk,
+                              const float *ztgt, float *lse_out, float *loss_out);
 
 /* Number of row blocks nblk of a column-reduction partial buffer (f32[nblk x N]) for M output rows. */
 int64_t coda_col_partial_blocks(int64_t M);

@@ -23,11 +23,11 @@ CODA_OK, CODA_ERR_NULL, CODA_ERR_SHAPE, CODA_ERR_ALIGN, CODA_ERR_DTYPE, CODA_ERR
     CODA_ERR_WORKSPACE, CODA_ERR_LAUNCH = range(8)
 CODA_BF16, CODA_F32 = 0, 1
 (CODA_EPI_ROW_SCALE, CODA_EPI_COL_SCALE_SIDE, CODA_EPI_ADD_TILE, CODA_EPI_SWIGLU_FWD, CODA_EPI_SWIGLU_BWD,
- CODA_EPI_ROW_SUMSQ, CODA_EPI_STORE, CODA_EPI_ACCUM_F32, CODA_EPI_ROPE, CODA_EPI_RMSNORM_BWD) = range(10)
+ CODA_EPI_ROW_SUMSQ, CODA_EPI_STORE, CODA_EPI_ACCUM_F32, CODA_EPI_ROPE, CODA_EPI_RMSNORM_BWD, CODA_EPI_LSE_PARTIAL) = range(11)
 CODA_REDUCE_PARTIALS, CODA_REDUCE_ATOMIC, CODA_STORE_F32 = 0, 1, 2
 
 EXPORTS = ["coda_gemm", "coda_gemm_workspace_bytes", "coda_row_partial_blocks", "coda_row_finalize",
-           "coda_col_partial_blocks", "coda_col_finalize",
+           "coda_col_partial_blocks", "coda_col_finalize", "coda_lse_finalize",
            "coda_row_sumsq", "coda_fold_gamma", "coda_interleave_pairs", "coda_status_string",
            "coda_last_hip_error"]
 EXPORTS_UNFUSED = ["coda_unfused_rmsnorm_apply", "coda_unfused_swiglu_fwd", "coda_unfused_swiglu_bwd",
@@ -43,7 +43,7 @@ class coda_epi_op(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("flags", ctypes.c_uint32), ("in_", ctypes.c_void_p),
                 ("out", ctypes.c_void_p), ("out2", ctypes.c_void_p), ("ld_in", ctypes.c_int64),
                 ("ld_out", ctypes.c_int64), ("in2", ctypes.c_void_p), ("in3", ctypes.c_void_p),
-                ("in4", ctypes.c_void_p), ("i0", ctypes.c_int64), ("i1", ctypes.c_int64)]
+                ("in4", ctypes.c_void_p), ("out3", ctypes.c_void_p), ("i0", ctypes.c_int64), ("i1", ctypes.c_int64)]
 
 
 _vp, _i64, _i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
@@ -60,6 +60,8 @@ _lib.coda_col_partial_blocks.restype = _i64
 _lib.coda_col_partial_blocks.argtypes = [_i64]
 _lib.coda_col_finalize.restype = ctypes.c_int
 _lib.coda_col_finalize.argtypes = [_vp, _vp, _i64, _i64, _vp]
+_lib.coda_lse_finalize.restype = ctypes.c_int
+_lib.coda_lse_finalize.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp, _vp, _vp]
 _lib.coda_row_sumsq.restype = ctypes.c_int
 _lib.coda_row_sumsq.argtypes = [_vp, ctypes.POINTER(coda_mat), _vp]
 _lib.coda_fold_gamma.restype = ctypes.c_int
@@ -119,9 +121,9 @@ def mat(t, trans=False):
     return coda_mat(t.data_ptr(), t.shape[0], t.shape[1], t.stride(0), 1 if trans else 0, dt)
 
 
-def _op(kind, flags=0, in_=None, out=None, out2=None, in2=None, in3=None, in4=None, i0=0, i1=0):
+def _op(kind, flags=0, in_=None, out=None, out2=None, in2=None, in3=None, in4=None, out3=None, i0=0, i1=0):
     return coda_epi_op(kind, flags, _ptr(in_), _ptr(out), _ptr(out2), _ld(in_), _ld(out), _ptr(in2), _ptr(in3),
-                       _ptr(in4), i0, i1)
+                       _ptr(in4), _ptr(out3), i0, i1)
 
 
 # --- epilogue op constructors (keep the tensors alive until the call returns) ----------------
@@ -141,6 +143,11 @@ def rope(cos, sin, pos, head_dim, rope_cols):
 def rmsnorm_bwd(C, r, z, gamma, c_out=None, dgamma_out=None, atomic=False):
     return _op(CODA_EPI_RMSNORM_BWD, CODA_REDUCE_ATOMIC if atomic else CODA_REDUCE_PARTIALS, in_=C, in2=r, in3=z,
                in4=gamma, out=c_out, out2=dgamma_out)
+
+
+def lse_partial(y, pmax, psum, ztgt):
+    """y: int32 [M] targets; pmax, psum: f32 [nblk x M]; ztgt: f32 [M]."""
+    return coda_epi_op(CODA_EPI_LSE_PARTIAL, 0, None, _ptr(pmax), _ptr(psum), 0, 0, None, _ptr(y), None, _ptr(ztgt), 0, 0)
 
 
 def add_tile(C):
@@ -201,6 +208,10 @@ def coda_row_partial_blocks(N):
 
 def coda_row_finalize(partials, M, nblk, sum_out=None, rstd_out=None, d=1, eps=0.0, stream=None):
     _check(_lib.coda_row_finalize(_stream(stream), _ptr(partials), M, nblk, _ptr(sum_out), _ptr(rstd_out), d, eps))
+
+
+def coda_lse_finalize(pmax, psum, M, nblk, ztgt=None, lse_out=None, loss_out=None, stream=None):
+    _check(_lib.coda_lse_finalize(_stream(stream), _ptr(pmax), _ptr(psum), M, nblk, _ptr(ztgt), _ptr(lse_out), _ptr(loss_out)))
 
 
 def coda_col_partial_blocks(M):

@@ -33,6 +33,22 @@ __global__ __launch_bounds__(256) void row_finalize_kernel(const float *__restri
     if (rstd_out) rstd_out[i] = 1.0f / sqrtf(s * inv_d + eps);
 }
 
+// Combine per-tile (max, sum-exp) pairs of each row into the row's log-sum-exp; optionally the per-token loss.
+__global__ __launch_bounds__(256) void lse_finalize_kernel(const float *__restrict__ pmax, const float *__restrict__ psum,
+                                                           int64_t M, int64_t nblk, const float *__restrict__ ztgt,
+                                                           float *__restrict__ lse_out, float *__restrict__ loss_out)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= M) return;
+    float mm = -__builtin_inff();
+    for (int64_t b = 0; b < nblk; ++b) mm = fmaxf(mm, pmax[b * M + i]);
+    float s = 0.0f;
+    for (int64_t b = 0; b < nblk; ++b) s += psum[b * M + i] * expf(pmax[b * M + i] - mm);
+    const float lse = mm + logf(s);
+    if (lse_out) lse_out[i] = lse;
+    if (loss_out) loss_out[i] = lse - ztgt[i];
+}
+
 // partials is [nblk x N]; consecutive threads read consecutive columns of one block: coalesced.
 __global__ __launch_bounds__(256) void col_finalize_kernel(const float *__restrict__ partials, int64_t N, int64_t nblk,
                                                            float *__restrict__ out)
@@ -113,6 +129,14 @@ hipError_t launch_row_finalize(hipStream_t s, const float *partials, int64_t M, 
 {
     hipLaunchKernelGGL(row_finalize_kernel, dim3(blocks_for(M, 256)), dim3(256), 0, s, partials, M, nblk, sum_out,
                        rstd_out, inv_d, eps);
+    return hipGetLastError();
+}
+
+hipError_t launch_lse_finalize(hipStream_t s, const float *pmax, const float *psum, int64_t M, int64_t nblk, const float *ztgt,
+                               float *lse_out, float *loss_out)
+{
+    hipLaunchKernelGGL(lse_finalize_kernel, dim3(blocks_for(M, 256)), dim3(256), 0, s, pmax, psum, M, nblk, ztgt, lse_out,
+                       loss_out);
     return hipGetLastError();
 }
 

@@ -87,6 +87,18 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
             stage = 4;          // only STORE may follow
             linear_only = true;
             break;
+        case CODA_EPI_LSE_PARTIAL:
+            if (stage > 1 || pair || rmsbwd) return CODA_ERR_PROGRAM;
+            if ((st = check_vec(op.in3)) != CODA_OK || (st = check_vec(op.out)) != CODA_OK ||
+                (st = check_vec(op.out2)) != CODA_OK || (st = check_vec(op.out3)) != CODA_OK)
+                return st;
+            p.lse_y = static_cast<const int *>(op.in3);
+            p.lse_max = static_cast<float *>(op.out);
+            p.lse_sum = static_cast<float *>(op.out2);
+            p.lse_tgt = static_cast<float *>(op.out3);
+            stage = 4;          // only STORE may follow
+            linear_only = true;
+            break;
         case CODA_EPI_RMSNORM_BWD:
             if (stage > 0 || pair) return CODA_ERR_PROGRAM;
             if ((st = check_tile(op.in, op.ld_in, N)) != CODA_OK) return st;
@@ -269,6 +281,16 @@ size_t coda_gemm_workspace_bytes(int64_t, int64_t, int64_t, const coda_epi_op *,
 int64_t coda_row_partial_blocks(int64_t N)
 {
     return N <= 0 ? 0 : (N + coda::MainCfg::BN - 1) / coda::MainCfg::BN;
+}
+
+coda_status coda_lse_finalize(void *stream, const float *pmax, const float *psum, int64_t M, int64_t nblk, const float *ztgt,
+                              float *lse_out, float *loss_out)
+{
+    if (M < 0 || nblk <= 0) return CODA_ERR_SHAPE;
+    if (!pmax || !psum || (!lse_out && !loss_out) || (loss_out && !ztgt)) return CODA_ERR_NULL;
+    if (M == 0) return CODA_OK;
+    if (!aligned4(pmax) || !aligned4(psum) || !aligned4(ztgt) || !aligned4(lse_out) || !aligned4(loss_out)) return CODA_ERR_ALIGN;
+    return launch_status(coda::launch_lse_finalize(static_cast<hipStream_t>(stream), pmax, psum, M, nblk, ztgt, lse_out, loss_out));
 }
 
 int64_t coda_col_partial_blocks(int64_t M)

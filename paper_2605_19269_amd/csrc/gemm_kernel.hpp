@@ -64,6 +64,10 @@ struct GemmParams {
     const uint16_t *rn_c; int64_t ld_rn_c;
     const float *rn_r, *rn_z, *rn_gamma;
     float *colred; int colred_mode;      // dgamma: partials [tiles_m x N] (ROWRED_PARTIALS) or atomics into f32[N]
+    // log-sum-exp partials (linear mode): per column tile the row maximum and sum of exp(v - max), both [tiles_n x M];
+    // target column y[M] and the selected logit z_tgt[M]
+    float *lse_max, *lse_sum, *lse_tgt;
+    const int *lse_y;
 };
 
 // ---------------------------------------------------------------------------------
@@ -364,6 +368,70 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
     float rsum[FM];
 #pragma unroll
     for (int i = 0; i < FM; ++i) rsum[i] = 0.0f;
+
+    if (EPI == EPI_LINEAR && p.lse_max) {
+        // ---- log-sum-exp partials of this 256-column tile (Kernels 3 / 8) on the fp32 values v = acc * r, before rounding:
+        // per lane and row the maximum and the sum of exp(v - max) over its 32 values, merged with the partner lane
+        // (other 4-column groups of the same row) and then over the four column waves with the usual rescaling rule.
+        constexpr float NEG_INF = -__builtin_inff();
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int m = mw + i * 32 + lrow;
+            const bool mok = !EDGE || m < p.M;
+            const float rs = p.row_scale ? (mok ? p.row_scale[m] : 0.0f) : 1.0f;
+            const int yy = mok ? p.lse_y[m] : -1;
+            float mx = NEG_INF;
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = nw + j * 32 + g * 8 + lhalf * 4;
+                    if (mok && (!EDGE || n < p.N)) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float v = acc[i][j][4 * g + e] * rs;
+                            mx = fmaxf(mx, v);
+                            if (n + e == yy) p.lse_tgt[m] = v;
+                        }
+                    }
+                }
+            float sm = 0.0f;
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = nw + j * 32 + g * 8 + lhalf * 4;
+                    if (mok && (!EDGE || n < p.N)) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) sm += __expf(acc[i][j][4 * g + e] * rs - mx);
+                    }
+                }
+            const float mo = __shfl_xor(mx, 32, 64), so = __shfl_xor(sm, 32, 64);
+            const float mm = fmaxf(mx, mo);
+            const float ss = (mx == NEG_INF ? 0.0f : sm * __expf(mx - mm)) + (mo == NEG_INF ? 0.0f : so * __expf(mo - mm));
+            if (lane < 32) {
+                red[wn * BM + wm * WTM + i * 32 + lane] = mm;
+                red[C::WGN * BM + wn * BM + wm * WTM + i * 32 + lane] = ss;
+            }
+        }
+        __syncthreads();
+        for (int r = tid; r < BM; r += C::NT) {
+            const int m = m0 + r;
+            if (EDGE && m >= p.M) continue;
+            float mm = NEG_INF;
+#pragma unroll
+            for (int w = 0; w < C::WGN; ++w) mm = fmaxf(mm, red[w * BM + r]);
+            float ss = 0.0f;
+#pragma unroll
+            for (int w = 0; w < C::WGN; ++w) {
+                const float mw_ = red[w * BM + r];
+                if (mw_ != NEG_INF) ss += red[C::WGN * BM + w * BM + r] * __expf(mw_ - mm);
+            }
+            p.lse_max[(int64_t)tn * p.M + m] = mm;
+            p.lse_sum[(int64_t)tn * p.M + m] = ss;
+        }
+        __syncthreads();   // `red` is reused by the row-reduction exchange below
+    }
 
     if constexpr (EPI == EPI_RMSNORM_BWD) {
         // ---- local part of RMSNorm backward: with d the accumulator, cn = C*r:
@@ -778,7 +846,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmParams p)
 {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, FM = C::FM, FN = C::FN;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * C::STAGE_BYTES];
-    __shared__ float red[C::WGN * C::BM];
+    __shared__ float red[2 * C::WGN * C::BM];   // row-reduction exchange; second half: sum-exp of the log-sum-exp partials
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % C::WGM, wn = wave / C::WGM;
@@ -926,7 +994,7 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     constexpr int BM = C::BM, BN = C::BN, BK = 32, FM = C::FM, FN = C::FN, S = C::STAGES;
     constexpr int LA = C::LA, LB = C::LB;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[S * C::STAGE_BYTES];
-    __shared__ float red[C::WGN * C::BM];
+    __shared__ float red[2 * C::WGN * C::BM];   // row-reduction exchange; second half: sum-exp of the log-sum-exp partials
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);

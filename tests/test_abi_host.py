@@ -36,18 +36,18 @@ def test_binding_mirrors_header_enums(coda):
     for name in ["CODA_OK", "CODA_ERR_NULL", "CODA_ERR_SHAPE", "CODA_ERR_ALIGN", "CODA_ERR_DTYPE", "CODA_ERR_PROGRAM",
                  "CODA_ERR_WORKSPACE", "CODA_ERR_LAUNCH", "CODA_EPI_ROW_SCALE", "CODA_EPI_COL_SCALE_SIDE",
                  "CODA_EPI_ADD_TILE", "CODA_EPI_SWIGLU_FWD", "CODA_EPI_SWIGLU_BWD", "CODA_EPI_ROW_SUMSQ",
-                 "CODA_EPI_STORE", "CODA_EPI_ACCUM_F32", "CODA_EPI_ROPE", "CODA_EPI_RMSNORM_BWD"]:
+                 "CODA_EPI_STORE", "CODA_EPI_ACCUM_F32", "CODA_EPI_ROPE", "CODA_EPI_RMSNORM_BWD", "CODA_EPI_LSE_PARTIAL"]:
         m = re.search(r"\b%s\s*=\s*(\d+)" % name, text)
         assert m and int(m.group(1)) == getattr(coda, name), name
-    assert ctypes.sizeof(coda.coda_mat) == 40 and ctypes.sizeof(coda.coda_epi_op) == 88
+    assert ctypes.sizeof(coda.coda_mat) == 40 and ctypes.sizeof(coda.coda_epi_op) == 96
 
 
 def _mat(coda, ptr, rows, cols, ld=None, trans=0, dtype=0):
     return coda.coda_mat(ptr, rows, cols, ld if ld is not None else cols, trans, dtype)
 
 
-def _op(coda, kind, flags=0, in_=None, out=None, out2=None, ld_in=0, ld_out=0, in2=None, in3=None, in4=None, i0=0, i1=0):
-    return coda.coda_epi_op(kind, flags, in_, out, out2, ld_in, ld_out, in2, in3, in4, i0, i1)
+def _op(coda, kind, flags=0, in_=None, out=None, out2=None, ld_in=0, ld_out=0, in2=None, in3=None, in4=None, out3=None, i0=0, i1=0):
+    return coda.coda_epi_op(kind, flags, in_, out, out2, ld_in, ld_out, in2, in3, in4, out3, i0, i1)
 
 
 P = 0x1000  # a fake, 16-byte aligned "device pointer"; no call below ever reaches a launch
@@ -111,6 +111,10 @@ def test_program_grammar(coda):
     assert g([rope, st]) == OK and g([rs, rope, st]) == OK
     assert g([rope, add, st]) == BAD and g([add, rope, st]) == BAD and g([rope, fwd, st_half]) == BAD
     assert g([rope, side, st]) == BAD and g([rope, rs, st]) == BAD
+    lse = _op(coda, coda.CODA_EPI_LSE_PARTIAL, in3=P, out=P, out2=P, out3=P)
+    assert g([lse, st]) == OK and g([rs, lse, st]) == OK
+    assert g([lse, add, st]) == BAD and g([lse, fwd, st_half]) == BAD and g([lse]) == BAD
+    assert g([_op(coda, coda.CODA_EPI_LSE_PARTIAL, in3=P, out=P, out2=None, out3=P), st]) == coda.CODA_ERR_NULL
     rnb = _op(coda, coda.CODA_EPI_RMSNORM_BWD, in_=P, ld_in=64, in2=P, in3=P, in4=P, out=P, ld_out=64, out2=P)
     assert g([rnb, st]) == OK and g([rnb, add, st]) == OK
     assert g([rs, rnb, st]) == BAD and g([rnb, ssq, st]) == BAD and g([rnb, rope, st]) == BAD and g([rnb, fwd, st_half]) == BAD

@@ -161,3 +161,30 @@ def test_llama8b_rmsnorm_backward(oracle):
     _, _, refdg = oracle.gemm_rmsnorm_bwd(dY, np.ascontiguousarray(W[cols]), np.ascontiguousarray(Cb[:, cols]), r64, z64,
                                           g64[cols], Oin=None, transB=True)
     G.assert_f32_signed_close(dg.cpu().numpy()[cols].astype(np.float64), refdg, "8B dgamma")
+
+
+def test_lm_head_logits_lse(oracle):
+    """Kernel 8 at an LM-head shape (tokens 8192, hidden 4096, vocabulary 32768): logits, target logit, lse, loss."""
+    g = np.random.Generator(np.random.PCG64(11))
+    M, K, N = 8192, 4096, 32768
+    Xb = synth.normal_bf16(g, (M, K), 1.0)
+    Wb = synth.normal_bf16(g, (K, N), 0.02)
+    y = g.integers(0, N, size=M).astype(np.int32)
+    X = G.dev_bf16(Xb)
+    r = gpu_rstd(X)
+    Z = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    nblk = coda.coda_row_partial_blocks(N)
+    pmax = torch.empty((nblk, M), dtype=torch.float32, device="cuda")
+    psum = torch.empty((nblk, M), dtype=torch.float32, device="cuda")
+    zt, lse, loss = (torch.empty(M, dtype=torch.float32, device="cuda") for _ in range(3))
+    dy = torch.from_numpy(y).cuda()
+    coda.coda_gemm(X, G.dev_bf16(Wb), [coda.row_scale(r), coda.lse_partial(dy, pmax, psum, zt), coda.store(Z)])
+    coda.coda_lse_finalize(pmax, psum, M, nblk, ztgt=zt, lse_out=lse, loss_out=loss)
+    torch.cuda.synchronize()
+    rows = synth.sample_rows(M, 32, seed=12)
+    refZ, refzt, reflse = oracle.gemm_rowscale_lse(Xb, Wb, y, r=r.cpu().numpy().astype(np.float64), rows=rows)
+    G.assert_bf16_close(rows_of(Z, rows), refZ, "LM-head logits")
+    G.assert_f32_signed_close(zt.cpu().numpy()[rows].astype(np.float64), refzt, "LM-head target logit")
+    d = np.abs(lse.cpu().numpy()[rows].astype(np.float64) - reflse)
+    assert (d <= 1e-3 * np.maximum(np.abs(reflse), 1.0)).all(), "lse max delta %.3g" % d.max()
+    G.assert_f32_signed_close(loss.cpu().numpy()[rows].astype(np.float64), reflse - refzt, "LM-head loss")

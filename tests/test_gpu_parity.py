@@ -408,3 +408,34 @@ def test_kernel9_rmsnorm_backward(oracle, M, N, K, with_oin, atomic, transB):
     G.assert_bf16_close(G.host_f64(Oout.t), refO, "O_out")
     G.assert_bf16_close(G.host_f64(Cout.t), refC, "C_out")
     G.assert_f32_signed_close(G.host_f64(dg), refdg, "dgamma")
+
+
+@pytest.mark.parametrize("M,N,K", [(512, 1024, 128), (520, 776, 200)])
+@pytest.mark.parametrize("with_r,transB", [(True, False), (False, True)])
+def test_kernel8_logits_lse_partials(oracle, M, N, K, with_r, transB):
+    """Kernels 3 / 8: logits (materialised), target logit and per-tile (max, sum-exp) partials -> lse and loss."""
+    g = rng(81)
+    A, B = operands(g, M, N, K, False, transB, b_std=0.3)
+    y = g.integers(0, N, size=M).astype(np.int32)
+    y[:4] = [0, N - 1, 255 if N > 255 else 1, 256 if N > 256 else 2]        # tile-boundary targets
+    r = synth.uniform_f32(g, (M,), 0.5, 1.5) if with_r else None
+    Z = G.Guarded(M, N, torch.bfloat16)
+    nblk = coda.coda_row_partial_blocks(N)
+    pmax = torch.full((nblk, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    psum = torch.full((nblk, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    zt = torch.full((M,), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    dy = torch.from_numpy(y).cuda()
+    ops = ([coda.row_scale(dr := G.dev_f32(r))] if with_r else []) + [coda.lse_partial(dy, pmax, psum, zt), coda.store(Z.t)]
+    coda.coda_gemm(G.dev_bf16(A), G.dev_bf16(B), ops, transB=transB)
+    lse = torch.empty(M, dtype=torch.float32, device="cuda")
+    loss = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_lse_finalize(pmax, psum, M, nblk, ztgt=zt, lse_out=lse, loss_out=loss)
+    torch.cuda.synchronize()
+    refZ, refzt, reflse = oracle.gemm_rowscale_lse(A, B, y, r=None if r is None else r.astype(np.float64), transB=transB)
+    Z.check_guards(); Z.written()
+    G.assert_bf16_close(G.host_f64(Z.t), refZ, "logits")
+    assert (pmax != G.SENTINEL_F32).all() and (psum != G.SENTINEL_F32).all() and (zt != G.SENTINEL_F32).all()
+    G.assert_f32_signed_close(G.host_f64(zt), refzt, "target logit")
+    d = np.abs(G.host_f64(lse) - reflse)
+    assert (d <= 1e-3 * np.maximum(np.abs(reflse), 1.0)).all(), "lse max delta %.3g" % d.max()
+    G.assert_f32_signed_close(G.host_f64(loss), reflse - refzt, "per-token loss")
