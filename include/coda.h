@@ -193,8 +193,8 @@ int64_t coda_row_partial_blocks(int64_t N);
 coda_status coda_row_finalize(void *stream, const float *partials, int64_t M, int64_t nblk,
                               float *sum_out, float *rstd_out, int64_t d, float eps);
 
-/* Auxiliary reduction of the log-sum-exp partials (Section 3.2.3: "a small auxiliary reduction then combines these
-   statistics across tiles"): lse[i] = M_i + log sum_b psum[b][i] exp(pmax[b][i] - M_i), M_i = max_b pmax[b][i];
+/* Auxiliary reduction of the log-sum-exp partials (Section 3.2.3: the per-tile maximum and sum-exp statistics are
+   combined across tiles by a separate small kernel): lse[i] = M_i + log sum_b psum[b][i] exp(pmax[b][i] - M_i), M_i = max_b pmax[b][i];
    loss[i] = lse[i] - ztgt[i].  pmax, psum: f32[nblk x M]; ztgt f32[M] (needed only for loss_out);
    lse_out, loss_out: f32[M], either may be NULL (not both). */
 coda_status coda_lse_finalize(void *stream, const float *pmax, const float *psum, int64_t M, int64_t nblk,

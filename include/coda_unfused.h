@@ -4,8 +4,8 @@
  * These exist only as the measurement baseline ("speedup vs unfused"): the same GEMM
  * mainloop with a plain store, followed by stand-alone elementwise / reduction kernels
  * that each make their own round trip through HBM -- the canonical formulation that
- * the paper's reparameterisation removes (Section 3.2, "a naive implementation
- * materializes the GEMM output ... and applies the activation in a separate kernel").
+ * the paper's reparameterisation removes (Section 3.2.2 describes it: the GEMM output is
+ * written out, split into pairs and transformed by a separate kernel).
  * Same conventions as coda.h: device pointers, row-major, ld in elements, 16-byte
  * aligned, widths multiples of 8, nothing allocated, work enqueued on `stream`.
  */

@@ -1,5 +1,5 @@
 // aux_kernels.hip -- small HBM-bound kernels around the GEMM (gfx950).
-//  * row_finalize: the "lightweight auxiliary reduction" of Section 3.2.1: sums the per-tile
+//  * row_finalize: the small auxiliary reduction of Section 3.2.1: sums the per-tile
 //    partial row reductions and optionally forms r = 1/sqrt(sum/d + eps).
 //  * row_sumsq: sum of squares of each row of a bf16 matrix that no GEMM of ours produced.
 //  * fold_gamma / interleave_pairs: one-time weight preparation.
