@@ -319,6 +319,32 @@ __device__ __forceinline__ void stage_store(const unsigned char *reg, unsigned c
     }
 }
 
+// Split form of stage_load: global -> registers now, registers -> region later, so the loads of the next pass can be
+// in flight while the current pass is processed.  t holds P / RPI chunks per lane.
+template <int RB, int P, bool EDGE>
+__device__ __forceinline__ void stage_fetch(u32x4 (&t)[P / Stage<RB>::RPI], const unsigned char *g, int64_t pitch, int rows_ok,
+                                            int bytes_ok, int lane)
+{
+    using St = Stage<RB>;
+    const int lr = lane / St::NCH, lc = (lane % St::NCH) * 16;
+    const uint32_t goff = (uint32_t)(lr * (int)pitch + lc);
+#pragma unroll
+    for (int it = 0; it < P / St::RPI; ++it) {
+        const unsigned char *gi = g + (int64_t)(it * St::RPI) * pitch;
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        const bool ok = !EDGE || (it * St::RPI + lr < rows_ok && lc < bytes_ok);
+        t[it] = ok ? *reinterpret_cast<const u32x4 *>(gi + goff) : z;
+    }
+}
+template <int RB, int P>
+__device__ __forceinline__ void stage_put(unsigned char *reg, const u32x4 (&t)[P / Stage<RB>::RPI], int lane)
+{
+    using St = Stage<RB>;
+    const uint32_t loff = St::row_lane(lane);
+#pragma unroll
+    for (int it = 0; it < P / St::RPI; ++it) *reinterpret_cast<u32x4 *>(reg + St::row_addr(loff, it)) = t[it];
+}
+
 // Phase boundary inside a wave: no instruction may be moved across it.
 __device__ __forceinline__ void stage_fence()
 {
@@ -576,46 +602,46 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
         // ---- pairwise SwiGLU backward (width doubles): Z in and dZ out staged; row statistic; the optional
         // recomputed activation silu(g)*u is a second sweep over 32-row blocks that re-reads Z.
         constexpr int RB = WTN * 4, RBO = WTN * 2;
-        constexpr int P = pass_rows(REG, RB, WTM), FPP = P / 32;
-        static_assert(P % 32 == 0 && WTM % P == 0 && 32 * (RB + RBO) <= REG, "staging pass");
+        static_assert(32 * (RB + RBO) <= REG, "staging pass");
         uint16_t *outp = reinterpret_cast<uint16_t *>(p.out);
         const uint32_t ulane = Stage<RB>::template unit_lane<16>(lane), ulane_o = Stage<RBO>::template unit_lane<8>(lane);
+        // 32-row passes; the Z rows of the next pass are fetched into registers while this pass is computed and stored
+        u32x4 zt[32 / Stage<RB>::RPI];
+        auto zrows = [&](int i) { return reinterpret_cast<const unsigned char *>(p.Z + (int64_t)(mw + i * 32) * p.ldz + 2 * nw); };
+        stage_fetch<RB, 32, EDGE>(zt, zrows(0), p.ldz * 2, rows_ok, cols_ok * 4, lane);
 #pragma unroll
-        for (int ps = 0; ps < WTM / P; ++ps) {
-            const int r0 = ps * P;
-            stage_load<RB, P, EDGE>(reg, reinterpret_cast<const unsigned char *>(p.Z + (int64_t)(mw + r0) * p.ldz + 2 * nw), p.ldz * 2,
-                                    rows_ok - r0, cols_ok * 4, lane);
+        for (int i = 0; i < FM; ++i) {
+            const int m = mw + i * 32 + lrow;
+            const bool mok = !EDGE || m < p.M;
+            stage_put<RB, 32>(reg, zt, lane);
+            stage_fence();
+            if (i + 1 < FM) stage_fetch<RB, 32, EDGE>(zt, zrows(i + 1), p.ldz * 2, rows_ok - (i + 1) * 32, cols_ok * 4, lane);
             stage_fence();
 #pragma unroll
-            for (int fi = 0; fi < FPP; ++fi) {
-                const int i = ps * FPP + fi, m = mw + i * 32 + lrow;
-                const bool mok = !EDGE || m < p.M;
+            for (int j = 0; j < FN; ++j)
 #pragma unroll
-                for (int j = 0; j < FN; ++j)
+                for (int g = 0; g < 4; ++g) {
+                    const int nl = j * 32 + g * 8 + lhalf * 4;
+                    const bool ok = mok && (!EDGE || nw + nl < p.N);
+                    u32x4 *slot = reinterpret_cast<u32x4 *>(reg + Stage<RB>::unit_addr(ulane, 0, (j * 32 + g * 8) * 4));
+                    const u32x4 z = *slot;
+                    u32x4 dz;
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int nl = j * 32 + g * 8 + lhalf * 4;
-                        const bool ok = mok && (!EDGE || nw + nl < p.N);
-                        u32x4 *slot = reinterpret_cast<u32x4 *>(reg + Stage<RB>::unit_addr(ulane, fi, (j * 32 + g * 8) * 4));
-                        const u32x4 z = *slot;
-                        u32x4 dz;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float d = acc[i][j][4 * g + e];
-                            const float gg = bf16_lo(z[e]), uu = bf16_hi(z[e]);
-                            const float sg = fast_sigmoid(gg), sl = gg * sg;
-                            const float dU = d * sl, dG = d * uu * (sg + sl * (1.0f - sg));
-                            dz[e] = pack_bf16x2(dG, dU);
-                            if (want_red && ok) rsum[i] += gg * dG + uu * dU;
-                        }
-                        *slot = dz;
-                        asm volatile("" : "+v"(rsum[i]));   // keep the row statistic's add chain in place (see above)
-                        if (g & 1) __builtin_amdgcn_sched_barrier(0);
+                    for (int e = 0; e < 4; ++e) {
+                        const float d = acc[i][j][4 * g + e];
+                        const float gg = bf16_lo(z[e]), uu = bf16_hi(z[e]);
+                        const float sg = fast_sigmoid(gg), sl = gg * sg;
+                        const float dU = d * sl, dG = d * uu * (sg + sl * (1.0f - sg));
+                        dz[e] = pack_bf16x2(dG, dU);
+                        if (want_red && ok) rsum[i] += gg * dG + uu * dU;
                     }
-            }
+                    *slot = dz;
+                    asm volatile("" : "+v"(rsum[i]));   // keep the row statistic's add chain in place (see above)
+                    if (g & 1) __builtin_amdgcn_sched_barrier(0);
+                }
             stage_fence();
-            stage_store<RB, P, EDGE>(reg, reinterpret_cast<unsigned char *>(outp + (int64_t)(mw + r0) * p.ld_out + 2 * nw), p.ld_out * 2,
-                                     rows_ok - r0, cols_ok * 4, lane);
+            stage_store<RB, 32, EDGE>(reg, reinterpret_cast<unsigned char *>(outp + (int64_t)(mw + i * 32) * p.ld_out + 2 * nw), p.ld_out * 2,
+                                      rows_ok - i * 32, cols_ok * 4, lane);
             stage_fence();
         }
         if (p.out2) {
