@@ -21,13 +21,13 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
-SOURCES = ["coda_api.hip", "aux_kernels.hip", "baseline_kernels.hip",
+SOURCES = ["coda_api.hip", "aux_kernels.hip", "baseline_kernels.hip", "calib_kernels.hip",
            "gemm_inst_nn.hip", "gemm_inst_nt.hip", "gemm_inst_tn.hip", "gemm_inst_tt.hip"]
 
 
 def _headers():
     return [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hpp", ".h"))] + \
-           [os.path.join(os.path.dirname(HERE), "include", "coda.h")]
+           [os.path.join(os.path.dirname(HERE), "include", h) for h in ("coda.h", "coda_unfused.h", "coda_calib.h")]
 
 
 def _compile(src, force):

@@ -23,12 +23,13 @@ def declared_symbols(header):
 
 def test_library_exports_every_declared_symbol(coda):
     lib = ctypes.CDLL(coda.LIB_PATH)
-    names = declared_symbols("coda.h") + declared_symbols("coda_unfused.h")
+    names = declared_symbols("coda.h") + declared_symbols("coda_unfused.h") + declared_symbols("coda_calib.h")
     assert "coda_gemm" in names and "coda_unfused_swiglu_bwd" in names
     for n in names:
         assert hasattr(lib, n), "libcoda.so does not export %s" % n
     assert set(coda.EXPORTS) == set(declared_symbols("coda.h"))
     assert set(coda.EXPORTS_UNFUSED) == set(declared_symbols("coda_unfused.h"))
+    assert set(coda.EXPORTS_CALIB) == set(declared_symbols("coda_calib.h"))
 
 
 def test_binding_mirrors_header_enums(coda):
