@@ -41,6 +41,10 @@ def main():
     ap.add_argument("--no-unfused", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the MFMA-only ceiling measurement")
+    ap.add_argument("--operand-data", choices=["synthetic", "zeros"], default="synthetic",
+                    help="'zeros' replaces every bf16 / fp32 input by zeros after generation: same kernels, same traffic, no "
+                         "operand-bit toggling -- shows how far the power-limited clock, rather than the kernel, sets the rate. "
+                         "Not the benchmark; the JSON line says so in `data`.")
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (known traffic) so that rocprofv3 --pmc "
@@ -71,6 +75,9 @@ def main():
     dY, Z = bf(bw["dY"]), bf(bw["Z"])
     Gbuf = torch.from_numpy(bw["G"]).to(dev)
     gamma = torch.ones(d, dtype=torch.float32, device=dev)   # unfused leg only (gamma folded = identity)
+    if args.operand_data == "zeros":
+        for t in (X, Wup, H, Wdn, R, dY, Z, Gbuf):
+            t.zero_()
 
     f32 = dict(dtype=torch.float32, device=dev)
     b16 = dict(dtype=torch.bfloat16, device=dev)
@@ -132,7 +139,8 @@ def main():
     out = {
         "metric": "fused GEMM+epilogue TFLOP/s", "value": round(value, 2), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic" if args.operand_data == "synthetic" else "all-zero operands (clock-ceiling probe, not the benchmark)",
         "config": {"workload": "llama3-1b-style MLP block fwd+bwd (up+rstd+SwiGLU, down+residual+sumsq, "
                                "dY*Wdown^T+SwiGLU-bwd, H^T*dY fp32-accumulate) + aux reductions",
                    "tokens": M, "hidden": d, "intermediate": F, "flop_per_step": total_flops},
