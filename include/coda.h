@@ -22,7 +22,8 @@
  *  - "row" means a row of the GEMM output (a token): a row scale multiplies
  *    row i by r[i], a row reduction sums over the columns of row i.
  *  - Alignment: every matrix pointer 16-byte aligned, every ld a multiple of 8
- *    elements; vectors 4-byte aligned.
+ *    elements; vectors 4-byte aligned.  Every ld is at most 4194304 elements
+ *    (CODA_ERR_SHAPE beyond that: per-lane offsets are formed in 32 bits).
  *  - Errors are return codes; on any error nothing has been enqueued.
  *  - Outputs must not alias inputs, except the in/out buffer of ACCUM_F32.
  */

@@ -17,6 +17,9 @@ coda_status launch_status(hipError_t e)
     return CODA_ERR_LAUNCH;
 }
 
+// The kernels form per-lane byte offsets of up to 256 rows in 32 bits: row pitches are bounded accordingly.
+constexpr int64_t MAX_LD = int64_t(1) << 22;
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 
@@ -26,7 +29,7 @@ coda_status check_operand(const coda_mat *X, int64_t r, int64_t c)
     if (!X) return CODA_ERR_NULL;
     if (X->dtype != CODA_BF16) return CODA_ERR_DTYPE;
     const int64_t sr = X->trans ? c : r, sc = X->trans ? r : c;
-    if (X->rows != sr || X->cols != sc || X->ld < sc) return CODA_ERR_SHAPE;
+    if (X->rows != sr || X->cols != sc || X->ld < sc || X->ld > MAX_LD) return CODA_ERR_SHAPE;
     if (sr > 0 && sc > 0 && !X->ptr) return CODA_ERR_NULL;
     if (!aligned16(X->ptr) || (X->ld & 7)) return CODA_ERR_ALIGN;
     return CODA_OK;
@@ -35,7 +38,7 @@ coda_status check_operand(const coda_mat *X, int64_t r, int64_t c)
 coda_status check_tile(const void *p, int64_t ld, int64_t width)
 {
     if (!p) return CODA_ERR_NULL;
-    if (ld < width) return CODA_ERR_SHAPE;
+    if (ld < width || ld > MAX_LD) return CODA_ERR_SHAPE;
     if (!aligned16(p) || (ld & 7)) return CODA_ERR_ALIGN;
     return CODA_OK;
 }
@@ -187,7 +190,7 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
             if ((pair || rmsbwd) && f32) return CODA_ERR_PROGRAM;
             const int64_t width = pair == 1 ? N / 2 : pair == 2 ? 2 * N : N;
             if (!op.out) return CODA_ERR_NULL;
-            if (op.ld_out < width) return CODA_ERR_SHAPE;
+            if (op.ld_out < width || op.ld_out > MAX_LD) return CODA_ERR_SHAPE;
             if (!aligned16(op.out) || (op.ld_out & (f32 ? 3 : 7))) return CODA_ERR_ALIGN;
             p.out = op.out;
             p.ld_out = op.ld_out;
@@ -200,7 +203,7 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
         case CODA_EPI_ACCUM_F32:
             if (stage > 0 || pair) return CODA_ERR_PROGRAM;
             if (!op.out) return CODA_ERR_NULL;
-            if (op.ld_out < N) return CODA_ERR_SHAPE;
+            if (op.ld_out < N || op.ld_out > MAX_LD) return CODA_ERR_SHAPE;
             if (!aligned16(op.out) || (op.ld_out & 3)) return CODA_ERR_ALIGN;
             p.out = op.out;
             p.ld_out = op.ld_out;

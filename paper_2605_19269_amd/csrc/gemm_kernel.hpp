@@ -1084,7 +1084,12 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 #pragma unroll
         for (int t = 0; t < S - 1; ++t)
             if (t < KT) issue(t);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // short prologue: wait for everything issued
+        // only tile 0 has to have landed; loads retire in order, so tiles 1 .. S-2 may stay in flight
+        if (KT >= S - 1) {
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
         __syncthreads();
         read_frags(fa0, fb0, 0, 0);
 

@@ -69,6 +69,9 @@ def test_argument_errors_are_status_codes(coda):
     assert g(64, 60, 32, A, _mat(coda, P, 32, 60, ld=64), [store]) == coda.CODA_ERR_SHAPE   # N % 8
     assert g(64, 64, 32, A, B, [_op(coda, coda.CODA_EPI_STORE, out=None, ld_out=64)]) == coda.CODA_ERR_NULL
     assert g(64, 64, 32, A, B, [_op(coda, coda.CODA_EPI_STORE, out=P, ld_out=32)]) == coda.CODA_ERR_SHAPE
+    # row pitches beyond 2^22 elements are refused (32-bit lane offsets in the kernels)
+    assert g(64, 64, 32, _mat(coda, P, 64, 32, ld=(1 << 22) + 8), B, [store]) == coda.CODA_ERR_SHAPE
+    assert g(64, 64, 32, A, B, [_op(coda, coda.CODA_EPI_STORE, out=P, ld_out=(1 << 22) + 8)]) == coda.CODA_ERR_SHAPE
     # transposed operands are described as stored ([K x M]); M == 0 so nothing is launched
     assert g(0, 64, 32, _mat(coda, P, 32, 0, ld=8, trans=1), B, [store]) == coda.CODA_OK
     assert g(0, 64, 32, _mat(coda, P, 0, 32, ld=32, trans=1), B, [store]) == coda.CODA_ERR_SHAPE
