@@ -285,6 +285,37 @@ def main():
                                                               "tflops": round(flops["up"] / ms_cold * 1e-9, 1)}
         del sets
 
+        # GEMM -> residual -> RMSNorm -> GEMM (Section 3.2.1) at 16K tokens, square weights of width d: fused = two GEMMs
+        # with epilogues + the aux combine; unfused = plain GEMM, add + sum-of-squares kernel, aux, normalise kernel, plain GEMM
+        grrg = {}
+        for dd in (2048, 4096, 8192):
+            Mg = 16384
+            x0, w0, w1, rz = rnd((Mg, dd)), rnd((dd, dd), 0.02), rnd((dd, dd), 0.02), rnd((Mg, dd))
+            h1, y2, t0, xn = (torch.empty((Mg, dd), **b16) for _ in range(4))
+            nbg = coda.coda_row_partial_blocks(dd)
+            pg, ssg, rg = torch.empty((nbg, Mg), **f32), torch.empty(Mg, **f32), torch.empty(Mg, **f32)
+            ones = torch.ones(dd, **f32)
+
+            def f_fused():
+                coda.coda_gemm(x0, w0, [coda.add_tile(rz), coda.row_sumsq(pg), coda.store(h1)])
+                coda.coda_row_finalize(pg, Mg, nbg, rstd_out=rg, d=dd, eps=1e-6)
+                coda.coda_gemm(h1, w1, [coda.row_scale(rg), coda.store(y2)])
+
+            def f_unf():
+                coda.coda_gemm(x0, w0, [coda.store(t0)])
+                coda.coda_unfused_add_sumsq(t0, rz, h1, ssg)
+                coda.coda_row_finalize(ssg.view(1, Mg), Mg, 1, rstd_out=rg, d=dd, eps=1e-6)
+                coda.coda_unfused_rmsnorm_apply(h1, rg, ones, xn)
+                coda.coda_gemm(xn, w1, [coda.store(y2)])
+            ms_f, ms_u = 1e9, 1e9
+            for _ in range(2):
+                ms_u = min(ms_u, time_kernel(f_unf, reps=5, warm=2))
+                ms_f = min(ms_f, time_kernel(f_fused, reps=5, warm=2))
+            grrg["d%d" % dd] = {"fused_ms": round(ms_f, 4), "unfused_ms": round(ms_u, 4), "speedup": round(ms_u / ms_f, 4),
+                                "fused_tflops": round(4.0 * Mg * dd * dd / ms_f * 1e-9, 1)}
+            del x0, w0, w1, rz, h1, y2, t0, xn
+        out["extra_kernels"]["gemm_residual_rmsnorm_gemm_16k_tokens"] = grrg
+
         # GEMM + SwiGLU at square sizes and at a hidden size of 8192 (70B-style up-projection)
         for name, (Ms, Ns, Ks) in {"swiglu_4096_cubed": (4096, 4096, 4096), "swiglu_8192_cubed": (8192, 8192, 8192),
                                    "up_70b_style": (8192, 2 * 28672, 8192)}.items():
