@@ -1,4 +1,4 @@
-"""Full-size parity: the BASELINE workloads at their real shapes, launched exactly as bench.py launches
+"""Full-size parity: the benchmark workloads at their real shapes, launched exactly as bench.py launches
 them (same programs, same layouts, whole-tile fast kernel), checked on a deterministic sample of output rows
 that the oracle computes one by one.  Every epilogue on the path is row-local, so sampled rows are exact; the
 weight gradient is sampled over its own output rows."""
