@@ -285,6 +285,14 @@ def main():
                                                               "tflops": round(flops["up"] / ms_cold * 1e-9, 1)}
         del sets
 
+        # outside context, not a path of this library: the vendor GEMM (torch.matmul -> hipBLASLt) on the shapes of the step,
+        # plain bf16 output, no epilogue work
+        ctx = {}
+        for name, (a_, b_) in {"up_8192x16384x2048": (X, Wup), "down_8192x2048x8192": (H, Wdn)}.items():
+            ms_t = min(time_kernel(lambda: torch.matmul(a_, b_), reps=10, warm=3) for _ in range(2))
+            ctx[name] = {"ms": round(ms_t, 4), "tflops": round(2.0 * a_.shape[0] * a_.shape[1] * b_.shape[1] / ms_t * 1e-9, 1)}
+        out["context_vendor_gemm_torch_matmul"] = ctx
+
         # GEMM -> residual -> RMSNorm -> GEMM (Section 3.2.1) at 16K tokens, square weights of width d: fused = two GEMMs
         # with epilogues + the aux combine; unfused = plain GEMM, add + sum-of-squares kernel, aux, normalise kernel, plain GEMM
         grrg = {}
