@@ -285,6 +285,24 @@ def main():
                                                               "tflops": round(flops["up"] / ms_cold * 1e-9, 1)}
         del sets
 
+        # split-K on shapes with few output tiles: the same call with and without the workspace that enables it
+        spk = {}
+        for (Ms, Ns, Ks) in ((512, 512, 8192), (1024, 1024, 8192), (2048, 2048, 8192)):
+            xs, ws_, rs_ = rnd((Ms, Ks)), rnd((Ks, Ns), 0.02), rnd((Ms, Ns))
+            ys = torch.empty((Ms, Ns), **b16)
+            nbs = coda.coda_row_partial_blocks(Ns)
+            ps = torch.empty((nbs, Ms), **f32)
+            wsp = torch.empty(coda.coda_gemm_workspace_bytes(Ms, Ns, Ks, []), dtype=torch.uint8, device=dev)
+            prog = lambda: [coda.add_tile(rs_), coda.row_sumsq(ps), coda.store(ys)]
+            ms_1 = min(time_kernel(lambda: coda.coda_gemm(xs, ws_, prog()), reps=10, warm=3) for _ in range(2))
+            ms_k = min(time_kernel(lambda: coda.coda_gemm(xs, ws_, prog(), workspace=wsp), reps=10, warm=3) for _ in range(2))
+            fls = 2.0 * Ms * Ns * Ks
+            spk["%dx%dx%d" % (Ms, Ns, Ks)] = {"tiles": (Ms // 256) * (Ns // 256), "workspace_mb": round(wsp.numel() / 1e6, 1),
+                                              "unsplit_ms": round(ms_1, 4), "unsplit_tflops": round(fls / ms_1 * 1e-9, 1),
+                                              "split_ms": round(ms_k, 4), "split_tflops": round(fls / ms_k * 1e-9, 1)}
+            del xs, ws_, rs_, ys, wsp
+        out["extra_kernels"]["split_k_residual_sumsq"] = spk
+
         # outside context, not a path of this library: the vendor GEMM (torch.matmul -> hipBLASLt) on the shapes of the step,
         # plain bf16 output, no epilogue work
         ctx = {}

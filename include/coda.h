@@ -171,13 +171,22 @@ typedef struct coda_epi_op {
  * multiple of 8; and M a multiple of 8 when A is used transposed.  No other
  * divisibility is required (edge tiles are predicated).
  *
- * workspace / workspace_bytes: scratch of at least
- * coda_gemm_workspace_bytes(...) bytes (currently always 0; may be NULL).
+ * workspace / workspace_bytes (device memory, 16-byte aligned; may be NULL): scratch for split-K.
+ * Shapes made of whole 256 x 256 x 64 tiles with at most 64 output tiles and K >= 2048 leave
+ * most of the chip idle; for them coda_gemm_workspace_bytes returns a non-zero size, and a call
+ * that brings that much workspace lets 2 to 8 workgroups share every output tile, each
+ * contracting a contiguous part of K: partial tiles go to the workspace in fp32, the workgroup
+ * that finishes last adds them up in a fixed order (the result does not depend on arrival
+ * order) and runs the epilogue program on the sum.  Without a workspace (NULL) the same shape
+ * runs unsplit.  A non-NULL workspace smaller than coda_gemm_workspace_bytes(...) is
+ * CODA_ERR_WORKSPACE.  The workspace needs no initialisation and holds nothing between calls;
+ * two calls that share one must not overlap in time.
  */
 coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_mat *A,
                       const coda_mat *B, const coda_epi_op *prog /* host */, int32_t n_ops,
                       void *workspace, size_t workspace_bytes);
 
+/* Bytes of workspace that enable split-K for this shape; 0 when the shape is not split (the program does not matter). */
 size_t coda_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, const coda_epi_op *prog /* host */,
                                  int32_t n_ops);
 

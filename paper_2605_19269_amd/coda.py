@@ -192,12 +192,15 @@ def coda_gemm_raw(stream, M, N, K, A, B, ops, workspace=None, workspace_bytes=0)
                           workspace, workspace_bytes)
 
 
-def coda_gemm(A, B, ops, transA=False, transB=False, stream=None):
-    """D = op(A) op(B), then the epilogue ops in order.  A, B: 2-D bf16 CUDA tensors as stored."""
+def coda_gemm(A, B, ops, transA=False, transB=False, stream=None, workspace=None):
+    """D = op(A) op(B), then the epilogue ops in order.  A, B: 2-D bf16 CUDA tensors as stored.
+    workspace: optional device tensor of at least coda_gemm_workspace_bytes(...) bytes (enables split-K)."""
     a, b = mat(A, transA), mat(B, transB)
     M, K = (A.shape[1], A.shape[0]) if transA else (A.shape[0], A.shape[1])
     N = B.shape[0] if transB else B.shape[1]
-    _check(coda_gemm_raw(_stream(stream), M, N, K, a, b, list(ops)))
+    ws_ptr = None if workspace is None else workspace.data_ptr()
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(coda_gemm_raw(_stream(stream), M, N, K, a, b, list(ops), ws_ptr, ws_bytes))
 
 
 def coda_gemm_workspace_bytes(M, N, K, ops):

@@ -68,6 +68,13 @@ struct GemmParams {
     // target column y[M] and the selected logit z_tgt[M]
     float *lse_max, *lse_sum, *lse_tgt;
     const int *lse_y;
+    // split-K (fast kernel only; splitk <= 1 = off): `splitk` workgroups share one output tile, each contracting a
+    // contiguous part of K.  Every workgroup leaves its fp32 partial tile in ws_part[tile * splitk + split] and takes a
+    // ticket from ws_cnt[tile] (zeroed before the launch); the last one to arrive adds the partials up in split order
+    // and runs the epilogue.
+    int splitk;
+    float *ws_part;
+    unsigned *ws_cnt;
 };
 
 // ---------------------------------------------------------------------------------
@@ -1025,8 +1032,10 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % C::WGM, wn = wave / C::WGM;
+    const int nsplit = p.splitk > 1 ? p.splitk : 1;
+    const int tile_id = (int)blockIdx.x / nsplit, split = (int)blockIdx.x % nsplit;
     int tm, tn;
-    tile_coords(blockIdx.x, gridDim.x, p.tiles_m, p.tiles_n, tm, tn);
+    tile_coords(tile_id, (int)gridDim.x / nsplit, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
     f32x16 acc[FM][FN];
@@ -1037,7 +1046,10 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    const int KT = p.K / BK;
+    // this workgroup's part of the contraction: K-steps [kbeg, kbeg + KT)
+    const int KT_all = p.K / BK;
+    const int kbeg = (int)((int64_t)KT_all * split / nsplit);
+    const int KT = (int)((int64_t)KT_all * (split + 1) / nsplit) - kbeg;
 
     // loop-invariant per-lane byte offsets of this wave's chunks; wave w issues wave-loads w*L .. w*L+L-1
     uint32_t offa[LA], offb[LB];
@@ -1046,10 +1058,10 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 #pragma unroll
     for (int i = 0; i < LB; ++i) offb[i] = dl_goffset<C, BN, BKC>(wave * LB + i, lane, p.ldb);
     // scalar bases of the tile's first element; advance by one K-step per tile
-    const unsigned char *ga = reinterpret_cast<const unsigned char *>(AK ? p.A + (int64_t)m0 * p.lda : p.A + m0);
-    const unsigned char *gb = reinterpret_cast<const unsigned char *>(BKC ? p.B + (int64_t)n0 * p.ldb : p.B + n0);
     const int64_t stepa = AK ? (int64_t)BK * 2 : (int64_t)BK * p.lda * 2;
     const int64_t stepb = BKC ? (int64_t)BK * 2 : (int64_t)BK * p.ldb * 2;
+    const unsigned char *ga = reinterpret_cast<const unsigned char *>(AK ? p.A + (int64_t)m0 * p.lda : p.A + m0) + kbeg * stepa;
+    const unsigned char *gb = reinterpret_cast<const unsigned char *>(BKC ? p.B + (int64_t)n0 * p.ldb : p.B + n0) + kbeg * stepb;
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
 
     auto issue = [&](int t) {  // loads of tile t into slot t % S
@@ -1114,6 +1126,56 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
         mma(fa1, fb1);
     }
     __syncthreads();  // every wave is done with the operand ring before the epilogue reuses it
+
+    if (nsplit > 1) {
+        // Partial tile -> workspace in register order: float4 q of thread t at [q][t], fully coalesced.  The layout is
+        // private to this exchange.
+        constexpr int NQ = FM * FN * 4;
+        f32x4 *part = reinterpret_cast<f32x4 *>(p.ws_part) + (size_t)tile_id * nsplit * NQ * C::NT;
+        f32x4 *mine = part + (size_t)split * NQ * C::NT + tid;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    mine[((i * FN + j) * 4 + q) * C::NT] = f32x4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        // Completed stores sit in this XCD's L2 (the vector L1 writes through).  One thread then does the device-scope
+        // release (L2 write-back) for the whole workgroup, takes the ticket, and -- if it is the last -- the acquire
+        // (L2 / L1 invalidate) on behalf of all waves of this compute unit.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        int *last = reinterpret_cast<int *>(red);
+        if (tid == 0) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            const unsigned ticket = __hip_atomic_fetch_add(p.ws_cnt + tile_id, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int is_last = ticket == (unsigned)(nsplit - 1);
+            if (is_last) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            *last = is_last;
+        }
+        __syncthreads();
+        if (!*last) return;          // uniform: the whole workgroup leaves; nobody waits for anybody
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+        for (int sp = 0; sp < nsplit; ++sp) {      // fixed order: the sum does not depend on who arrived last
+            const f32x4 *src = part + (size_t)sp * NQ * C::NT + tid;
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f32x4 v = src[((i * FN + j) * 4 + q) * C::NT];
+                        acc[i][j][4 * q] += v[0]; acc[i][j][4 * q + 1] += v[1];
+                        acc[i][j][4 * q + 2] += v[2]; acc[i][j][4 * q + 3] += v[3];
+                    }
+        }
+        __syncthreads();             // `red` (the flag) is reused by the epilogue
+    }
 
     run_epilogue<C, EPI, false, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
 }

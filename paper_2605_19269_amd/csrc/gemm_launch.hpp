@@ -25,7 +25,8 @@ hipError_t launch_gemm(const GemmParams &p_in, hipStream_t stream)
         using C = FastCfg;
         p.tiles_m = p.M / C::BM;
         p.tiles_n = p.N / C::BN;
-        hipLaunchKernelGGL((gemm_kernel_dl<C, AK, BKC, EPI>), dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(C::NT), 0, stream, p);
+        const unsigned nsplit = p.splitk > 1 ? (unsigned)p.splitk : 1u;
+        hipLaunchKernelGGL((gemm_kernel_dl<C, AK, BKC, EPI>), dim3((unsigned)(p.tiles_m * p.tiles_n) * nsplit), dim3(C::NT), 0, stream, p);
     }
     return hipGetLastError();
 }

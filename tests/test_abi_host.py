@@ -140,3 +140,22 @@ def test_aux_argument_errors(coda):
     assert coda.coda_row_partial_blocks(2048) * 256 >= 2048
     assert coda.coda_gemm_workspace_bytes(8, 8, 8, []) == 0
     assert coda.coda_status_string(coda.CODA_ERR_PROGRAM) == "unsupported epilogue program"
+
+
+def test_splitk_workspace_planning_and_errors(coda):
+    """Host logic only: which shapes are planned for split-K, how much workspace they ask for, and the status codes
+    of a workspace that is too small or misaligned (returned before anything is launched)."""
+    wb = lambda M, N, K: coda.coda_gemm_workspace_bytes(M, N, K, [])
+    tile = 256 * 256 * 4
+    assert wb(512, 512, 4096) == 1024 + 4 * 4 * tile        # 4 tiles, K / 1024 = 4 parts
+    assert wb(256, 256, 8192) == 1024 + 1 * 8 * tile        # 1 tile, capped at 8 parts
+    assert wb(2048, 2048, 8192) == 1024 + 64 * 4 * tile     # 64 tiles: 4 parts fill the 256 compute units
+    assert wb(2048, 2048 + 256, 8192) == 0                  # 72 tiles: more than a quarter of the chip already busy
+    assert wb(512, 512, 1024) == 0                          # contraction too short to split
+    assert wb(512, 512, 4096 + 32) == 0                     # not whole tiles: edge kernel, never split
+    assert wb(0, 512, 4096) == 0 and wb(-1, 512, 4096) == 0
+    A, B = _mat(coda, P, 512, 4096), _mat(coda, P, 4096, 512)
+    store = _op(coda, coda.CODA_EPI_STORE, out=P, ld_out=512)
+    need = wb(512, 512, 4096)
+    assert coda.coda_gemm_raw(None, 512, 512, 4096, A, B, [store], P, need - 1) == coda.CODA_ERR_WORKSPACE
+    assert coda.coda_gemm_raw(None, 512, 512, 4096, A, B, [store], P + 4, need) == coda.CODA_ERR_ALIGN
