@@ -19,7 +19,7 @@ __all__ = [
     "build", "lib_path", "num_threads", "bf16_bits_to_f64", "row_sumsq", "rstd", "rstd_from_sumsq",
     "gemm_rowscale", "gemm_rowscale_lse", "gemm_rowscale_rope", "gemm_rowscale_swiglu", "gemm_residual_sumsq", "gemm_swiglu_bwd",
     "gemm_accumulate", "gemm_rmsnorm_bwd", "rmsnorm_linear_unfused", "rmsnorm_linear_reparam", "mlp_block",
-    "fold_gamma", "interleave_pairs", "swiglu_fwd_points", "swiglu_bwd_points",
+    "fold_gamma", "interleave_pairs", "swiglu_fwd_points", "swiglu_bwd_points", "f8e4m3_to_bf16_bits",
 ]
 
 
@@ -349,3 +349,12 @@ def swiglu_bwd_points(d, g, u):
     dG, dU = np.empty_like(g), np.empty_like(g)
     _check(_load().coda_oracle_swiglu_bwd_points(_p(d), _p(g), _p(u), _i64(g.size), _p(dG), _p(dU)))
     return dG, dU
+
+
+def f8e4m3_to_bf16_bits(bits):
+    """OCP E4M3 bytes (uint8 array, any shape) -> the bf16 bit patterns of the same values (exact); the result can be
+    passed to every gemm_* function above in place of a bf16 operand."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    out = np.empty(bits.shape, np.uint16)
+    _check(_load().coda_oracle_f8e4m3_to_bf16(_p(bits), _i64(bits.size), _p(out)))
+    return out

@@ -30,7 +30,9 @@
  * definition; the row statistic vs sum(Z * dZ); the weight gradient vs finite
  * differences of <dY, H W>; RoPE vs complex multiplication by a library, norm preservation, the
  * relative-position property; the RMSNorm-backward kernel vs reverse-mode autodiff of a library RMSNorm;
- * the log-sum-exp kernel vs a library logsumexp / cross-entropy, shift invariance and the uniform case.  No function here is "parity unpinned".
+ * the log-sum-exp kernel vs a library logsumexp / cross-entropy, shift invariance and the uniform case; the 8-bit
+ * operand decoder vs the values the OFP8 specification names and vs a library's conversion of all 256 codes.
+ * No function here is "parity unpinned".
  *
  * Naming: "row scale" multiplies row i by r[i]; "column scale" multiplies
  * column j by gamma[j]; a "row reduction" sums over columns and yields one
@@ -671,6 +673,34 @@ int coda_oracle_mlp_block(const uint16_t *X, int64_t ldx, const double *gamma, d
             ss[q] = s;
     }
     free(r); free(Xd); free(W1d); free(W2d); free(Zm); free(H);
+    return ORACLE_OK;
+}
+
+/* ---- 8-bit operands ------------------------------------------------------------- */
+
+/* OCP 8-bit floating point, E4M3 (OFP8 specification): 1 sign, 4 exponent (bias 7), 3 mantissa bits; no
+   infinities; S.1111.111 is NaN; exponent field 0 is subnormal: (-1)^s * 2^-6 * (m / 8); otherwise
+   (-1)^s * 2^(e - 7) * (1 + m / 8).  Every such value is exactly representable in bf16, so 8-bit operands reach
+   the GEMM definitions above as the bf16 bit patterns of the same numbers: out[i] = bf16 bits of decode(in[i]). */
+int coda_oracle_f8e4m3_to_bf16(const uint8_t *in, int64_t n, uint16_t *out)
+{
+    if (n < 0 || (n > 0 && (!in || !out))) return ORACLE_ERR_ARG;
+    for (int64_t i = 0; i < n; ++i) {
+        const unsigned b = in[i], sgn = b >> 7, e = (b >> 3) & 15u, m = b & 7u;
+        double v;
+        if (e == 15u && m == 7u)
+            v = NAN;
+        else if (e == 0u)
+            v = ldexp((double)m / 8.0, -6);
+        else
+            v = ldexp(1.0 + (double)m / 8.0, (int)e - 7);
+        if (sgn) v = -v;
+        float f = (float)v;      /* exact: at most 4 significant bits */
+        uint32_t u;
+        memcpy(&u, &f, sizeof u);
+        if (v == v && (u & 0xffffu) != 0u) return ORACLE_ERR_ARG;   /* cannot happen for E4M3 */
+        out[i] = (uint16_t)(u >> 16);
+    }
     return ORACLE_OK;
 }
 

@@ -23,6 +23,25 @@ def normal_bf16(rng, shape, std):
     return f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32) * np.float32(std))
 
 
+def f32_to_f8e4m3_bits(x):
+    """Round-to-nearest-even fp32 -> OCP E4M3 bytes (uint8), saturating at +-448 (finite inputs).  Storage rounding of
+    synthetic inputs only: 8-bit operands are an input format of the GEMM, not part of its arithmetic."""
+    codes = np.arange(127)                                         # 0x00 .. 0x7E: the non-negative finite codes, ascending
+    e, m = codes >> 3, codes & 7
+    vals = np.where(e == 0, m / 8.0 * 2.0 ** -6, (1.0 + m / 8.0) * 2.0 ** (e - 7.0))
+    mids = (vals[:-1] + vals[1:]) / 2.0
+    a = np.abs(np.asarray(x, dtype=np.float64))
+    idx = np.searchsorted(mids, a, side="left")                    # mids[idx-1] < a <= mids[idx]
+    tie = (idx < 126) & (a == mids[np.minimum(idx, 125)])
+    idx = np.where(tie & (idx % 2 == 1), idx + 1, idx)             # a tie goes to the code with an even mantissa
+    out = idx.astype(np.uint8)
+    return np.where(np.signbit(np.asarray(x, dtype=np.float64)), out | np.uint8(0x80), out).astype(np.uint8)
+
+
+def normal_f8e4m3(rng, shape, std):
+    return f32_to_f8e4m3_bits(rng.standard_normal(shape, dtype=np.float32) * np.float32(std))
+
+
 def normal_f32(rng, shape, std):
     return rng.standard_normal(shape, dtype=np.float32) * np.float32(std)
 

@@ -504,3 +504,51 @@ def test_lse_closed_forms(oracle):
     # scaling the row by r scales every logit: lse(r*z) for r = 2 on the constant row
     _, _, lse2 = oracle.gemm_rowscale_lse(rowc, I, y0, r=np.array([2.0]))
     assert abs(lse2[0] - (6.0 + math.log(N))) < 1e-14
+
+
+# ---- 8-bit operands (OCP E4M3) --------------------------------------------------------------------------------
+def test_f8e4m3_decoder_named_values(oracle):
+    """Values the OFP8 specification names for E4M3: bias 7, max normal 448 (0x7E), min normal 2^-6 (0x08), max
+    subnormal 0.875 * 2^-6 (0x07), min subnormal 2^-9 (0x01), no infinities, S.1111.111 = NaN, signed zeros."""
+    dec = lambda codes: oracle.bf16_bits_to_f64(oracle.f8e4m3_to_bf16_bits(np.array(codes, dtype=np.uint8)))
+    named = {0x00: 0.0, 0x01: 2.0 ** -9, 0x07: 0.875 * 2.0 ** -6, 0x08: 2.0 ** -6, 0x38: 1.0, 0x39: 1.125, 0x3C: 1.5,
+             0x40: 2.0, 0x77: 240.0, 0x78: 256.0, 0x7E: 448.0, 0xB8: -1.0, 0xC0: -2.0, 0xFE: -448.0}
+    got = dec(list(named.keys()))
+    assert np.array_equal(got, np.array(list(named.values())))
+    assert np.isnan(dec([0x7F, 0xFF])).all()
+    assert np.signbit(dec([0x80]))[0] and dec([0x80])[0] == 0.0
+    pos = dec(list(range(0x7F)))
+    assert (np.diff(pos) > 0).all(), "codes 0x00..0x7E must be strictly increasing"
+    assert np.array_equal(dec(list(range(0x80, 0xFF))), -pos)
+
+
+def test_f8e4m3_decoder_vs_library_all_codes(oracle):
+    codes = np.arange(256, dtype=np.uint8)
+    got = oracle.bf16_bits_to_f64(oracle.f8e4m3_to_bf16_bits(codes))
+    lib = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    assert np.array_equal(np.isnan(got), np.isnan(lib))
+    ok = ~np.isnan(lib)
+    assert np.array_equal(got[ok], lib[ok]) and np.array_equal(np.signbit(got[ok]), np.signbit(lib[ok]))
+
+
+def test_f8e4m3_input_rounding_is_rne_and_round_trips(oracle):
+    """The seeded generator's storage rounding: every finite code survives decode -> encode, ties go to the even
+    mantissa, values beyond 448 saturate, and the rounding agrees with a library conversion on random draws."""
+    codes = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)
+    vals = oracle.bf16_bits_to_f64(oracle.f8e4m3_to_bf16_bits(codes))
+    assert np.array_equal(synth.f32_to_f8e4m3_bits(vals.astype(np.float32)), codes)
+    ties = np.array([1.0625, 1.1875, -1.0625, 2.0 ** -10, 3 * 2.0 ** -10], dtype=np.float32)   # midpoints of neighbours
+    assert list(synth.f32_to_f8e4m3_bits(ties)) == [0x38, 0x3A, 0xB8, 0x00, 0x02]
+    assert list(synth.f32_to_f8e4m3_bits(np.array([449.0, 1e6, -1e6], dtype=np.float32))) == [0x7E, 0x7E, 0xFE]
+    x = (np.random.Generator(np.random.PCG64(3)).standard_normal(100000) * 2.5).astype(np.float32)
+    lib = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(synth.f32_to_f8e4m3_bits(x), lib)
+
+
+def test_gemm_on_f8e4m3_operands_is_the_gemm_of_their_values(oracle):
+    g = np.random.Generator(np.random.PCG64(4))
+    A8, B8 = synth.normal_f8e4m3(g, (24, 40), 1.0), synth.normal_f8e4m3(g, (16, 40), 1.0)
+    got = oracle.gemm_rowscale(oracle.f8e4m3_to_bf16_bits(A8), oracle.f8e4m3_to_bf16_bits(B8), transB=True)
+    Af = torch.from_numpy(A8).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    Bf = torch.from_numpy(B8).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    np.testing.assert_allclose(got, Af @ Bf.T, rtol=1e-13, atol=1e-13)
