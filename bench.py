@@ -285,6 +285,29 @@ def main():
                                                               "tflops": round(flops["up"] / ms_cold * 1e-9, 1)}
         del sets
 
+        # 8-bit operands (OCP E4M3, both K-contiguous) through the same epilogues: the step's forward GEMMs and 8192^3.
+        # Operands ~ N(0,1) rounded to E4M3; the row scale carries rstd times the operands' quantisation scales.
+        def rnd8(shape):
+            return torch.randn(shape, device=dev).to(torch.float8_e4m3fn).view(torch.uint8)
+        f8 = {}
+        x8, w8 = rnd8((M, d)), rnd8((2 * F, d))
+        h8 = torch.empty((M, F), **b16)
+        r8 = rstd * 0.02
+        ms8 = min(time_kernel(lambda: coda.coda_gemm(x8, w8, [coda.row_scale(r8), coda.swiglu_fwd(), coda.store(h8)], transB=True)) for _ in range(3))
+        f8["up_rowscale_swiglu_8192x16384x2048"] = {"ms": round(ms8, 4), "tflops": round(flops["up"] / ms8 * 1e-9, 1)}
+        hh8, wd8 = rnd8((M, F)), rnd8((d, F))
+        y8 = torch.empty((M, d), **b16)
+        ms8 = min(time_kernel(lambda: coda.coda_gemm(hh8, wd8, [coda.row_scale(r8), coda.add_tile(R), coda.row_sumsq(part), coda.store(y8)], transB=True))
+                  for _ in range(3))
+        f8["down_residual_sumsq_8192x2048x8192"] = {"ms": round(ms8, 4), "tflops": round(flops["down"] / ms8 * 1e-9, 1)}
+        a8, b8 = rnd8((8192, 8192)), rnd8((8192, 8192))
+        c8 = torch.empty((8192, 8192), **b16)
+        ms8 = min(time_kernel(lambda: coda.coda_gemm(a8, b8, [coda.row_scale(r8), coda.swiglu_fwd(), coda.store(c8[:, :4096])], transB=True), reps=5)
+                  for _ in range(3))
+        f8["rowscale_swiglu_8192_cubed"] = {"ms": round(ms8, 4), "tflops": round(2.0 * 8192 ** 3 / ms8 * 1e-9, 1)}
+        out["extra_kernels"]["f8e4m3_operands"] = f8
+        del x8, w8, h8, hh8, wd8, y8, a8, b8, c8
+
         # split-K on shapes with few output tiles: the same call with and without the workspace that enables it
         spk = {}
         for (Ms, Ns, Ks) in ((512, 512, 8192), (1024, 1024, 8192), (2048, 2048, 8192)):

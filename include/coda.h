@@ -48,7 +48,8 @@ typedef enum coda_status {
     CODA_ERR_LAUNCH = 7     /* HIP reported an error; see coda_last_hip_error()    */
 } coda_status;
 
-typedef enum coda_dtype { CODA_BF16 = 0, CODA_F32 = 1 } coda_dtype;
+/* CODA_F8E4M3: OCP 8-bit floating point E4M3 (1-4-3, bias 7, max 448, no infinities), one byte per element. */
+typedef enum coda_dtype { CODA_BF16 = 0, CODA_F32 = 1, CODA_F8E4M3 = 2 } coda_dtype;
 
 /*
  * A GEMM operand.  rows/cols/ld describe the matrix AS STORED.
@@ -61,7 +62,7 @@ typedef struct coda_mat {
     const void *ptr; /* device */
     int64_t rows, cols, ld;
     int32_t trans;
-    int32_t dtype; /* coda_dtype; operands must be CODA_BF16 */
+    int32_t dtype; /* coda_dtype; operands are CODA_BF16, or both CODA_F8E4M3 (see coda_gemm) */
 } coda_mat;
 
 /*
@@ -171,6 +172,13 @@ typedef struct coda_epi_op {
  * multiple of 8; and M a multiple of 8 when A is used transposed.  No other
  * divisibility is required (edge tiles are predicated).
  *
+ * 8-bit operands: A and B may both be CODA_F8E4M3 (ld in elements = bytes, a multiple of 16).  The contraction
+ * runs on the fp8 matrix cores with fp32 accumulation of the exact products, and every epilogue program
+ * above applies unchanged (outputs stay bf16 / fp32; quantisation scales of the operands are the caller's
+ * and fold into ROW_SCALE).  This variant exists for whole tiles only: both operands stored with the contraction
+ * index contiguous (A [M x K] with trans = 0, B [N x K] with trans = 1), M and N multiples of 256, K a
+ * multiple of 128; anything else is CODA_ERR_DTYPE (layout, mixed dtypes) or CODA_ERR_SHAPE (sizes).
+ *
  * workspace / workspace_bytes (device memory, 16-byte aligned; may be NULL): scratch for split-K.
  * Shapes made of whole 256 x 256 x 64 tiles with at most 64 output tiles and K >= 2048 leave
  * most of the chip idle; for them coda_gemm_workspace_bytes returns a non-zero size, and a call
@@ -186,7 +194,8 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
                       const coda_mat *B, const coda_epi_op *prog /* host */, int32_t n_ops,
                       void *workspace, size_t workspace_bytes);
 
-/* Bytes of workspace that enable split-K for this shape; 0 when the shape is not split (the program does not matter). */
+/* Bytes of workspace that enable split-K for this shape; 0 when the shape is not split (the program does not matter;
+   the figure is sufficient for bf16 and for 8-bit operands alike). */
 size_t coda_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, const coda_epi_op *prog /* host */,
                                  int32_t n_ops);
 

@@ -21,7 +21,7 @@ _lib = ctypes.CDLL(LIB_PATH)
 # status codes / enums (mirrors of include/coda.h)
 CODA_OK, CODA_ERR_NULL, CODA_ERR_SHAPE, CODA_ERR_ALIGN, CODA_ERR_DTYPE, CODA_ERR_PROGRAM, \
     CODA_ERR_WORKSPACE, CODA_ERR_LAUNCH = range(8)
-CODA_BF16, CODA_F32 = 0, 1
+CODA_BF16, CODA_F32, CODA_F8E4M3 = 0, 1, 2
 (CODA_EPI_ROW_SCALE, CODA_EPI_COL_SCALE_SIDE, CODA_EPI_ADD_TILE, CODA_EPI_SWIGLU_FWD, CODA_EPI_SWIGLU_BWD,
  CODA_EPI_ROW_SUMSQ, CODA_EPI_STORE, CODA_EPI_ACCUM_F32, CODA_EPI_ROPE, CODA_EPI_RMSNORM_BWD, CODA_EPI_LSE_PARTIAL) = range(11)
 CODA_REDUCE_PARTIALS, CODA_REDUCE_ATOMIC, CODA_STORE_F32 = 0, 1, 2
@@ -120,7 +120,12 @@ def mat(t, trans=False):
     """coda_mat describing a 2-D torch tensor as stored (row-major, unit column stride)."""
     import torch
     assert t.dim() == 2 and (t.shape[1] <= 1 or t.stride(1) == 1), "row-major 2-D tensor expected"
-    dt = CODA_BF16 if t.dtype == torch.bfloat16 else CODA_F32
+    if t.dtype == torch.bfloat16:
+        dt = CODA_BF16
+    elif t.dtype in (torch.uint8, torch.float8_e4m3fn):     # raw OCP E4M3 bytes
+        dt = CODA_F8E4M3
+    else:
+        dt = CODA_F32
     return coda_mat(t.data_ptr(), t.shape[0], t.shape[1], t.stride(0), 1 if trans else 0, dt)
 
 

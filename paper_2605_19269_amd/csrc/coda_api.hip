@@ -27,11 +27,11 @@ bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0
 coda_status check_operand(const coda_mat *X, int64_t r, int64_t c)
 {
     if (!X) return CODA_ERR_NULL;
-    if (X->dtype != CODA_BF16) return CODA_ERR_DTYPE;
+    if (X->dtype != CODA_BF16 && X->dtype != CODA_F8E4M3) return CODA_ERR_DTYPE;
     const int64_t sr = X->trans ? c : r, sc = X->trans ? r : c;
     if (X->rows != sr || X->cols != sc || X->ld < sc || X->ld > MAX_LD) return CODA_ERR_SHAPE;
     if (sr > 0 && sc > 0 && !X->ptr) return CODA_ERR_NULL;
-    if (!aligned16(X->ptr) || (X->ld & 7)) return CODA_ERR_ALIGN;
+    if (!aligned16(X->ptr) || (X->ld & (X->dtype == CODA_F8E4M3 ? 15 : 7))) return CODA_ERR_ALIGN;   // 16-byte rows
     return CODA_OK;
 }
 
@@ -222,15 +222,18 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
 // of partial tiles) and whose contraction gives every part at least 32 K-steps of 32.
 // Returns the number of parts (1 = no split).
 constexpr int64_t SPLITK_CUS = 256, SPLITK_MAX = 8, SPLITK_MIN_K = 1024, SPLITK_MAX_TILES = 64;
-int plan_splitk(int64_t M, int64_t N, int64_t K)
+int plan_splitk(int64_t M, int64_t N, int64_t K, bool f8 = false)
 {
     using C = coda::MainCfg;
-    if (M <= 0 || N <= 0 || (M % C::BM) || (N % C::BN) || (K % C::BK)) return 1;
+    if (M <= 0 || N <= 0 || (M % C::BM) || (N % C::BN) || (K % (f8 ? 128 : C::BK))) return 1;
     const int64_t tiles = (M / C::BM) * (N / C::BN);
     if (tiles > SPLITK_MAX_TILES) return 1;
+    const int64_t min_k = f8 ? 2 * SPLITK_MIN_K : SPLITK_MIN_K;   // 32 K-steps of 32 bf16 or of 64 fp8 elements per part
     int64_t s = SPLITK_CUS / tiles;
-    if (s > K / SPLITK_MIN_K) s = K / SPLITK_MIN_K;
+    if (s > K / min_k) s = K / min_k;
     if (s > SPLITK_MAX) s = SPLITK_MAX;
+    // the 8-bit kernel walks its K-steps in pairs: every part must get an even number of them
+    while (f8 && s >= 2 && (K / 64) % (2 * s)) --s;
     return s >= 2 ? (int)s : 1;
 }
 constexpr size_t SPLITK_CNT_BYTES = 1024;   // ticket counters (at most 64 tiles x 4 bytes), kept apart from the partials
@@ -277,6 +280,9 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
     coda_status st;
     if ((st = check_operand(A, M, K)) != CODA_OK) return st;
     if ((st = check_operand(B, K, N)) != CODA_OK) return st;
+    const bool f8 = A->dtype == CODA_F8E4M3 || B->dtype == CODA_F8E4M3;
+    if (f8 && (A->dtype != B->dtype || A->trans || !B->trans)) return CODA_ERR_DTYPE;   // both 8-bit, both K-contiguous
+    if (f8 && ((M % coda::MainCfg::BM) || (N % coda::MainCfg::BN) || (K % 128))) return CODA_ERR_SHAPE;
     if ((K & 7) || (N & 7) || (A->trans && (M & 7))) return CODA_ERR_SHAPE;
     Parsed ps;
     if ((st = parse_program(prog, n_ops, N, ps)) != CODA_OK) return st;
@@ -299,7 +305,7 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
     hipError_t e;
     // split-K only when the caller brought the workspace for it; without one the shape runs unsplit
     if (workspace) {
-        const int parts = plan_splitk(M, N, K);
+        const int parts = plan_splitk(M, N, K, f8);
         const size_t need = splitk_bytes(M, N, parts);
         if (!aligned16(workspace)) return CODA_ERR_ALIGN;
         if (workspace_bytes < need) return CODA_ERR_WORKSPACE;
@@ -312,7 +318,16 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
             if ((e = hipGetLastError()) != hipSuccess) return launch_status(e);
         }
     }
-    if (ak && !bkc)
+    if (f8) {
+        using namespace coda;
+        switch (ps.mode) {
+        case EPI_LINEAR: e = launch_gemm_f8<EPI_LINEAR>(p, s); break;
+        case EPI_SWIGLU_FWD: e = launch_gemm_f8<EPI_SWIGLU_FWD>(p, s); break;
+        case EPI_SWIGLU_BWD: e = launch_gemm_f8<EPI_SWIGLU_BWD>(p, s); break;
+        case EPI_RMSNORM_BWD: e = launch_gemm_f8<EPI_RMSNORM_BWD>(p, s); break;
+        default: e = launch_gemm_f8<EPI_ACCUM>(p, s); break;
+        }
+    } else if (ak && !bkc)
         e = dispatch_mode<true, false>(ps.mode, edge, p, s);
     else if (ak && bkc)
         e = dispatch_mode<true, true>(ps.mode, edge, p, s);

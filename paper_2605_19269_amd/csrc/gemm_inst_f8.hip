@@ -1,0 +1,10 @@
+// Instantiations of the 8-bit-operand fast kernel (A [M x K], B [N x K], OCP E4M3), one per epilogue mode.
+#include "gemm_launch.hpp"
+
+namespace coda {
+template hipError_t launch_gemm_f8<EPI_LINEAR>(const GemmParams &, hipStream_t);
+template hipError_t launch_gemm_f8<EPI_SWIGLU_FWD>(const GemmParams &, hipStream_t);
+template hipError_t launch_gemm_f8<EPI_SWIGLU_BWD>(const GemmParams &, hipStream_t);
+template hipError_t launch_gemm_f8<EPI_ACCUM>(const GemmParams &, hipStream_t);
+template hipError_t launch_gemm_f8<EPI_RMSNORM_BWD>(const GemmParams &, hipStream_t);
+}  // namespace coda

@@ -1021,6 +1021,66 @@ __device__ __forceinline__ void dl_load16(uint32_t voff, const void *sbase, uint
                  : "memory");
 }
 
+// ---------------------------------------------------------------------------------
+// Split-K exchange (fast kernels).  Every workgroup of a tile leaves its fp32 partial in the workspace and takes a
+// ticket; all but the last one to arrive return false (and must exit); the last one gets the sum of all partials,
+// added in split order so that it does not depend on who arrived last, and returns true.
+// ---------------------------------------------------------------------------------
+template <class C>
+__device__ __forceinline__ bool splitk_exchange(f32x16 (&acc)[C::FM][C::FN], const GemmParams &p, int tile_id, int split,
+                                                int nsplit, float *red, int tid)
+{
+    constexpr int FM = C::FM, FN = C::FN;
+    // Partial tile -> workspace in register order: float4 q of thread t at [q][t], fully coalesced.  The layout is
+    // private to this exchange.
+    constexpr int NQ = FM * FN * 4;
+    f32x4 *part = reinterpret_cast<f32x4 *>(p.ws_part) + (size_t)tile_id * nsplit * NQ * C::NT;
+    f32x4 *mine = part + (size_t)split * NQ * C::NT + tid;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                mine[((i * FN + j) * 4 + q) * C::NT] = f32x4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+    // Completed stores sit in this XCD's L2 (the vector L1 writes through).  One thread then does the device-scope
+    // release (L2 write-back) for the whole workgroup, takes the ticket, and -- if it is the last -- the acquire
+    // (L2 / L1 invalidate) on behalf of all waves of this compute unit.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    int *last = reinterpret_cast<int *>(red);
+    if (tid == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        const unsigned ticket = __hip_atomic_fetch_add(p.ws_cnt + tile_id, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int is_last = ticket == (unsigned)(nsplit - 1);
+        if (is_last) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        *last = is_last;
+    }
+    __syncthreads();
+    if (!*last) return false;        // uniform: the whole workgroup leaves; nobody waits for anybody
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    for (int sp = 0; sp < nsplit; ++sp) {          // fixed order
+        const f32x4 *src = part + (size_t)sp * NQ * C::NT + tid;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x4 v = src[((i * FN + j) * 4 + q) * C::NT];
+                    acc[i][j][4 * q] += v[0]; acc[i][j][4 * q + 1] += v[1];
+                    acc[i][j][4 * q + 2] += v[2]; acc[i][j][4 * q + 3] += v[3];
+                }
+    }
+    __syncthreads();                 // `red` (the flag) is reused by the epilogue
+    return true;
+}
+
 template <class C, bool AK, bool BKC, int EPI>
 __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE))) void gemm_kernel_dl(const GemmParams p)
 {
@@ -1127,55 +1187,152 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     }
     __syncthreads();  // every wave is done with the operand ring before the epilogue reuses it
 
-    if (nsplit > 1) {
-        // Partial tile -> workspace in register order: float4 q of thread t at [q][t], fully coalesced.  The layout is
-        // private to this exchange.
-        constexpr int NQ = FM * FN * 4;
-        f32x4 *part = reinterpret_cast<f32x4 *>(p.ws_part) + (size_t)tile_id * nsplit * NQ * C::NT;
-        f32x4 *mine = part + (size_t)split * NQ * C::NT + tid;
+    if (nsplit > 1 && !splitk_exchange<C>(acc, p, tile_id, split, nsplit, red, tid)) return;
+
+    run_epilogue<C, EPI, false, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
+}
+
+// ---------------------------------------------------------------------------------
+// 8-bit operands (OCP E4M3), both stored with the contraction index contiguous: A [M x K], B [N x K] bytes.
+// One K-step is 64 elements = 64 bytes per row, so operand tiles, ring stages, the direct-to-LDS fill and the XOR
+// swizzle have the byte geometry of the bf16 kernel's 32-element step.  v_mfma_f32_32x32x64_f8f6f4 takes 32 bytes
+// per lane and operand: lane (row = lane % 32, half = lane / 32) holds bytes 32*half .. 32*half+31 of its row's 64;
+// both operands are loaded with the same rule, so every product pairs bytes of equal k.  The accumulator layout is
+// that of the bf16 instruction, and the epilogues are shared.
+// Per K-step (one MFMA per 32x32 block) the work is split in two halves of the wave's rows, so that the
+// fragment reads of one half run under the MFMAs of the other, with the workgroup barrier between them:
+//   A  issue loads of tile kt+S-1
+//   B  read the row fragments of the upper half of tile kt; MFMAs of the lower half
+//   C  wait for this wave's loads of tile kt+1; barrier
+//   D  read the lower-half row fragments and the column fragments of tile kt+1; MFMAs of the upper half
+// ---------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+
+template <class C>
+__device__ __forceinline__ uint32_t dl_goffset_f8(int j, int lane, int64_t ld)
+{
+    const int r = j * 16 + (lane >> 2);
+    const int c = (lane & 3) ^ ((r >> 2) & 3);
+    return (uint32_t)((int64_t)r * ld + c * 16);
+}
+
+__device__ __forceinline__ i32x8 dl_frag_f8(const unsigned char *tile, int row_base, int lane)
+{
+    const int r = row_base + (lane & 31), h = lane >> 5, sw = (r >> 2) & 3;
+    const u32x4 lo = *reinterpret_cast<const u32x4 *>(tile + r * 64 + (((2 * h) ^ sw) << 4));
+    const u32x4 hi = *reinterpret_cast<const u32x4 *>(tile + r * 64 + (((2 * h + 1) ^ sw) << 4));
+    return i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+}
+
+template <class C, int EPI>
+__global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE))) void gemm_kernel_dl_f8(const GemmParams p)
+{
+    constexpr int BM = C::BM, BN = C::BN, BKB = 64, FM = C::FM, FN = C::FN, S = C::STAGES, HM = FM / 2;
+    constexpr int LA = C::LA, LB = C::LB;
+    static_assert(FM % 2 == 0, "two row halves");
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[S * C::STAGE_BYTES];
+    __shared__ float red[2 * C::WGN * C::BM];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % C::WGM, wn = wave / C::WGM;
+    const int nsplit = p.splitk > 1 ? p.splitk : 1;
+    const int tile_id = (int)blockIdx.x / nsplit, split = (int)blockIdx.x % nsplit;
+    int tm, tn;
+    tile_coords(tile_id, (int)gridDim.x / nsplit, p.tiles_m, p.tiles_n, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    f32x16 acc[FM][FN];
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // this workgroup's K-steps [kbeg, kbeg + KT); the host guarantees an even, positive count
+    const int KT_all = p.K / BKB;
+    const int kbeg = (int)((int64_t)KT_all * split / nsplit);
+    const int KT = (int)((int64_t)KT_all * (split + 1) / nsplit) - kbeg;
+
+    uint32_t offa[LA], offb[LB];
+#pragma unroll
+    for (int i = 0; i < LA; ++i) offa[i] = dl_goffset_f8<C>(wave * LA + i, lane, p.lda);
+#pragma unroll
+    for (int i = 0; i < LB; ++i) offb[i] = dl_goffset_f8<C>(wave * LB + i, lane, p.ldb);
+    const unsigned char *ga = reinterpret_cast<const unsigned char *>(p.A) + (int64_t)m0 * p.lda + (int64_t)kbeg * BKB;
+    const unsigned char *gb = reinterpret_cast<const unsigned char *>(p.B) + (int64_t)n0 * p.ldb + (int64_t)kbeg * BKB;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+
+    auto issue = [&](int t) {
+        const uint32_t slot = lds0 + (uint32_t)(t % S) * C::STAGE_BYTES;
+        const unsigned char *sa = ga + (int64_t)t * BKB;
+        const unsigned char *sb = gb + (int64_t)t * BKB;
+#pragma unroll
+        for (int i = 0; i < LA; ++i) dl_load16(offa[i], sa, slot + (uint32_t)(wave * LA + i) * 1024u);
+#pragma unroll
+        for (int i = 0; i < LB; ++i) dl_load16(offb[i], sb, slot + C::A_BYTES + (uint32_t)(wave * LB + i) * 1024u);
+    };
+    i32x8 fal[HM], fah[HM], fb0[FN], fb1[FN];
+    auto read_a = [&](i32x8(&fa)[HM], int t, int half) {
+        const unsigned char *sa = smem + (t % S) * C::STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < HM; ++i) fa[i] = dl_frag_f8(sa, wm * C::WTM + (half * HM + i) * 32, lane);
+    };
+    auto read_b = [&](i32x8(&fb)[FN], int t) {
+        const unsigned char *sb = smem + (t % S) * C::STAGE_BYTES + C::A_BYTES;
+#pragma unroll
+        for (int j = 0; j < FN; ++j) fb[j] = dl_frag_f8(sb, wn * C::WTN + j * 32, lane);
+    };
+    auto mma = [&](const i32x8(&fa)[HM], const i32x8(&fb)[FN], int half) {
+#pragma unroll
+        for (int i = 0; i < HM; ++i)
 #pragma unroll
             for (int j = 0; j < FN; ++j)
+                acc[half * HM + i][j] =
+                    __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j], fa[i], acc[half * HM + i][j], 0, 0, 0, 0, 0, 0);
+    };
+    auto step = [&](int kt, const i32x8(&fbc)[FN], i32x8(&fbn)[FN], bool last) {
+        const bool refill = kt + S - 1 < KT;
+        if (refill) issue(kt + S - 1);                                   // A
+        read_a(fah, kt, 1);                                              // B
+        mma(fal, fbc, 0);
+        if (!last) {
+            if (refill) {                                                // C
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
+            } else {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+            __syncthreads();
+            read_a(fal, kt + 1, 0);                                      // D
+            read_b(fbn, kt + 1);
+        }
+        mma(fah, fbc, 1);
+    };
+
+    if (KT > 0) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    mine[((i * FN + j) * 4 + q) * C::NT] = f32x4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-        // Completed stores sit in this XCD's L2 (the vector L1 writes through).  One thread then does the device-scope
-        // release (L2 write-back) for the whole workgroup, takes the ticket, and -- if it is the last -- the acquire
-        // (L2 / L1 invalidate) on behalf of all waves of this compute unit.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        int *last = reinterpret_cast<int *>(red);
-        if (tid == 0) {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-            const unsigned ticket = __hip_atomic_fetch_add(p.ws_cnt + tile_id, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const int is_last = ticket == (unsigned)(nsplit - 1);
-            if (is_last) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            *last = is_last;
+        for (int t = 0; t < S - 1; ++t)
+            if (t < KT) issue(t);
+        if (KT >= S - 1) {
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
         __syncthreads();
-        if (!*last) return;          // uniform: the whole workgroup leaves; nobody waits for anybody
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-        for (int sp = 0; sp < nsplit; ++sp) {      // fixed order: the sum does not depend on who arrived last
-            const f32x4 *src = part + (size_t)sp * NQ * C::NT + tid;
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const f32x4 v = src[((i * FN + j) * 4 + q) * C::NT];
-                        acc[i][j][4 * q] += v[0]; acc[i][j][4 * q + 1] += v[1];
-                        acc[i][j][4 * q + 2] += v[2]; acc[i][j][4 * q + 3] += v[3];
-                    }
+        read_a(fal, 0, 0);
+        read_b(fb0, 0);
+        // two K-steps per trip, so that the two column-fragment buffers swap roles without copies
+        for (int kt = 0; kt < KT - 2; kt += 2) {
+            step(kt, fb0, fb1, false);
+            step(kt + 1, fb1, fb0, false);
         }
-        __syncthreads();             // `red` (the flag) is reused by the epilogue
+        step(KT - 2, fb0, fb1, false);
+        step(KT - 1, fb1, fb0, true);
     }
+    __syncthreads();  // every wave is done with the operand ring before the epilogue reuses it
+
+    if (nsplit > 1 && !splitk_exchange<C>(acc, p, tile_id, split, nsplit, red, tid)) return;
 
     run_epilogue<C, EPI, false, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
 }

@@ -31,6 +31,19 @@ hipError_t launch_gemm(const GemmParams &p_in, hipStream_t stream)
     return hipGetLastError();
 }
 
+// 8-bit operands: whole tiles only (M, N multiples of 256, K a multiple of 128), both operands K-contiguous.
+template <int EPI>
+hipError_t launch_gemm_f8(const GemmParams &p_in, hipStream_t stream)
+{
+    using C = FastCfg;
+    GemmParams p = p_in;
+    p.tiles_m = p.M / C::BM;
+    p.tiles_n = p.N / C::BN;
+    const unsigned nsplit = p.splitk > 1 ? (unsigned)p.splitk : 1u;
+    hipLaunchKernelGGL((gemm_kernel_dl_f8<C, EPI>), dim3((unsigned)(p.tiles_m * p.tiles_n) * nsplit), dim3(C::NT), 0, stream, p);
+    return hipGetLastError();
+}
+
 #define CODA_INSTANTIATE_ONE(AK, BKC, EPI)                                                   \
     template hipError_t launch_gemm<AK, BKC, EPI, false>(const GemmParams &, hipStream_t);   \
     template hipError_t launch_gemm<AK, BKC, EPI, true>(const GemmParams &, hipStream_t);

@@ -1,0 +1,196 @@
+"""GPU parity of the 8-bit-operand variant (OCP E4M3 A [M x K] and B [N x K], fp32 accumulation, the same epilogue
+programs) against the CPU oracle, which decodes the very same bytes by the format's definition and then applies its
+ordinary GEMM definitions.  Covers the decoding of every finite code, every epilogue mode, and split-K."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_19269_amd import synth
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+coda = None
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    global coda
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2605_19269_amd import coda as _c
+    coda = _c
+    yield
+    torch.cuda.synchronize()
+
+
+def dev_u8(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits)).cuda()
+
+
+def operands(oracle, g, M, N, K, a_std=1.0, b_std=1.0):
+    """E4M3 bytes for the GPU and the bf16 bit patterns of the same values for the oracle."""
+    A8, B8 = synth.normal_f8e4m3(g, (M, K), a_std), synth.normal_f8e4m3(g, (N, K), b_std)
+    return A8, B8, oracle.f8e4m3_to_bf16_bits(A8), oracle.f8e4m3_to_bf16_bits(B8)
+
+
+SHAPES = [(256, 256, 128), (512, 768, 384), (256, 512, 2048)]
+
+
+def test_every_finite_code_is_decoded_as_e4m3(oracle):
+    """B selects single elements of A (one 1.0 per row), so D holds A's decoded values themselves: exact in fp32."""
+    M, N, K = 256, 256, 128
+    codes = (np.arange(M * K, dtype=np.int64) % 256).astype(np.uint8).reshape(M, K)
+    codes[(codes & 0x7F) == 0x7F] = 0                        # the two NaN codes are outside the contract
+    B8 = np.zeros((N, K), np.uint8)
+    B8[np.arange(N), np.arange(N) % K] = 0x38                # 1.0
+    out = G.Guarded(M, N, torch.float32, pad_cols=4)
+    coda.coda_gemm(dev_u8(codes), dev_u8(B8), [coda.store(out.t, f32=True)], transB=True)
+    torch.cuda.synchronize()
+    out.check_guards(); out.written()
+    ref = oracle.gemm_rowscale(oracle.f8e4m3_to_bf16_bits(codes), oracle.f8e4m3_to_bf16_bits(B8), transB=True)
+    got = G.host_f64(out.t)
+    assert np.array_equal(got, ref), "max |delta| %.3g" % np.abs(got - ref).max()
+    assert set(np.unique(codes)) >= set(c for c in range(256) if (c & 0x7F) != 0x7F)
+
+
+# without a workspace | with one, on shapes the 8-bit plan splits 4-way and 2-way
+@pytest.mark.parametrize("M,N,K,split", [(m, n, k, False) for m, n, k in SHAPES] + [(256, 256, 8192, True), (512, 512, 4096, True)])
+def test_f8_linear_program(oracle, M, N, K, split):
+    g = np.random.Generator(np.random.PCG64(1100 + M + K))
+    A8, B8, A16, B16 = operands(oracle, g, M, N, K)
+    C = synth.normal_bf16(g, (M, N), 1.0)
+    r = synth.uniform_f32(g, (M,), 0.02, 0.06)               # carries the operands' dequantisation scales
+    ws = None
+    if split:
+        need = coda.coda_gemm_workspace_bytes(M, N, K, [])
+        assert need > 0
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda").fill_(0x5A)
+    Y = G.Guarded(M, N, torch.bfloat16)
+    nblk = coda.coda_row_partial_blocks(N)
+    part = torch.full((nblk, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    dr, dC = G.dev_f32(r), G.dev_bf16(C)
+    coda.coda_gemm(dev_u8(A8), dev_u8(B8), [coda.row_scale(dr), coda.add_tile(dC), coda.row_sumsq(part), coda.store(Y.t)],
+                   transB=True, workspace=ws)
+    ss = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_row_finalize(part, M, nblk, sum_out=ss, d=N, eps=0.0)
+    torch.cuda.synchronize()
+    refD, refss = oracle.gemm_residual_sumsq(A16, B16, r=r.astype(np.float64), C=C, transB=True)[:2]
+    Y.check_guards(); Y.written()
+    G.assert_bf16_close(G.host_f64(Y.t), refD, "f8 row scale + residual")
+    G.assert_sumsq_close(G.host_f64(ss), refss, "f8 row sum of squares")
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_f8_swiglu_forward_and_backward(oracle, M, N, K):
+    g = np.random.Generator(np.random.PCG64(1200 + M + K))
+    A8, B8, A16, B16 = operands(oracle, g, M, N, K)
+    r = synth.uniform_f32(g, (M,), 0.02, 0.06)
+    H, Zs = G.Guarded(M, N // 2, torch.bfloat16), G.Guarded(M, N, torch.bfloat16)
+    dr = G.dev_f32(r)
+    coda.coda_gemm(dev_u8(A8), dev_u8(B8), [coda.row_scale(dr), coda.swiglu_fwd(Zs.t), coda.store(H.t)], transB=True)
+    torch.cuda.synchronize()
+    refH, refZ = oracle.gemm_rowscale_swiglu(A16, B16, r=r.astype(np.float64), transB=True, want_preact=True)
+    H.check_guards(); H.written(); Zs.check_guards(); Zs.written()
+    G.assert_bf16_close(G.host_f64(H.t), refH, "f8 swiglu forward")
+    G.assert_bf16_close(G.host_f64(Zs.t), refZ, "f8 pre-activation")
+    # backward on the same operands: D plays the incoming gradient (small values via small A)
+    A8b = synth.normal_f8e4m3(g, (M, K), 0.05)
+    A16b = oracle.f8e4m3_to_bf16_bits(A8b)
+    Z = synth.normal_bf16(g, (M, 2 * N), 1.0)
+    dZ, O = G.Guarded(M, 2 * N, torch.bfloat16), G.Guarded(M, N, torch.bfloat16)
+    nblk = coda.coda_row_partial_blocks(N)
+    part = torch.full((nblk, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    dZin = G.dev_bf16(Z)
+    coda.coda_gemm(dev_u8(A8b), dev_u8(B8), [coda.swiglu_bwd(dZin, act_out=O.t, stat_out=part), coda.store(dZ.t)], transB=True)
+    stat = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_row_finalize(part, M, nblk, sum_out=stat, d=1, eps=0.0)
+    torch.cuda.synchronize()
+    refdZ, refO, refstat = oracle.gemm_swiglu_bwd(A16b, B16, Z, transB=True)
+    dZ.check_guards(); dZ.written(); O.check_guards(); O.written()
+    G.assert_bf16_close(G.host_f64(dZ.t), refdZ, "f8 dZ")
+    G.assert_bf16_close(G.host_f64(O.t), refO, "f8 recomputed activation")
+    G.assert_f32_signed_close(G.host_f64(stat), refstat, "f8 row statistic")
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_f8_accumulate_rmsnorm_backward_rope_lse(oracle, M, N, K):
+    g = np.random.Generator(np.random.PCG64(1300 + M + K))
+    A8, B8, A16, B16 = operands(oracle, g, M, N, K, a_std=0.25, b_std=0.25)
+    dA, dB = dev_u8(A8), dev_u8(B8)
+    # fp32 accumulate
+    Gin = synth.normal_f32(g, (M, N), 1e-1)
+    buf = G.Guarded(M, N, torch.float32, pad_cols=4)
+    buf.t.copy_(torch.from_numpy(Gin))
+    buf.ref = buf.full.clone()
+    coda.coda_gemm(dA, dB, [coda.accum_f32(buf.t)], transB=True)
+    torch.cuda.synchronize()
+    buf.check_guards()
+    G.assert_f32_signed_close(G.host_f64(buf.t), oracle.gemm_accumulate(A16, B16, Gin, transB=True), "f8 fp32 accumulate")
+    # RMSNorm backward
+    Cb, Oin = synth.normal_bf16(g, (M, N), 1.0), synth.normal_bf16(g, (M, N), 1.0)
+    r, z = synth.uniform_f32(g, (M,), 0.5, 1.5), synth.normal_f32(g, (M,), 0.3)
+    gamma = synth.uniform_f32(g, (N,), 0.5, 1.5)
+    Oout, Cout = G.Guarded(M, N, torch.bfloat16), G.Guarded(M, N, torch.bfloat16)
+    nblk = coda.coda_col_partial_blocks(M)
+    dgp = torch.full((nblk, N), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    dC, dr, dz, dgm, dO = G.dev_bf16(Cb), G.dev_f32(r), G.dev_f32(z), G.dev_f32(gamma), G.dev_bf16(Oin)
+    coda.coda_gemm(dA, dB, [coda.rmsnorm_bwd(dC, dr, dz, dgm, c_out=Cout.t, dgamma_out=dgp), coda.add_tile(dO), coda.store(Oout.t)],
+                   transB=True)
+    dg = torch.empty(N, dtype=torch.float32, device="cuda")
+    coda.coda_col_finalize(dgp, N, nblk, dg)
+    torch.cuda.synchronize()
+    refO, refC, refdg = oracle.gemm_rmsnorm_bwd(A16, B16, Cb, r.astype(np.float64), z.astype(np.float64), gamma.astype(np.float64),
+                                                Oin=Oin, transB=True)
+    Oout.check_guards(); Oout.written(); Cout.check_guards(); Cout.written()
+    G.assert_bf16_close(G.host_f64(Oout.t), refO, "f8 O_out")
+    G.assert_bf16_close(G.host_f64(Cout.t), refC, "f8 C_out")
+    G.assert_f32_signed_close(G.host_f64(dg), refdg, "f8 dgamma")
+    # RoPE
+    hd, rc, T = 64, 256, 80
+    cos, sin = synth.rope_tables(T, hd)
+    pos = g.integers(0, T, size=M).astype(np.int32)
+    out = G.Guarded(M, N, torch.bfloat16)
+    dcos, dsin, dpos = G.dev_f32(cos), G.dev_f32(sin), torch.from_numpy(pos).cuda()
+    coda.coda_gemm(dA, dB, [coda.row_scale(dr), coda.rope(dcos, dsin, dpos, hd, rc), coda.store(out.t)], transB=True)
+    torch.cuda.synchronize()
+    out.check_guards(); out.written()
+    G.assert_bf16_close(G.host_f64(out.t), oracle.gemm_rowscale_rope(A16, B16, cos, sin, pos, hd, rc, r=r.astype(np.float64), transB=True),
+                        "f8 rope")
+    # log-sum-exp partials
+    y = g.integers(0, N, size=M).astype(np.int32)
+    Zl = G.Guarded(M, N, torch.bfloat16)
+    nb = coda.coda_row_partial_blocks(N)
+    pmax = torch.full((nb, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    psum = torch.full((nb, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    zt = torch.full((M,), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    dy = torch.from_numpy(y).cuda()
+    rl = synth.uniform_f32(g, (M,), 0.05, 0.15)
+    drl = G.dev_f32(rl)
+    coda.coda_gemm(dA, dB, [coda.row_scale(drl), coda.lse_partial(dy, pmax, psum, zt), coda.store(Zl.t)], transB=True)
+    lse = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_lse_finalize(pmax, psum, M, nb, ztgt=zt, lse_out=lse)
+    torch.cuda.synchronize()
+    refZ, refzt, reflse = oracle.gemm_rowscale_lse(A16, B16, y, r=rl.astype(np.float64), transB=True)
+    Zl.check_guards(); Zl.written()
+    G.assert_bf16_close(G.host_f64(Zl.t), refZ, "f8 logits")
+    G.assert_f32_signed_close(G.host_f64(zt), refzt, "f8 target logit")
+    d = np.abs(G.host_f64(lse) - reflse)
+    assert (d <= 1e-3 * np.maximum(np.abs(reflse), 1.0)).all(), "lse max delta %.3g" % d.max()
+
+
+def test_f8_argument_errors(oracle):
+    M, N, K = 256, 256, 128
+    A8 = torch.zeros((M, K), dtype=torch.uint8, device="cuda")
+    B8 = torch.zeros((N, K), dtype=torch.uint8, device="cuda")
+    Bb = torch.zeros((N, K), dtype=torch.bfloat16, device="cuda")
+    Bn = torch.zeros((K, N), dtype=torch.uint8, device="cuda")
+    out = G.Guarded(M, N, torch.bfloat16)
+    for a, b, kw, status in [(A8, Bb, dict(transB=True), "CODA_ERR_DTYPE"),            # mixed operand types
+                             (A8, Bn, dict(), "CODA_ERR_DTYPE"),                        # B not K-contiguous
+                             (A8[:128], B8, dict(transB=True), "CODA_ERR_SHAPE"),       # M not a whole tile
+                             (A8[:, :64], B8[:, :64], dict(transB=True), "CODA_ERR_SHAPE")]:   # K not a multiple of 128
+        with pytest.raises(coda.CodaError) as ei:
+            coda.coda_gemm(a, b, [coda.store(out.t)], **kw)
+        assert ei.value.status == getattr(coda, status)
+    torch.cuda.synchronize()
+    out.check_guards()
