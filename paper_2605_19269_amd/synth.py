@@ -26,16 +26,17 @@ def normal_bf16(rng, shape, std):
 def f32_to_f8e4m3_bits(x):
     """Round-to-nearest-even fp32 -> OCP E4M3 bytes (uint8), saturating at +-448 (finite inputs).  Storage rounding of
     synthetic inputs only: 8-bit operands are an input format of the GEMM, not part of its arithmetic."""
-    codes = np.arange(127)                                         # 0x00 .. 0x7E: the non-negative finite codes, ascending
-    e, m = codes >> 3, codes & 7
-    vals = np.where(e == 0, m / 8.0 * 2.0 ** -6, (1.0 + m / 8.0) * 2.0 ** (e - 7.0))
-    mids = (vals[:-1] + vals[1:]) / 2.0
-    a = np.abs(np.asarray(x, dtype=np.float64))
-    idx = np.searchsorted(mids, a, side="left")                    # mids[idx-1] < a <= mids[idx]
-    tie = (idx < 126) & (a == mids[np.minimum(idx, 125)])
-    idx = np.where(tie & (idx % 2 == 1), idx + 1, idx)             # a tie goes to the code with an even mantissa
-    out = idx.astype(np.uint8)
-    return np.where(np.signbit(np.asarray(x, dtype=np.float64)), out | np.uint8(0x80), out).astype(np.uint8)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    a = np.abs(x)
+    # normal range (|x| >= 2^-6): round the 23-bit mantissa to 3 bits on the raw bits, then re-bias the exponent (127 -> 7)
+    u = a.view(np.uint32)
+    r = u + np.uint32(0x7FFFF) + ((u >> np.uint32(20)) & np.uint32(1))
+    code = (r >> np.uint32(20)).astype(np.int32) - np.int32((127 - 7) << 3)
+    # subnormal range: multiples of 2^-9; a value that rounds up to 8 * 2^-9 is the smallest normal, code 0x08
+    sub = np.rint(a * np.float32(512.0)).astype(np.int32)
+    code = np.where(a < np.float32(2.0 ** -6), sub, code)
+    code = np.minimum(code, 0x7E).astype(np.uint8)
+    return code | (np.signbit(x).astype(np.uint8) << np.uint8(7))
 
 
 def normal_f8e4m3(rng, shape, std):

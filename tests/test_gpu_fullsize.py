@@ -188,3 +188,39 @@ def test_lm_head_logits_lse(oracle):
     d = np.abs(lse.cpu().numpy()[rows].astype(np.float64) - reflse)
     assert (d <= 1e-3 * np.maximum(np.abs(reflse), 1.0)).all(), "lse max delta %.3g" % d.max()
     G.assert_f32_signed_close(loss.cpu().numpy()[rows].astype(np.float64), reflse - refzt, "LM-head loss")
+
+
+def test_llama1b_forward_gemms_on_f8e4m3_operands(oracle):
+    """The 8-bit-operand variant at the step's forward shapes, launched as bench.py launches it, on sampled rows:
+    up-projection (row scale carrying rstd times a quantisation scale, SwiGLU) and down-projection (row scale,
+    residual, sum of squares).  Operands ~ N(0,1) rounded to E4M3; the weights are stored [out x in]."""
+    M, d, F = 8192, 2048, 8192
+    g = np.random.Generator(np.random.PCG64(31))
+    rows = synth.sample_rows(M, NSAMPLE, seed=5)
+    X8, W8 = synth.normal_f8e4m3(g, (M, d), 1.0), synth.normal_f8e4m3(g, (2 * F, d), 1.0)
+    r = synth.uniform_f32(g, (M,), 0.01, 0.03)
+    dr = G.dev_f32(r)
+    H = torch.empty((M, F), dtype=torch.bfloat16, device="cuda")
+    coda.coda_gemm(torch.from_numpy(X8).cuda(), torch.from_numpy(W8).cuda(), [coda.row_scale(dr), coda.swiglu_fwd(), coda.store(H)],
+                   transB=True)
+    torch.cuda.synchronize()
+    ref = oracle.gemm_rowscale_swiglu(oracle.f8e4m3_to_bf16_bits(X8), oracle.f8e4m3_to_bf16_bits(W8), r=r.astype(np.float64),
+                                      transB=True, rows=rows)
+    G.assert_bf16_close(rows_of(H, rows), ref, "1B up, E4M3 operands")
+    del X8, W8, H
+    H8, Wd8 = synth.normal_f8e4m3(g, (M, F), 1.0), synth.normal_f8e4m3(g, (d, F), 1.0)
+    Rb = synth.normal_bf16(g, (M, d), 1.0)
+    r2 = synth.uniform_f32(g, (M,), 0.005, 0.015)
+    dr2, dR = G.dev_f32(r2), G.dev_bf16(Rb)
+    Y = torch.empty((M, d), dtype=torch.bfloat16, device="cuda")
+    nblk = coda.coda_row_partial_blocks(d)
+    part = torch.empty((nblk, M), dtype=torch.float32, device="cuda")
+    ss = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_gemm(torch.from_numpy(H8).cuda(), torch.from_numpy(Wd8).cuda(),
+                   [coda.row_scale(dr2), coda.add_tile(dR), coda.row_sumsq(part), coda.store(Y)], transB=True)
+    coda.coda_row_finalize(part, M, nblk, sum_out=ss, d=d, eps=0.0)
+    torch.cuda.synchronize()
+    refY, refss = oracle.gemm_residual_sumsq(oracle.f8e4m3_to_bf16_bits(H8), oracle.f8e4m3_to_bf16_bits(Wd8), r=r2.astype(np.float64),
+                                             C=Rb, transB=True, rows=rows)[:2]
+    G.assert_bf16_close(rows_of(Y, rows), refY, "1B down, E4M3 operands")
+    G.assert_sumsq_close(ss.cpu().numpy()[rows], refss, "1B down sumsq, E4M3 operands")
