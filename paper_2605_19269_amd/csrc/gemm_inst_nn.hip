@@ -1,5 +1,6 @@
 // GEMM+epilogue kernel instantiations for one operand-layout pair:
 // A stored [M x K] (K-contiguous), B stored [K x N] (N-contiguous).
+#define CODA_GEMM_INSTANTIATION_UNIT
 #include "gemm_launch.hpp"
 namespace coda {
 CODA_INSTANTIATE_LAYOUT(true, false)

@@ -55,4 +55,27 @@ hipError_t launch_gemm_f8(const GemmParams &p_in, hipStream_t stream)
     CODA_INSTANTIATE_ONE(AK, BKC, EPI_ACCUM)        \
     CODA_INSTANTIATE_ONE(AK, BKC, EPI_RMSNORM_BWD)
 
+// Translation units that only call the launchers (the C ABI) must not instantiate the kernels a second time:
+// unless CODA_GEMM_INSTANTIATION_UNIT is defined, every launcher is declared as instantiated elsewhere.
+#ifndef CODA_GEMM_INSTANTIATION_UNIT
+#define CODA_EXTERN_ONE(AK, BKC, EPI)                                                               \
+    extern template hipError_t launch_gemm<AK, BKC, EPI, false>(const GemmParams &, hipStream_t);  \
+    extern template hipError_t launch_gemm<AK, BKC, EPI, true>(const GemmParams &, hipStream_t);
+#define CODA_EXTERN_LAYOUT(AK, BKC)            \
+    CODA_EXTERN_ONE(AK, BKC, EPI_LINEAR)       \
+    CODA_EXTERN_ONE(AK, BKC, EPI_SWIGLU_FWD)   \
+    CODA_EXTERN_ONE(AK, BKC, EPI_SWIGLU_BWD)   \
+    CODA_EXTERN_ONE(AK, BKC, EPI_ACCUM)        \
+    CODA_EXTERN_ONE(AK, BKC, EPI_RMSNORM_BWD)
+CODA_EXTERN_LAYOUT(true, false)
+CODA_EXTERN_LAYOUT(true, true)
+CODA_EXTERN_LAYOUT(false, false)
+CODA_EXTERN_LAYOUT(false, true)
+extern template hipError_t launch_gemm_f8<EPI_LINEAR>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_gemm_f8<EPI_SWIGLU_FWD>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_gemm_f8<EPI_SWIGLU_BWD>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_gemm_f8<EPI_ACCUM>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_gemm_f8<EPI_RMSNORM_BWD>(const GemmParams &, hipStream_t);
+#endif
+
 }  // namespace coda
