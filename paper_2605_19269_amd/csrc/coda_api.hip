@@ -232,8 +232,8 @@ int plan_splitk(int64_t M, int64_t N, int64_t K, bool f8 = false)
     int64_t s = SPLITK_CUS / tiles;
     if (s > K / min_k) s = K / min_k;
     if (s > SPLITK_MAX) s = SPLITK_MAX;
-    // the 8-bit kernel walks its K-steps in pairs: every part must get an even number of them
-    while (f8 && s >= 2 && (K / 64) % (2 * s)) --s;
+    // the fast kernels walk their K-steps (32 bf16 or 64 fp8 elements) in pairs: every part must get an even number
+    while (s >= 2 && (K / (f8 ? 64 : 32)) % (2 * s)) --s;
     return s >= 2 ? (int)s : 1;
 }
 constexpr size_t SPLITK_CNT_BYTES = 1024;   // ticket counters (at most 64 tiles x 4 bytes), kept apart from the partials

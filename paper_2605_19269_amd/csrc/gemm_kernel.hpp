@@ -1,19 +1,20 @@
 // gemm_kernel.hpp -- bf16 MFMA GEMM mainloop + epilogue program for gfx950 (MI355X).
 //
-// D = op(A) op(B) with fp32 accumulation in v_mfma_f32_32x32x16_bf16, followed by
+// D = op(A) op(B) with fp32 accumulation on the matrix cores (v_mfma_f32_16x16x32_bf16 in the fast kernel,
+// v_mfma_f32_32x32x16_bf16 in the edge kernel, v_mfma_f32_32x32x64_f8f6f4 for 8-bit operands), followed by
 // the epilogue primitives of the paper's Section 3.1 applied to the accumulators
 // while they are still in registers (kernel forms: Appendix "List of Kernels",
-// Kernels 2, 4, 5, 6, 10, plus the accumulating weight gradient of Theorem 1).
+// Kernels 1 - 10, plus the accumulating weight gradient of Theorem 1).
 //
 // Orientation.  The MFMA's first source takes the B-matrix fragment (indexed by
 // output column n) and the second the A-matrix fragment (indexed by token row m),
-// i.e. each 32x32 block is computed transposed.  The accumulator layout of the
-// instruction then gives every lane ONE token row (m = lane % 32) and, in each
+// i.e. each block is computed transposed.  The accumulator layout of the
+// instruction then gives every lane ONE token row per block and, in each
 // group of four consecutive registers, FOUR CONSECUTIVE output columns
-// (n = 8*(reg/4) + 4*(lane/32) + reg%4).  Adjacent (gate, up) column pairs
+// (see Acc32 / Acc16 below).  Adjacent (gate, up) column pairs
 // therefore sit in adjacent registers of one lane, so the pairwise maps are pure
-// register arithmetic, and a row's 32 columns of a block live in just two lanes
-// (lane, lane^32), so a row reduction is in-lane adds plus one cross-half exchange.
+// register arithmetic, and a row's columns of a block live in just two (four) lanes,
+// so a row reduction is in-lane adds plus one (two) cross-lane exchanges.
 //
 // Operand staging.  Tiles are copied global -> registers -> LDS in 16-byte chunks
 // exactly as they lie in memory.  An operand whose contraction index is
@@ -257,18 +258,20 @@ struct Stage {
     {
         return (uint32_t)(it * 1024) + (lane_part ^ (uint32_t)((((it * RPI) >> SH) & (NCH - 1)) << 4));
     }
-    // ---- unit phase: lane -> row (lane & 31) of 32-row block fi, a unit of U bytes at byte column cb + (lane >> 5) * U
-    template <int U>
+    // ---- unit phase (accumulator layout with LR rows per block, 64 / LR lanes per row): lane -> row (lane % LR) of
+    // LR-row block fi, a unit of U bytes at byte column cb + (lane / LR) * U
+    template <int U, int LR>
     __device__ static __forceinline__ uint32_t unit_lane(int lane)
     {
-        const int lrow = lane & 31, h = lane >> 5;
+        const int lrow = lane % LR, hb = (lane / LR) * U;
         const int f = (lrow >> SH) & (NCH - 1);
-        return U == 16 ? (uint32_t)(lrow * RB + ((f ^ h) << 4)) : (uint32_t)(lrow * RB + (f << 4) + h * U);
+        return (uint32_t)(lrow * RB + ((f ^ (hb >> 4)) << 4) + (hb & 15));
     }
-    // cb: compile-time byte column of the h = 0 unit (a multiple of 2U)
+    // cb: compile-time byte column of the first lane's unit (a multiple of U * 64 / LR)
+    template <int LR>
     __device__ static __forceinline__ uint32_t unit_addr(uint32_t lane_part, int fi, int cb)
     {
-        return (uint32_t)(fi * 32 * RB + (cb & 15)) + (lane_part ^ (uint32_t)((cb >> 4) << 4));
+        return (uint32_t)(fi * LR * RB + (cb & 15)) + (lane_part ^ (uint32_t)((cb >> 4) << 4));
     }
 };
 
@@ -379,72 +382,125 @@ constexpr int pass_rows(int reg_bytes, int row_bytes, int max_rows)
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
 // ---------------------------------------------------------------------------------
-// Epilogue program on the accumulators of one workgroup tile.
-//   lane -> (row, column group):  m = mb + (lane & 31);  n = nb + 8*g + 4*(lane >> 5) + e
-// `ring` (RING bytes, 1 KiB aligned) must no longer be read by any wave as an operand
-// tile (callers synchronise); `red` is a separate [WGN][BM] float exchange buffer.
+// Accumulators of one wave's WTM x WTN tile, in the layout of the MFMA that produced them.
+// Both instructions are issued with the B fragment as first source, so a lane owns ONE token row per block and
+// groups of four consecutive output columns ("units").  With LR rows per block and LQ = 64 / LR lanes per row:
+//   row of block i:   i * LR + lane % LR
+//   unit u of a row:  columns u * 4 * LQ + 4 * (lane / LR) .. + 3
+// Acc32: v_mfma_f32_32x32x16_bf16 (LR 32, 2 lanes per row, 8 units per 32x32 block pair);
+// Acc16: v_mfma_f32_16x16x32_bf16 (LR 16, 4 lanes per row, one unit per 16x16 block).
 // ---------------------------------------------------------------------------------
-template <class C, int EPI, bool EDGE, int RING>
-__device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const GemmParams &p, int m0, int n0, int tn,
+template <class C>
+struct Acc32 {
+    static constexpr int LR = 32, LQ = 2, NB = C::WTM / 32, NU = C::WTN / 8;
+    f32x16 a[C::WTM / 32][C::WTN / 32];
+    __device__ __forceinline__ f32x4 get(int i, int u) const
+    {
+        const f32x16 &b = a[i][u >> 2];
+        const int g = (u & 3) * 4;
+        return f32x4{b[g], b[g + 1], b[g + 2], b[g + 3]};
+    }
+    __device__ __forceinline__ void set(int i, int u, f32x4 v)
+    {
+        f32x16 &b = a[i][u >> 2];
+        const int g = (u & 3) * 4;
+        b[g] = v[0]; b[g + 1] = v[1]; b[g + 2] = v[2]; b[g + 3] = v[3];
+    }
+};
+template <class C>
+struct Acc16 {
+    static constexpr int LR = 16, LQ = 4, NB = C::WTM / 16, NU = C::WTN / 16;
+    f32x4 a[C::WTM / 16][C::WTN / 16];
+    __device__ __forceinline__ f32x4 get(int i, int u) const { return a[i][u]; }
+    __device__ __forceinline__ void set(int i, int u, f32x4 v) { a[i][u] = v; }
+};
+template <class ACC>
+__device__ __forceinline__ void acc_zero(ACC &acc)
+{
+#pragma unroll
+    for (int i = 0; i < ACC::NB; ++i)
+#pragma unroll
+        for (int u = 0; u < ACC::NU; ++u) acc.set(i, u, f32x4{0.f, 0.f, 0.f, 0.f});
+}
+
+// Sum over the LQ lanes that share a row (lanes lane % LR + k * LR).
+template <int LR>
+__device__ __forceinline__ float row_lanes_sum(float v)
+{
+#pragma unroll
+    for (int off = LR; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// ---------------------------------------------------------------------------------
+// Epilogue program on the accumulators of one workgroup tile (layout: see Acc32 / Acc16).
+// `ring` (RING bytes, 1 KiB aligned) must no longer be read by any wave as an operand
+// tile (callers synchronise); `red` is a separate [2][WGN][BM] float exchange buffer.
+// ---------------------------------------------------------------------------------
+template <class C, class ACC, int EPI, bool EDGE, int RING>
+__device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int m0, int n0, int tn,
                                              unsigned char *ring, float *red, int tid)
 {
-    constexpr int BM = C::BM, FM = C::FM, FN = C::FN, WTM = C::WTM, WTN = C::WTN;
+    constexpr int BM = C::BM, WTM = C::WTM, WTN = C::WTN;
+    constexpr int LR = ACC::LR, LQ = ACC::LQ, NB = ACC::NB, NU = ACC::NU, UC = 4 * LQ;   // UC: column step between units
     constexpr int REG = RING / (C::WGM * C::WGN);   // private staging bytes per wave
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave % C::WGM, wn = wave / C::WGM;
-    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int lrow = lane % LR, lcol = (lane / LR) * 4;           // the lane's row in a block, first column in a unit step
     const int mw = m0 + wm * WTM, nw = n0 + wn * WTN;
     unsigned char *reg = ring + wave * REG;
     const int rows_ok = EDGE ? clampi(p.M - mw, 0, WTM) : WTM;   // valid rows / columns of this wave's tile
     const int cols_ok = EDGE ? clampi(p.N - nw, 0, WTN) : WTN;
     const bool want_red = (EPI == EPI_LINEAR || EPI == EPI_SWIGLU_BWD) && p.rowred_mode != ROWRED_NONE;
-    float rsum[FM];
+    float rsum[NB];
 #pragma unroll
-    for (int i = 0; i < FM; ++i) rsum[i] = 0.0f;
+    for (int i = 0; i < NB; ++i) rsum[i] = 0.0f;
 
     if (EPI == EPI_LINEAR && p.lse_max) {
         // ---- log-sum-exp partials of this 256-column tile (Kernels 3 / 8) on the fp32 values v = acc * r, before rounding:
-        // per lane and row the maximum and the sum of exp(v - max) over its 32 values, merged with the partner lane
-        // (other 4-column groups of the same row) and then over the four column waves with the usual rescaling rule.
+        // per lane and row the maximum and the sum of exp(v - max) over its values, merged over the lanes that share the
+        // row and then over the four column waves with the usual rescaling rule.
         constexpr float NEG_INF = -__builtin_inff();
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            const int m = mw + i * 32 + lrow;
+        for (int i = 0; i < NB; ++i) {
+            const int m = mw + i * LR + lrow;
             const bool mok = !EDGE || m < p.M;
             const float rs = p.row_scale ? (mok ? p.row_scale[m] : 0.0f) : 1.0f;
             const int yy = mok ? p.lse_y[m] : -1;
             float mx = NEG_INF;
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
+            for (int u = 0; u < NU; ++u) {
+                const int n = nw + u * UC + lcol;
+                if (mok && (!EDGE || n < p.N)) {
+                    const f32x4 a = acc.get(i, u);
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = nw + j * 32 + g * 8 + lhalf * 4;
-                    if (mok && (!EDGE || n < p.N)) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float v = acc[i][j][4 * g + e] * rs;
-                            mx = fmaxf(mx, v);
-                            if (n + e == yy) p.lse_tgt[m] = v;
-                        }
+                    for (int e = 0; e < 4; ++e) {
+                        const float v = a[e] * rs;
+                        mx = fmaxf(mx, v);
+                        if (n + e == yy) p.lse_tgt[m] = v;
                     }
                 }
+            }
             float sm = 0.0f;
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
+            for (int u = 0; u < NU; ++u) {
+                const int n = nw + u * UC + lcol;
+                if (mok && (!EDGE || n < p.N)) {
+                    const f32x4 a = acc.get(i, u);
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = nw + j * 32 + g * 8 + lhalf * 4;
-                    if (mok && (!EDGE || n < p.N)) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) sm += __expf(acc[i][j][4 * g + e] * rs - mx);
-                    }
+                    for (int e = 0; e < 4; ++e) sm += __expf(a[e] * rs - mx);
                 }
-            const float mo = __shfl_xor(mx, 32, 64), so = __shfl_xor(sm, 32, 64);
-            const float mm = fmaxf(mx, mo);
-            const float ss = (mx == NEG_INF ? 0.0f : sm * __expf(mx - mm)) + (mo == NEG_INF ? 0.0f : so * __expf(mo - mm));
-            if (lane < 32) {
-                red[wn * BM + wm * WTM + i * 32 + lane] = mm;
-                red[C::WGN * BM + wn * BM + wm * WTM + i * 32 + lane] = ss;
+            }
+#pragma unroll
+            for (int off = LR; off < 64; off <<= 1) {
+                const float mo = __shfl_xor(mx, off, 64), so = __shfl_xor(sm, off, 64);
+                const float mm = fmaxf(mx, mo);
+                sm = (mx == NEG_INF ? 0.0f : sm * __expf(mx - mm)) + (mo == NEG_INF ? 0.0f : so * __expf(mo - mm));
+                mx = mm;
+            }
+            if (lane < LR) {
+                red[wn * BM + wm * WTM + i * LR + lane] = mx;
+                red[C::WGN * BM + wn * BM + wm * WTM + i * LR + lane] = sm;
             }
         }
         __syncthreads();
@@ -470,17 +526,15 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
         // ---- local part of RMSNorm backward: with d the accumulator, cn = C*r:
         //   O_out = O_in + (d*gamma - cn*z)*r,   C_out = cn*gamma,   dgamma partial = column sums of d*cn over this tile.
         // Per 64-row pass the region holds the C rows and the O_in rows side by side; results overwrite them in place.
-        constexpr int RB = WTN * 2, P = 64, FPP = 2;
+        constexpr int RB = WTN * 2, P = 64, FPP = P / LR;
         static_assert(WTN == 64 && WTM % P == 0 && 2 * P * RB <= REG, "staging pass");
         using St = Stage<RB>;
-        const uint32_t ulane = St::template unit_lane<8>(lane);
+        const uint32_t ulane = St::template unit_lane<8, LR>(lane);
         unsigned char *rego = reg + P * RB;
         uint16_t *outp = reinterpret_cast<uint16_t *>(p.out);
-        f32x4 dg[FN][4];
+        f32x4 dg[NU];
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) dg[j][g] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int u = 0; u < NU; ++u) dg[u] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ps = 0; ps < WTM / P; ++ps) {
             const int r0 = ps * P;
@@ -492,32 +546,30 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
             stage_fence();
 #pragma unroll
             for (int fi = 0; fi < FPP; ++fi) {
-                const int i = ps * FPP + fi, m = mw + i * 32 + lrow;
+                const int i = ps * FPP + fi, m = mw + i * LR + lrow;
                 const bool mok = !EDGE || m < p.M;
                 const float rr = mok ? p.rn_r[m] : 0.0f, zz = mok ? p.rn_z[m] : 0.0f;
 #pragma unroll
-                for (int j = 0; j < FN; ++j)
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int nl = j * 32 + g * 8 + lhalf * 4;
-                        const bool ok = mok && (!EDGE || nw + nl < p.N);
-                        const uint32_t ua = St::unit_addr(ulane, fi, (j * 32 + g * 8) * 2);
-                        f32x4 gm = {0.f, 0.f, 0.f, 0.f};
-                        if (ok) gm = *reinterpret_cast<const f32x4 *>(p.rn_gamma + nw + nl);
-                        const u32x2 cw = *reinterpret_cast<const u32x2 *>(reg + ua);
-                        const f32x4 d = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                        const f32x4 cn = f32x4{bf16_lo(cw[0]), bf16_hi(cw[0]), bf16_lo(cw[1]), bf16_hi(cw[1])} * rr;
-                        f32x4 o = (d * gm - cn * zz) * rr;
-                        if (p.add) {
-                            const u32x2 ow = *reinterpret_cast<const u32x2 *>(rego + ua);
-                            o += f32x4{bf16_lo(ow[0]), bf16_hi(ow[0]), bf16_lo(ow[1]), bf16_hi(ow[1])};
-                        }
-                        if (ok) dg[j][g] += d * cn;
-                        const f32x4 co = cn * gm;
-                        *reinterpret_cast<u32x2 *>(rego + ua) = u32x2{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
-                        *reinterpret_cast<u32x2 *>(reg + ua) = u32x2{pack_bf16x2(co[0], co[1]), pack_bf16x2(co[2], co[3])};
-                        if (g == 3) __builtin_amdgcn_sched_barrier(0);
+                for (int u = 0; u < NU; ++u) {
+                    const int nl = u * UC + lcol;
+                    const bool ok = mok && (!EDGE || nw + nl < p.N);
+                    const uint32_t ua = St::template unit_addr<LR>(ulane, fi, u * UC * 2);
+                    f32x4 gm = {0.f, 0.f, 0.f, 0.f};
+                    if (ok) gm = *reinterpret_cast<const f32x4 *>(p.rn_gamma + nw + nl);
+                    const u32x2 cw = *reinterpret_cast<const u32x2 *>(reg + ua);
+                    const f32x4 d = acc.get(i, u);
+                    const f32x4 cn = f32x4{bf16_lo(cw[0]), bf16_hi(cw[0]), bf16_lo(cw[1]), bf16_hi(cw[1])} * rr;
+                    f32x4 o = (d * gm - cn * zz) * rr;
+                    if (p.add) {
+                        const u32x2 ow = *reinterpret_cast<const u32x2 *>(rego + ua);
+                        o += f32x4{bf16_lo(ow[0]), bf16_hi(ow[0]), bf16_lo(ow[1]), bf16_hi(ow[1])};
                     }
+                    if (ok) dg[u] += d * cn;
+                    const f32x4 co = cn * gm;
+                    *reinterpret_cast<u32x2 *>(rego + ua) = u32x2{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+                    *reinterpret_cast<u32x2 *>(reg + ua) = u32x2{pack_bf16x2(co[0], co[1]), pack_bf16x2(co[2], co[3])};
+                    if ((u & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+                }
             }
             stage_fence();
             stage_store<RB, P, EDGE>(rego, reinterpret_cast<unsigned char *>(outp + (int64_t)(mw + r0) * p.ld_out + nw), p.ld_out * 2,
@@ -528,18 +580,16 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
             stage_fence();
         }
         if (p.colred_mode != ROWRED_NONE) {
-            // column reduction: the lane's 32 partial sums go to the region as a [32 rows][64 columns] f32 tile, lane l
-            // then adds up column l over the 32 rows; the two row-waves of the workgroup meet in `red`
+            // column reduction: the lane's partial sums go to the region as an [LR rows][64 columns] f32 tile, lane l
+            // then adds up column l over the LR rows; the two row-waves of the workgroup meet in `red`
             using Sf = Stage<256>;
-            const uint32_t fl = Sf::template unit_lane<16>(lane);
+            const uint32_t fl = Sf::template unit_lane<16, LR>(lane);
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) *reinterpret_cast<f32x4 *>(reg + Sf::unit_addr(fl, 0, (j * 32 + g * 8) * 4)) = dg[j][g];
+            for (int u = 0; u < NU; ++u) *reinterpret_cast<f32x4 *>(reg + Sf::template unit_addr<LR>(fl, 0, u * UC * 4)) = dg[u];
             stage_fence();
             float cs = 0.0f;
 #pragma unroll
-            for (int rr = 0; rr < 32; ++rr)
+            for (int rr = 0; rr < LR; ++rr)
                 cs += *reinterpret_cast<const float *>(reg + rr * 256 + ((((lane >> 2) ^ rr) & 15) << 4) + (lane & 3) * 4);
             red[wm * C::BN + wn * WTN + lane] = cs;
             __syncthreads();
@@ -559,27 +609,24 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
     } else if constexpr (EPI == EPI_SWIGLU_FWD) {
         // ---- row scale, pairwise SwiGLU (width halves), optional pre-activation side output
         constexpr int RBH = WTN, RBZ = WTN * 2;
-        constexpr int P = pass_rows(REG, RBZ, WTM), FPP = P / 32;
-        static_assert(P % 32 == 0 && WTM % P == 0, "staging pass");
+        constexpr int P = pass_rows(REG, RBZ, WTM), FPP = P / LR;
+        static_assert(P % LR == 0 && WTM % P == 0, "staging pass");
         uint16_t *outp = reinterpret_cast<uint16_t *>(p.out);
-        const uint32_t ulane_h = Stage<RBH>::template unit_lane<4>(lane), ulane_z = Stage<RBZ>::template unit_lane<8>(lane);
+        const uint32_t ulane_h = Stage<RBH>::template unit_lane<4, LR>(lane), ulane_z = Stage<RBZ>::template unit_lane<8, LR>(lane);
 #pragma unroll
         for (int ps = 0; ps < WTM / P; ++ps) {
             const int r0 = ps * P;
 #pragma unroll
             for (int fi = 0; fi < FPP; ++fi) {
-                const int i = ps * FPP + fi, m = mw + i * 32 + lrow;
+                const int i = ps * FPP + fi, m = mw + i * LR + lrow;
                 const float rs = p.row_scale ? ((!EDGE || m < p.M) ? p.row_scale[m] : 0.0f) : 1.0f;
 #pragma unroll
-                for (int j = 0; j < FN; ++j)
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const float v0 = acc[i][j][4 * g] * rs, v1 = acc[i][j][4 * g + 1] * rs;
-                        const float v2 = acc[i][j][4 * g + 2] * rs, v3 = acc[i][j][4 * g + 3] * rs;
-                        const float h0 = v0 * fast_sigmoid(v0) * v1, h1 = v2 * fast_sigmoid(v2) * v3;
-                        *reinterpret_cast<uint32_t *>(reg + Stage<RBH>::unit_addr(ulane_h, fi, j * 32 + g * 8)) = pack_bf16x2(h0, h1);
-                        if (g == 3) __builtin_amdgcn_sched_barrier(0);
-                    }
+                for (int u = 0; u < NU; ++u) {
+                    const f32x4 v = acc.get(i, u) * rs;
+                    const float h0 = v[0] * fast_sigmoid(v[0]) * v[1], h1 = v[2] * fast_sigmoid(v[2]) * v[3];
+                    *reinterpret_cast<uint32_t *>(reg + Stage<RBH>::template unit_addr<LR>(ulane_h, fi, u * UC)) = pack_bf16x2(h0, h1);
+                    if ((u & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+                }
             }
             stage_fence();
             stage_store<RBH, P, EDGE>(reg, reinterpret_cast<unsigned char *>(outp + (int64_t)(mw + r0) * p.ld_out + (nw >> 1)),
@@ -588,16 +635,14 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
                 stage_fence();
 #pragma unroll
                 for (int fi = 0; fi < FPP; ++fi) {
-                    const int i = ps * FPP + fi, m = mw + i * 32 + lrow;
+                    const int i = ps * FPP + fi, m = mw + i * LR + lrow;
                     const float rs = p.row_scale ? ((!EDGE || m < p.M) ? p.row_scale[m] : 0.0f) : 1.0f;
 #pragma unroll
-                    for (int j = 0; j < FN; ++j)
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            *reinterpret_cast<u32x2 *>(reg + Stage<RBZ>::unit_addr(ulane_z, fi, (j * 32 + g * 8) * 2)) =
-                                u32x2{pack_bf16x2(acc[i][j][4 * g] * rs, acc[i][j][4 * g + 1] * rs),
-                                      pack_bf16x2(acc[i][j][4 * g + 2] * rs, acc[i][j][4 * g + 3] * rs)};
-                        }
+                    for (int u = 0; u < NU; ++u) {
+                        const f32x4 v = acc.get(i, u) * rs;
+                        *reinterpret_cast<u32x2 *>(reg + Stage<RBZ>::template unit_addr<LR>(ulane_z, fi, u * UC * 2)) =
+                            u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+                    }
                 }
                 stage_fence();
                 stage_store<RBZ, P, EDGE>(reg, reinterpret_cast<unsigned char *>(p.out2 + (int64_t)(mw + r0) * p.ld_out2 + nw),
@@ -607,35 +652,35 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
         }
     } else if constexpr (EPI == EPI_SWIGLU_BWD) {
         // ---- pairwise SwiGLU backward (width doubles): Z in and dZ out staged; row statistic; the optional
-        // recomputed activation silu(g)*u is a second sweep over 32-row blocks that re-reads Z.
-        constexpr int RB = WTN * 4, RBO = WTN * 2;
-        static_assert(32 * (RB + RBO) <= REG, "staging pass");
+        // recomputed activation silu(g)*u is a second sweep over 32-row passes that re-reads Z.
+        constexpr int RB = WTN * 4, RBO = WTN * 2, P = 32, FPP = P / LR, NP = WTM / P;
+        static_assert(P * (RB + RBO) <= REG && WTM % P == 0, "staging pass");
         uint16_t *outp = reinterpret_cast<uint16_t *>(p.out);
-        const uint32_t ulane = Stage<RB>::template unit_lane<16>(lane), ulane_o = Stage<RBO>::template unit_lane<8>(lane);
+        const uint32_t ulane = Stage<RB>::template unit_lane<16, LR>(lane), ulane_o = Stage<RBO>::template unit_lane<8, LR>(lane);
         // 32-row passes; the Z rows of the next pass are fetched into registers while this pass is computed and stored
-        u32x4 zt[32 / Stage<RB>::RPI];
-        auto zrows = [&](int i) { return reinterpret_cast<const unsigned char *>(p.Z + (int64_t)(mw + i * 32) * p.ldz + 2 * nw); };
-        stage_fetch<RB, 32, EDGE>(zt, zrows(0), p.ldz * 2, rows_ok, cols_ok * 4, lane);
+        u32x4 zt[P / Stage<RB>::RPI];
+        auto zrows = [&](int ps) { return reinterpret_cast<const unsigned char *>(p.Z + (int64_t)(mw + ps * P) * p.ldz + 2 * nw); };
+        stage_fetch<RB, P, EDGE>(zt, zrows(0), p.ldz * 2, rows_ok, cols_ok * 4, lane);
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            const int m = mw + i * 32 + lrow;
-            const bool mok = !EDGE || m < p.M;
-            stage_put<RB, 32>(reg, zt, lane);
+        for (int ps = 0; ps < NP; ++ps) {
+            stage_put<RB, P>(reg, zt, lane);
             stage_fence();
-            if (i + 1 < FM) stage_fetch<RB, 32, EDGE>(zt, zrows(i + 1), p.ldz * 2, rows_ok - (i + 1) * 32, cols_ok * 4, lane);
+            if (ps + 1 < NP) stage_fetch<RB, P, EDGE>(zt, zrows(ps + 1), p.ldz * 2, rows_ok - (ps + 1) * P, cols_ok * 4, lane);
             stage_fence();
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
+            for (int fi = 0; fi < FPP; ++fi) {
+                const int i = ps * FPP + fi, m = mw + i * LR + lrow;
+                const bool mok = !EDGE || m < p.M;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int nl = j * 32 + g * 8 + lhalf * 4;
-                    const bool ok = mok && (!EDGE || nw + nl < p.N);
-                    u32x4 *slot = reinterpret_cast<u32x4 *>(reg + Stage<RB>::unit_addr(ulane, 0, (j * 32 + g * 8) * 4));
+                for (int u = 0; u < NU; ++u) {
+                    const bool ok = mok && (!EDGE || nw + u * UC + lcol < p.N);
+                    u32x4 *slot = reinterpret_cast<u32x4 *>(reg + Stage<RB>::template unit_addr<LR>(ulane, fi, u * UC * 4));
                     const u32x4 z = *slot;
+                    const f32x4 a = acc.get(i, u);
                     u32x4 dz;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float d = acc[i][j][4 * g + e];
+                        const float d = a[e];
                         const float gg = bf16_lo(z[e]), uu = bf16_hi(z[e]);
                         const float sg = fast_sigmoid(gg), sl = gg * sg;
                         const float dU = d * sl, dG = d * uu * (sg + sl * (1.0f - sg));
@@ -643,56 +688,58 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
                         if (want_red && ok) rsum[i] += gg * dG + uu * dU;
                     }
                     *slot = dz;
-                    asm volatile("" : "+v"(rsum[i]));   // keep the row statistic's add chain in place (see above)
-                    if (g & 1) __builtin_amdgcn_sched_barrier(0);
+                    asm volatile("" : "+v"(rsum[i]));   // keep the row statistic's add chain in place
+                    if (u & 1) __builtin_amdgcn_sched_barrier(0);
                 }
+            }
             stage_fence();
-            stage_store<RB, 32, EDGE>(reg, reinterpret_cast<unsigned char *>(outp + (int64_t)(mw + i * 32) * p.ld_out + 2 * nw), p.ld_out * 2,
-                                      rows_ok - i * 32, cols_ok * 4, lane);
+            stage_store<RB, P, EDGE>(reg, reinterpret_cast<unsigned char *>(outp + (int64_t)(mw + ps * P) * p.ld_out + 2 * nw), p.ld_out * 2,
+                                     rows_ok - ps * P, cols_ok * 4, lane);
             stage_fence();
         }
         if (p.out2) {
-            unsigned char *rego = reg + 32 * RB;   // activation rows live behind the 32 staged Z rows
+            unsigned char *rego = reg + P * RB;   // activation rows live behind the staged Z rows
 #pragma unroll
-            for (int i = 0; i < FM; ++i) {
-                const int r0 = i * 32;
-                stage_load<RB, 32, EDGE>(reg, reinterpret_cast<const unsigned char *>(p.Z + (int64_t)(mw + r0) * p.ldz + 2 * nw),
-                                         p.ldz * 2, rows_ok - r0, cols_ok * 4, lane);
+            for (int ps = 0; ps < NP; ++ps) {
+                const int r0 = ps * P;
+                stage_load<RB, P, EDGE>(reg, reinterpret_cast<const unsigned char *>(p.Z + (int64_t)(mw + r0) * p.ldz + 2 * nw),
+                                        p.ldz * 2, rows_ok - r0, cols_ok * 4, lane);
                 stage_fence();
 #pragma unroll
-                for (int j = 0; j < FN; ++j)
+                for (int fi = 0; fi < FPP; ++fi)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const u32x4 z = *reinterpret_cast<const u32x4 *>(reg + Stage<RB>::unit_addr(ulane, 0, (j * 32 + g * 8) * 4));
+                    for (int u = 0; u < NU; ++u) {
+                        const u32x4 z = *reinterpret_cast<const u32x4 *>(reg + Stage<RB>::template unit_addr<LR>(ulane, fi, u * UC * 4));
                         float o[4];
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             const float gg = bf16_lo(z[e]);
                             o[e] = gg * fast_sigmoid(gg) * bf16_hi(z[e]);
                         }
-                        *reinterpret_cast<u32x2 *>(rego + Stage<RBO>::unit_addr(ulane_o, 0, (j * 32 + g * 8) * 2)) = u32x2{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+                        *reinterpret_cast<u32x2 *>(rego + Stage<RBO>::template unit_addr<LR>(ulane_o, fi, u * UC * 2)) =
+                            u32x2{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
                     }
                 stage_fence();
-                stage_store<RBO, 32, EDGE>(rego, reinterpret_cast<unsigned char *>(p.out2 + (int64_t)(mw + r0) * p.ld_out2 + nw),
-                                           p.ld_out2 * 2, rows_ok - r0, cols_ok * 2, lane);
+                stage_store<RBO, P, EDGE>(rego, reinterpret_cast<unsigned char *>(p.out2 + (int64_t)(mw + r0) * p.ld_out2 + nw),
+                                          p.ld_out2 * 2, rows_ok - r0, cols_ok * 2, lane);
                 stage_fence();
             }
         }
     } else if (EPI == EPI_LINEAR && !p.out_f32 && p.rope_cos && WTN == 64 && (p.rope_half & 31) == 0) {
-        // ---- row scale, RoPE, bf16 store with the cos / sin rows staged like tiles: per 32-row block the wave gathers
+        // ---- row scale, RoPE, bf16 store with the cos / sin rows staged like tiles: per 32-row pass the wave gathers
         // each token's 32 table entries (128 bytes of cos, 128 of sin; the wave's 64 columns are 32 consecutive pairs
         // inside one head because head_dim/2 is a multiple of 32) with row-contiguous 16-byte loads into its region,
         // so the per-unit table reads come from LDS instead of 8-byte gathers from 32 different rows.
-        constexpr int RB = 128;
+        constexpr int RB = 128, P = 32, FPP = P / LR, NP = WTM / P;
         using St = Stage<RB>;
-        const uint32_t ulane = St::template unit_lane<8>(lane);
+        const uint32_t ulane = St::template unit_lane<8, LR>(lane);
         const uint32_t rlane = St::row_lane(lane);
         const int f0 = (nw >> 1) % p.rope_half;                        // first frequency index of this wave's columns
-        unsigned char *rcos = reg + 32 * RB, *rsin = reg + 64 * RB;
+        unsigned char *rcos = reg + P * RB, *rsin = reg + 2 * P * RB;
         uint16_t *outp = reinterpret_cast<uint16_t *>(p.out);
         u32x4 tc[4], ts[4];
-        auto gather = [&](int i) {                                     // table slices of 32-row block i -> registers
-            const int m = mw + i * 32 + lrow;
+        auto gather = [&](int ps) {                                    // table slices of 32-row pass ps -> registers
+            const int m = mw + ps * P + (lane & 31);
             const int trow = (!EDGE || m < p.M) ? p.rope_pos[m] * p.rope_half + f0 : f0;
 #pragma unroll
             for (int it = 0; it < 4; ++it) {                           // 8 rows x 128 bytes per access
@@ -703,26 +750,25 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
         };
         gather(0);
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            const int m = mw + i * 32 + lrow;
-            const bool mok = !EDGE || m < p.M;
-            const float rs = p.row_scale ? (mok ? p.row_scale[m] : 0.0f) : 1.0f;
+        for (int ps = 0; ps < NP; ++ps) {
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
                 *reinterpret_cast<u32x4 *>(rcos + St::row_addr(rlane, it)) = tc[it];
                 *reinterpret_cast<u32x4 *>(rsin + St::row_addr(rlane, it)) = ts[it];
             }
             stage_fence();
-            if (i + 1 < FM) gather(i + 1);                             // in flight under this block's math and stores
+            if (ps + 1 < NP) gather(ps + 1);                           // in flight under this pass's math and stores
             stage_fence();
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
+            for (int fi = 0; fi < FPP; ++fi) {
+                const int i = ps * FPP + fi, m = mw + i * LR + lrow;
+                const bool mok = !EDGE || m < p.M;
+                const float rs = p.row_scale ? (mok ? p.row_scale[m] : 0.0f) : 1.0f;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int nl = j * 32 + g * 8 + lhalf * 4;
-                    const uint32_t ua = St::unit_addr(ulane, 0, (j * 32 + g * 8) * 2);
-                    f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                    v *= rs;
+                for (int u = 0; u < NU; ++u) {
+                    const int nl = u * UC + lcol;
+                    const uint32_t ua = St::template unit_addr<LR>(ulane, fi, u * UC * 2);
+                    f32x4 v = acc.get(i, u) * rs;
                     if (nw + nl < p.rope_cols) {
                         const f32x2 c = *reinterpret_cast<const f32x2 *>(rcos + ua);
                         const f32x2 sn = *reinterpret_cast<const f32x2 *>(rsin + ua);
@@ -731,18 +777,19 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
                     }
                     *reinterpret_cast<u32x2 *>(reg + ua) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
                 }
+            }
             stage_fence();
-            stage_store<RB, 32, EDGE>(reg, reinterpret_cast<unsigned char *>(outp + (int64_t)(mw + i * 32) * p.ld_out + nw), p.ld_out * 2,
-                                      rows_ok - i * 32, cols_ok * 2, lane);
+            stage_store<RB, P, EDGE>(reg, reinterpret_cast<unsigned char *>(outp + (int64_t)(mw + ps * P) * p.ld_out + nw), p.ld_out * 2,
+                                     rows_ok - ps * P, cols_ok * 2, lane);
             stage_fence();
         }
     } else if (EPI == EPI_LINEAR && !p.out_f32) {
         // ---- row scale, residual add, row sum of squares, bf16 store: all tile I/O staged.  The gamma-scaled side
         // output (when requested) is a second sweep that re-reads the residual and recomputes the value, so that
         // nothing has to stay in registers between the two stores.
-        constexpr int RB = WTN * 2, P = pass_rows(REG, RB, WTM), FPP = P / 32;
-        static_assert(P % 32 == 0 && WTM % P == 0, "staging pass");
-        const uint32_t ulane = Stage<RB>::template unit_lane<8>(lane);
+        constexpr int RB = WTN * 2, P = pass_rows(REG, RB, WTM), FPP = P / LR;
+        static_assert(P % LR == 0 && WTM % P == 0, "staging pass");
+        const uint32_t ulane = Stage<RB>::template unit_lane<8, LR>(lane);
         const int sweeps = p.side ? 2 : 1;
         for (int sw = 0; sw < sweeps; ++sw) {
             uint16_t *dst = sw == 0 ? reinterpret_cast<uint16_t *>(p.out) : p.side;
@@ -757,47 +804,45 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
                 }
 #pragma unroll
                 for (int fi = 0; fi < FPP; ++fi) {
-                    const int i = ps * FPP + fi, m = mw + i * 32 + lrow;
+                    const int i = ps * FPP + fi, m = mw + i * LR + lrow;
                     const bool mok = !EDGE || m < p.M;
                     const float rs = p.row_scale ? (mok ? p.row_scale[m] : 0.0f) : 1.0f;
                     // RoPE: table row of this token and the frequency index of the lane's first pair; units follow each
-                    // other 4 pairs apart and rope_half is a multiple of 4, so the index wraps at most once per step
+                    // other UC / 2 <= 8 pairs apart and rope_half is a multiple of 4, so the index wraps at most twice per step
                     const int64_t trow = (p.rope_cos && mok) ? (int64_t)p.rope_pos[m] * p.rope_half : 0;
-                    int rf = p.rope_cos ? ((nw + lhalf * 4) >> 1) % p.rope_half : 0;
+                    int rf = p.rope_cos ? ((nw + lcol) >> 1) % p.rope_half : 0;
 #pragma unroll
-                    for (int j = 0; j < FN; ++j)
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            const int nl = j * 32 + g * 8 + lhalf * 4;
-                            const bool ok = mok && (!EDGE || nw + nl < p.N);
-                            f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                            v *= rs;
-                            if (p.rope_cos) {
-                                if (ok && nw + nl < p.rope_cols) rope_unit(v, p, trow, rf);
-                                rf += 4;
-                                if (rf >= p.rope_half) rf -= p.rope_half;
-                            }
-                            u32x2 *slot = reinterpret_cast<u32x2 *>(reg + Stage<RB>::unit_addr(ulane, fi, (j * 32 + g * 8) * 2));
-                            if (p.add) {
-                                const u32x2 c = *slot;
-                                v[0] += bf16_lo(c[0]); v[1] += bf16_hi(c[0]);
-                                v[2] += bf16_lo(c[1]); v[3] += bf16_hi(c[1]);
-                            }
-                            if (sw == 0) {
-                                if (ok) rsum[i] += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-                            } else {
-                                f32x4 gm = {0.f, 0.f, 0.f, 0.f};
-                                if (ok) gm = *reinterpret_cast<const f32x4 *>(p.col_scale + nw + nl);
-                                v *= gm;
-                            }
-                            *slot = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-                            if (g == 3) {
-                                // pin the running row sum here: otherwise its whole add chain is sunk to the point of
-                                // use after the stores and every addend has to stay live (spilled) until then
-                                asm volatile("" : "+v"(rsum[i]));
-                                __builtin_amdgcn_sched_barrier(0);
-                            }
+                    for (int u = 0; u < NU; ++u) {
+                        const int nl = u * UC + lcol;
+                        const bool ok = mok && (!EDGE || nw + nl < p.N);
+                        f32x4 v = acc.get(i, u) * rs;
+                        if (p.rope_cos) {
+                            if (ok && nw + nl < p.rope_cols) rope_unit(v, p, trow, rf);
+                            rf += UC / 2;
+                            if (rf >= p.rope_half) rf -= p.rope_half;
+                            if (rf >= p.rope_half) rf -= p.rope_half;
                         }
+                        u32x2 *slot = reinterpret_cast<u32x2 *>(reg + Stage<RB>::template unit_addr<LR>(ulane, fi, u * UC * 2));
+                        if (p.add) {
+                            const u32x2 c = *slot;
+                            v[0] += bf16_lo(c[0]); v[1] += bf16_hi(c[0]);
+                            v[2] += bf16_lo(c[1]); v[3] += bf16_hi(c[1]);
+                        }
+                        if (sw == 0) {
+                            if (ok) rsum[i] += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+                        } else {
+                            f32x4 gm = {0.f, 0.f, 0.f, 0.f};
+                            if (ok) gm = *reinterpret_cast<const f32x4 *>(p.col_scale + nw + nl);
+                            v *= gm;
+                        }
+                        *slot = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+                        if ((u & 3) == 3) {
+                            // pin the running row sum here: otherwise its whole add chain is sunk to the point of
+                            // use after the stores and every addend has to stay live (spilled) until then
+                            asm volatile("" : "+v"(rsum[i]));
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
                 }
                 stage_fence();
                 stage_store<RB, P, EDGE>(reg, reinterpret_cast<unsigned char *>(dst + (int64_t)(mw + r0) * ldd + nw), ldd * 2,
@@ -808,56 +853,55 @@ __device__ __forceinline__ void run_epilogue(f32x16 (&acc)[C::FM][C::FN], const 
     } else {
         // ---- fp32 outputs (f32 store of the linear program, in-place fp32 accumulate): 16 bytes per lane, direct
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            const int m = mw + i * 32 + lrow;
+        for (int i = 0; i < NB; ++i) {
+            const int m = mw + i * LR + lrow;
             const bool mok = !EDGE || m < p.M;
             float rs = 1.0f;
             if (EPI == EPI_LINEAR && p.row_scale) rs = mok ? p.row_scale[m] : 0.0f;
             const bool rope = EPI == EPI_LINEAR && p.rope_cos;
             const int64_t trow = (rope && mok) ? (int64_t)p.rope_pos[m] * p.rope_half : 0;
-            int rf = rope ? ((nw + lhalf * 4) >> 1) % p.rope_half : 0;
+            int rf = rope ? ((nw + lcol) >> 1) % p.rope_half : 0;
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = nw + j * 32 + g * 8 + lhalf * 4;
-                    const bool ok = mok && (!EDGE || n < p.N);
-                    f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                    float *gp = reinterpret_cast<float *>(p.out) + (int64_t)m * p.ld_out + n;
-                    if (EPI == EPI_LINEAR) {
-                        v *= rs;
-                        if (rope) {
-                            if (ok && n < p.rope_cols) rope_unit(v, p, trow, rf);
-                            rf += 4;
-                            if (rf >= p.rope_half) rf -= p.rope_half;
-                        }
-                        if (p.add && ok) {
-                            const u32x2 c = *reinterpret_cast<const u32x2 *>(p.add + (int64_t)m * p.ld_add + n);
-                            v[0] += bf16_lo(c[0]); v[1] += bf16_hi(c[0]);
-                            v[2] += bf16_lo(c[1]); v[3] += bf16_hi(c[1]);
-                        }
-                        if (ok) rsum[i] += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-                        if (p.side && ok) {
-                            const f32x4 gm = *reinterpret_cast<const f32x4 *>(p.col_scale + n);
-                            *reinterpret_cast<u32x2 *>(p.side + (int64_t)m * p.ld_side + n) =
-                                u32x2{pack_bf16x2(v[0] * gm[0], v[1] * gm[1]), pack_bf16x2(v[2] * gm[2], v[3] * gm[3])};
-                        }
-                        if (ok) *reinterpret_cast<f32x4 *>(gp) = v;
-                        asm volatile("" : "+v"(rsum[i]));
-                    } else if (ok) {
-                        f32x4 cur = *reinterpret_cast<const f32x4 *>(gp);
-                        cur += v;
-                        *reinterpret_cast<f32x4 *>(gp) = cur;
+            for (int u = 0; u < NU; ++u) {
+                const int n = nw + u * UC + lcol;
+                const bool ok = mok && (!EDGE || n < p.N);
+                f32x4 v = acc.get(i, u);
+                float *gp = reinterpret_cast<float *>(p.out) + (int64_t)m * p.ld_out + n;
+                if (EPI == EPI_LINEAR) {
+                    v *= rs;
+                    if (rope) {
+                        if (ok && n < p.rope_cols) rope_unit(v, p, trow, rf);
+                        rf += UC / 2;
+                        if (rf >= p.rope_half) rf -= p.rope_half;
+                        if (rf >= p.rope_half) rf -= p.rope_half;
                     }
+                    if (p.add && ok) {
+                        const u32x2 c = *reinterpret_cast<const u32x2 *>(p.add + (int64_t)m * p.ld_add + n);
+                        v[0] += bf16_lo(c[0]); v[1] += bf16_hi(c[0]);
+                        v[2] += bf16_lo(c[1]); v[3] += bf16_hi(c[1]);
+                    }
+                    if (ok) rsum[i] += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+                    if (p.side && ok) {
+                        const f32x4 gm = *reinterpret_cast<const f32x4 *>(p.col_scale + n);
+                        *reinterpret_cast<u32x2 *>(p.side + (int64_t)m * p.ld_side + n) =
+                            u32x2{pack_bf16x2(v[0] * gm[0], v[1] * gm[1]), pack_bf16x2(v[2] * gm[2], v[3] * gm[3])};
+                    }
+                    if (ok) *reinterpret_cast<f32x4 *>(gp) = v;
+                    asm volatile("" : "+v"(rsum[i]));
+                } else if (ok) {
+                    f32x4 cur = *reinterpret_cast<const f32x4 *>(gp);
+                    cur += v;
+                    *reinterpret_cast<f32x4 *>(gp) = cur;
                 }
+            }
         }
     }
 
     if (want_red) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            const float s = rsum[i] + __shfl_xor(rsum[i], 32, 64);
-            if (lane < 32) red[wn * BM + wm * WTM + i * 32 + lane] = s;
+        for (int i = 0; i < NB; ++i) {
+            const float s = row_lanes_sum<LR>(rsum[i]);
+            if (lane < LR) red[wn * BM + wm * WTM + i * LR + lane] = s;
         }
         __syncthreads();
         for (int r = tid; r < BM; r += C::NT) {
@@ -887,13 +931,9 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmParams p)
     tile_coords(blockIdx.x, gridDim.x, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
-    f32x16 acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    using ACC = Acc32<C>;
+    ACC acc;
+    acc_zero(acc);
 
     const int KT = (p.K + BK - 1) / BK;
     u32x4 ra[C::CHA], rb[C::CHB];
@@ -927,7 +967,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmParams p)
             for (int i = 0; i < FM; ++i)
 #pragma unroll
                 for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+                    acc.a[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc.a[i][j], 0, 0, 0);
         }
         if (more) {
             unsigned char *da = smem + ((kt + 1) & 1) * C::STAGE_BYTES;
@@ -937,7 +977,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmParams p)
         __syncthreads();
     }
 
-    run_epilogue<C, EPI, EDGE, 2 * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
+    run_epilogue<C, ACC, EPI, EDGE, 2 * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
 }
 
 // ---------------------------------------------------------------------------------
@@ -990,28 +1030,6 @@ __device__ __forceinline__ uint32_t dl_goffset(int j, int lane, int64_t ld)
     }
 }
 
-// K-contiguous fragment read for BK = 32 tiles (64-byte rows, 4 chunks, swizzle on row bits 2..3).
-template <int ROWS, bool KCONT>
-__device__ __forceinline__ bf16x8 dl_frag(const unsigned char *tile, int row_base, int ks, int lane)
-{
-    if (KCONT) {
-        const int r = row_base + (lane & 31);
-        const int c = (ks * 2 + (lane >> 5)) ^ ((r >> 2) & 3);
-        return *reinterpret_cast<const bf16x8 *>(tile + r * 64 + c * 16);
-    } else {
-        const int i = lane & 15, nh = (lane >> 4) & 1, h = lane >> 5;
-        const int gr = (row_base >> 4) + nh;
-        const int k_lo = ks * 16 + 8 * h + (i >> 2);
-        const uint32_t sub = (uint32_t)((i & 3) << 3);
-        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tile + lds_mn<ROWS>(k_lo, gr) + sub));
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tile + lds_mn<ROWS>(k_lo + 4, gr) + sub));
-        typedef __attribute__((ext_vector_type(8))) short s16x8;
-        s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        return __builtin_bit_cast(bf16x8, v);
-    }
-}
-
 __device__ __forceinline__ void dl_load16(uint32_t voff, const void *sbase, uint32_t lds_addr)
 {
     // M0 carries the wave-uniform LDS destination; one wait state between the M0 write and its use.
@@ -1026,23 +1044,19 @@ __device__ __forceinline__ void dl_load16(uint32_t voff, const void *sbase, uint
 // ticket; all but the last one to arrive return false (and must exit); the last one gets the sum of all partials,
 // added in split order so that it does not depend on who arrived last, and returns true.
 // ---------------------------------------------------------------------------------
-template <class C>
-__device__ __forceinline__ bool splitk_exchange(f32x16 (&acc)[C::FM][C::FN], const GemmParams &p, int tile_id, int split,
-                                                int nsplit, float *red, int tid)
+template <class C, class ACC>
+__device__ __forceinline__ bool splitk_exchange(ACC &acc, const GemmParams &p, int tile_id, int split, int nsplit, float *red, int tid)
 {
-    constexpr int FM = C::FM, FN = C::FN;
     // Partial tile -> workspace in register order: float4 q of thread t at [q][t], fully coalesced.  The layout is
     // private to this exchange.
-    constexpr int NQ = FM * FN * 4;
+    constexpr int NQ = ACC::NB * ACC::NU;
+    static_assert(NQ * 4 * C::NT == C::BM * C::BN, "one float per output element");
     f32x4 *part = reinterpret_cast<f32x4 *>(p.ws_part) + (size_t)tile_id * nsplit * NQ * C::NT;
     f32x4 *mine = part + (size_t)split * NQ * C::NT + tid;
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < ACC::NB; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                mine[((i * FN + j) * 4 + q) * C::NT] = f32x4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        for (int u = 0; u < ACC::NU; ++u) mine[(i * ACC::NU + u) * C::NT] = acc.get(i, u);
     // Completed stores sit in this XCD's L2 (the vector L1 writes through).  One thread then does the device-scope
     // release (L2 write-back) for the whole workgroup, takes the ticket, and -- if it is the last -- the acquire
     // (L2 / L1 invalidate) on behalf of all waves of this compute unit.
@@ -1058,34 +1072,63 @@ __device__ __forceinline__ bool splitk_exchange(f32x16 (&acc)[C::FM][C::FN], con
     }
     __syncthreads();
     if (!*last) return false;        // uniform: the whole workgroup leaves; nobody waits for anybody
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    acc_zero(acc);
     for (int sp = 0; sp < nsplit; ++sp) {          // fixed order
         const f32x4 *src = part + (size_t)sp * NQ * C::NT + tid;
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
+        for (int i = 0; i < ACC::NB; ++i)
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const f32x4 v = src[((i * FN + j) * 4 + q) * C::NT];
-                    acc[i][j][4 * q] += v[0]; acc[i][j][4 * q + 1] += v[1];
-                    acc[i][j][4 * q + 2] += v[2]; acc[i][j][4 * q + 3] += v[3];
-                }
+            for (int u = 0; u < ACC::NU; ++u) acc.set(i, u, acc.get(i, u) + src[(i * ACC::NU + u) * C::NT]);
     }
     __syncthreads();                 // `red` (the flag) is reused by the epilogue
     return true;
 }
 
+// One 16-row operand fragment of v_mfma_f32_16x16x32_bf16 from a BK = 32 tile of the ring:
+// lane l holds row (l % 16), k = 8*(l/16) .. 8*(l/16)+7.
+template <int ROWS, bool KCONT>
+__device__ __forceinline__ bf16x8 dl_frag16(const unsigned char *tile, int row_base, int lane)
+{
+    if (KCONT) {   // 64-byte rows, 4 chunks, swizzle on row bits 2..3
+        const int r = row_base + (lane & 15);
+        const int c = (lane >> 4) ^ ((r >> 2) & 3);
+        return *reinterpret_cast<const bf16x8 *>(tile + r * 64 + c * 16);
+    } else {
+        // transposing read: within each 16-lane group, lane i supplies the address of k-row (i/4), columns 4*(i%4)..+3
+        // of the 16-row granule and receives column i of those four k-rows
+        const int i = lane & 15, kq = lane >> 4;
+        const int gr = row_base >> 4;
+        const int k_lo = 8 * kq + (i >> 2);
+        const uint32_t sub = (uint32_t)((i & 3) << 3);
+        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tile + lds_mn<ROWS>(k_lo, gr) + sub));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tile + lds_mn<ROWS>(k_lo + 4, gr) + sub));
+        typedef __attribute__((ext_vector_type(8))) short s16x8;
+        s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, v);
+    }
+}
+
+// bf16 fast kernel.  One K-step of 32 is ONE v_mfma_f32_16x16x32_bf16 per 16x16 block (this shape draws less power per
+// FLOP than 32x32x16 and sustains a higher clock on non-trivial operands); the wave's 128 x 64 tile is 8 x 4 blocks.
+// Per K-step the work is split in two halves of the wave's rows, so that the fragment reads of one half run under the
+// MFMAs of the other, with the workgroup barrier between them:
+//   A  issue loads of tile kt+S-1 into the slot freed by tile kt-1
+//   B  read the row fragments of the upper half of tile kt; MFMAs of the lower half (fragments already in VGPRs)
+//   C  wait until this wave's loads of tile kt+1 have landed; workgroup barrier
+//   D  read the lower-half row fragments and the column fragments of tile kt+1; MFMAs of the upper half
+// The barrier orders (i) every wave's reads of tile kt before the slot is refilled in step A of kt+1 and (ii) all
+// loads of tile kt+1 before step D.  The loads are issued from inline asm, invisible to the compiler's waitcnt
+// insertion; vmcnt is waited on explicitly (loads retire in order).  K-steps are walked in pairs so that the two
+// column-fragment buffers swap roles without copies: the host guarantees an even, positive count per workgroup.
 template <class C, bool AK, bool BKC, int EPI>
 __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE))) void gemm_kernel_dl(const GemmParams p)
 {
-    constexpr int BM = C::BM, BN = C::BN, BK = 32, FM = C::FM, FN = C::FN, S = C::STAGES;
+    constexpr int BM = C::BM, BN = C::BN, BK = 32, S = C::STAGES;
+    using ACC = Acc16<C>;
+    constexpr int NI = ACC::NB, NJ = ACC::NU, HM = NI / 2;
     constexpr int LA = C::LA, LB = C::LB;
+    static_assert(NI % 2 == 0, "two row halves");
     __shared__ __attribute__((aligned(1024))) unsigned char smem[S * C::STAGE_BYTES];
     __shared__ float red[2 * C::WGN * C::BM];   // row-reduction exchange; second half: sum-exp of the log-sum-exp partials
 
@@ -1098,13 +1141,8 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     tile_coords(tile_id, (int)gridDim.x / nsplit, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
-    f32x16 acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    ACC acc;
+    acc_zero(acc);
 
     // this workgroup's part of the contraction: K-steps [kbeg, kbeg + KT)
     const int KT_all = p.K / BK;
@@ -1133,63 +1171,67 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 #pragma unroll
         for (int i = 0; i < LB; ++i) dl_load16(offb[i], sb, slot + C::A_BYTES + (uint32_t)(wave * LB + i) * 1024u);
     };
-
-    bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];
-    auto read_frags = [&](bf16x8(&fa)[FM], bf16x8(&fb)[FN], int t, int ks) {
+    bf16x8 fal[HM], fah[HM], fb0[NJ], fb1[NJ];
+    auto read_a = [&](bf16x8(&fa)[HM], int t, int half) {
         const unsigned char *sa = smem + (t % S) * C::STAGE_BYTES;
-        const unsigned char *sb = sa + C::A_BYTES;
 #pragma unroll
-        for (int i = 0; i < FM; ++i) fa[i] = dl_frag<BM, AK>(sa, wm * C::WTM + i * 32, ks, lane);
-#pragma unroll
-        for (int j = 0; j < FN; ++j) fb[j] = dl_frag<BN, BKC>(sb, wn * C::WTN + j * 32, ks, lane);
+        for (int i = 0; i < HM; ++i) fa[i] = dl_frag16<BM, AK>(sa, wm * C::WTM + (half * HM + i) * 16, lane);
     };
-    auto mma = [&](const bf16x8(&fa)[FM], const bf16x8(&fb)[FN]) {
+    auto read_b = [&](bf16x8(&fb)[NJ], int t) {
+        const unsigned char *sb = smem + (t % S) * C::STAGE_BYTES + C::A_BYTES;
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
+        for (int j = 0; j < NJ; ++j) fb[j] = dl_frag16<BN, BKC>(sb, wn * C::WTN + j * 16, lane);
+    };
+    auto mma = [&](const bf16x8(&fa)[HM], const bf16x8(&fb)[NJ], int half) {
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+        for (int i = 0; i < HM; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                acc.a[half * HM + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc.a[half * HM + i][j], 0, 0, 0);
+    };
+    auto step = [&](int kt, const bf16x8(&fbc)[NJ], bf16x8(&fbn)[NJ], bool last) {
+        const bool refill = kt + S - 1 < KT;
+        if (refill) issue(kt + S - 1);                                   // A
+        read_a(fah, kt, 1);                                              // B
+        mma(fal, fbc, 0);
+        if (!last) {
+            if (refill) {                                                // C
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
+            } else {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+            __syncthreads();
+            read_a(fal, kt + 1, 0);                                      // D
+            read_b(fbn, kt + 1);
+        }
+        mma(fah, fbc, 1);
     };
 
     if (KT > 0) {
-        // prologue: fill S-1 slots, wait for tile 0
+        // prologue: fill S-1 slots; only tile 0 has to have landed (loads retire in order)
 #pragma unroll
         for (int t = 0; t < S - 1; ++t)
             if (t < KT) issue(t);
-        // only tile 0 has to have landed; loads retire in order, so tiles 1 .. S-2 may stay in flight
         if (KT >= S - 1) {
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
         } else {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
         __syncthreads();
-        read_frags(fa0, fb0, 0, 0);
-
-        // all iterations but the last (peeled so that the loop body is branch-free around the MFMA blocks)
-        for (int kt = 0; kt < KT - 1; ++kt) {
-            const bool refill = kt + S - 1 < KT;
-            if (refill) issue(kt + S - 1);                               // A
-            read_frags(fa1, fb1, kt, 1);                                 // B
-            mma(fa0, fb0);
-            // C: this wave's loads of tile kt+1 must have landed; tiles kt+2.. may still be in flight
-            if (refill) {
-                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
-            } else {
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            }
-            __syncthreads();
-            read_frags(fa0, fb0, kt + 1, 0);                             // D
-            mma(fa1, fb1);
+        read_a(fal, 0, 0);
+        read_b(fb0, 0);
+        for (int kt = 0; kt < KT - 2; kt += 2) {
+            step(kt, fb0, fb1, false);
+            step(kt + 1, fb1, fb0, false);
         }
-        read_frags(fa1, fb1, KT - 1, 1);
-        mma(fa0, fb0);
-        mma(fa1, fb1);
+        step(KT - 2, fb0, fb1, false);
+        step(KT - 1, fb1, fb0, true);
     }
     __syncthreads();  // every wave is done with the operand ring before the epilogue reuses it
 
     if (nsplit > 1 && !splitk_exchange<C>(acc, p, tile_id, split, nsplit, red, tid)) return;
 
-    run_epilogue<C, EPI, false, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
+    run_epilogue<C, ACC, EPI, false, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
 }
 
 // ---------------------------------------------------------------------------------
@@ -1242,13 +1284,9 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     tile_coords(tile_id, (int)gridDim.x / nsplit, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
-    f32x16 acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    using ACC = Acc32<C>;
+    ACC acc;
+    acc_zero(acc);
 
     // this workgroup's K-steps [kbeg, kbeg + KT); the host guarantees an even, positive count
     const int KT_all = p.K / BKB;
@@ -1289,8 +1327,8 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
         for (int i = 0; i < HM; ++i)
 #pragma unroll
             for (int j = 0; j < FN; ++j)
-                acc[half * HM + i][j] =
-                    __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j], fa[i], acc[half * HM + i][j], 0, 0, 0, 0, 0, 0);
+                acc.a[half * HM + i][j] =
+                    __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j], fa[i], acc.a[half * HM + i][j], 0, 0, 0, 0, 0, 0);
     };
     auto step = [&](int kt, const i32x8(&fbc)[FN], i32x8(&fbn)[FN], bool last) {
         const bool refill = kt + S - 1 < KT;
@@ -1334,7 +1372,7 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 
     if (nsplit > 1 && !splitk_exchange<C>(acc, p, tile_id, split, nsplit, red, tid)) return;
 
-    run_epilogue<C, EPI, false, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
+    run_epilogue<C, ACC, EPI, false, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
 }
 
 // Host-side launcher, one per (operand layouts, epilogue mode, edge predication).
