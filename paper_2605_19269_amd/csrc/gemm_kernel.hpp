@@ -1189,8 +1189,9 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
             for (int j = 0; j < NJ; ++j)
                 acc.a[half * HM + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc.a[half * HM + i][j], 0, 0, 0);
     };
-    auto step = [&](int kt, const bf16x8(&fbc)[NJ], bf16x8(&fbn)[NJ], bool last) {
-        const bool refill = kt + S - 1 < KT;
+    // `steady`: the caller knows that tile kt+S-1 exists (no refill test in the body)
+    auto step = [&](int kt, const bf16x8(&fbc)[NJ], bf16x8(&fbn)[NJ], bool last, bool steady) {
+        const bool refill = steady || kt + S - 1 < KT;
         if (refill) issue(kt + S - 1);                                   // A
         read_a(fah, kt, 1);                                              // B
         mma(fal, fbc, 0);
@@ -1220,12 +1221,17 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
         __syncthreads();
         read_a(fal, 0, 0);
         read_b(fb0, 0);
-        for (int kt = 0; kt < KT - 2; kt += 2) {
-            step(kt, fb0, fb1, false);
-            step(kt + 1, fb1, fb0, false);
+        int kt = 0;
+        for (; kt + S < KT; kt += 2) {            // both steps refill: branch-free body
+            step(kt, fb0, fb1, false, true);
+            step(kt + 1, fb1, fb0, false, true);
         }
-        step(KT - 2, fb0, fb1, false);
-        step(KT - 1, fb1, fb0, true);
+        for (; kt < KT - 2; kt += 2) {            // ring runs dry
+            step(kt, fb0, fb1, false, false);
+            step(kt + 1, fb1, fb0, false, false);
+        }
+        step(KT - 2, fb0, fb1, false, false);
+        step(KT - 1, fb1, fb0, true, false);
     }
     __syncthreads();  // every wave is done with the operand ring before the epilogue reuses it
 
