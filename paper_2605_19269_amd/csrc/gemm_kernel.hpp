@@ -1012,6 +1012,12 @@ struct DlCfg : TileCfg<BM_, BN_, 32, WGM_, WGN_> {
     static_assert(STAGES >= 3 && STAGES * Base::STAGE_BYTES <= 160 * 1024, "LDS ring");
 };
 
+// Chunk swizzle of the K-contiguous [ROWS][32] ring tiles (64-byte rows, four 16-byte chunks): chunk c of row r sits
+// at chunk position c ^ kc16_swz(r).  The 16-row fragment read (lane -> row lane % 16, chunk lane / 16) is
+// bank-conflict-free with row bit 2 folded into chunk bit 1 (timed over all XOR maps of the row bits: folding row
+// bits 2..3 into chunk bits 0..1, which is conflict-free for 32-row fragments, takes twice as long here).
+__device__ __forceinline__ int kc16_swz(int r) { return ((r >> 2) & 1) << 1; }
+
 // Byte offset (from the tile's first element in global memory) of the chunk that lane `lane`
 // of wave-load `j` must fetch so that it lands at its swizzled LDS home.
 template <class C, int ROWS, bool KCONT>
@@ -1019,7 +1025,7 @@ __device__ __forceinline__ uint32_t dl_goffset(int j, int lane, int64_t ld)
 {
     if (KCONT) {  // [ROWS][32]: 64-byte rows, 16 rows per wave-load
         const int r = j * 16 + (lane >> 2);
-        const int c = (lane & 3) ^ ((r >> 2) & 3);
+        const int c = (lane & 3) ^ kc16_swz(r);
         return (uint32_t)(((int64_t)r * ld + c * 8) * 2);
     } else {      // [32][ROWS]: 2 k-rows per wave-load (ROWS = 256) or 4 (ROWS = 128)
         constexpr int CPR = ROWS / 8;  // chunks per k-row
@@ -1089,9 +1095,9 @@ __device__ __forceinline__ bool splitk_exchange(ACC &acc, const GemmParams &p, i
 template <int ROWS, bool KCONT>
 __device__ __forceinline__ bf16x8 dl_frag16(const unsigned char *tile, int row_base, int lane)
 {
-    if (KCONT) {   // 64-byte rows, 4 chunks, swizzle on row bits 2..3
+    if (KCONT) {   // 64-byte rows, 4 chunks
         const int r = row_base + (lane & 15);
-        const int c = (lane >> 4) ^ ((r >> 2) & 3);
+        const int c = (lane >> 4) ^ kc16_swz(r);
         return *reinterpret_cast<const bf16x8 *>(tile + r * 64 + c * 16);
     } else {
         // transposing read: within each 16-lane group, lane i supplies the address of k-row (i/4), columns 4*(i%4)..+3
