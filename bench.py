@@ -172,16 +172,20 @@ def main():
         g_c = torch.Generator(device=dev).manual_seed(5)
         fa = torch.randn(nb_c * 4 * 512 * 8, device=dev, generator=g_c).to(torch.bfloat16)          # activations ~ N(0, 1)
         fb = (torch.randn(nb_c * 2 * 512 * 8, device=dev, generator=g_c) * 0.02).to(torch.bfloat16)   # weights ~ N(0, 0.02)
-        ms_r = min(time_kernel(lambda: coda.coda_calib_mfma_loop(fa, fb, nb_c, it_c), reps=3, warm=2) for _ in range(2))
+        # the bf16 fast kernel issues v_mfma_f32_16x16x32_bf16 (loop16); the 32x32x16 loop is kept beside it
+        ms_r = min(time_kernel(lambda: coda.coda_calib_mfma_loop16(fa, fb, nb_c, it_c), reps=3, warm=2) for _ in range(2))
+        ms_r32 = min(time_kernel(lambda: coda.coda_calib_mfma_loop(fa, fb, nb_c, it_c), reps=3, warm=2) for _ in range(2))
         fa.zero_(); fb.zero_()
-        ms_z = min(time_kernel(lambda: coda.coda_calib_mfma_loop(fa, fb, nb_c, it_c), reps=3, warm=2) for _ in range(2))
+        ms_z = min(time_kernel(lambda: coda.coda_calib_mfma_loop16(fa, fb, nb_c, it_c), reps=3, warm=2) for _ in range(2))
         ceil_r, ceil_z = fl_c / ms_r * 1e-9, fl_c / ms_z * 1e-9
         out["roofline"]["mfma_only_same_data"] = round(ceil_r, 1)
+        out["roofline"]["mfma_only_same_data_32x32x16"] = round(fl_c / ms_r32 * 1e-9, 1)
         out["roofline"]["mfma_only_zero_data"] = round(ceil_z, 1)
         out["roofline"]["frac_of_mfma_only_same_data"] = round(kern_tflops["up"] / ceil_r, 4)
-        out["roofline"]["note"] = ("peak is the published figure; mfma_only_* is a register-resident MFMA loop with no memory "
-                                   "traffic, measured in this run on N(0,1) x N(0,0.02) operands and on zeros: the chip lowers "
-                                   "its clock under its power limit when operand bits toggle")
+        out["roofline"]["note"] = ("peak is the published figure; mfma_only_* is a register-resident loop of the kernel's MFMA "
+                                   "instruction (v_mfma_f32_16x16x32_bf16) with no memory traffic, measured in this run on "
+                                   "N(0,1) x N(0,0.02) operands and on zeros: the chip lowers its clock under its power limit "
+                                   "when operand bits toggle")
         del fa, fb
 
     # ---- further GEMM+epilogue kernels measured on their own (not part of `value`) -----------------------------

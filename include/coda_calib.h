@@ -34,6 +34,19 @@ extern "C" {
 coda_status coda_calib_mfma_loop(void *stream, const void *a_frags, const void *b_frags, int64_t n_blocks,
                                  int64_t iters, float *out);
 
+/*
+ * The same measurement on v_mfma_f32_16x16x32_bf16, the instruction of the bf16 fast kernel (it draws less
+ * power per FLOP than 32x32x16, so its ceiling on non-trivial operands is higher).  Same fragment inputs and
+ * launch shape; each iteration runs 32 MFMAs (each of the 4 x 2 accumulator tiles four times), the same
+ * FLOP count per iteration as coda_calib_mfma_loop: n_blocks * 8 * 16 * 32768 * iters FLOP in total.
+ * A fragment holds row (lane % 16), k = 8*(lane/16) .. +7 of a [16 x 32] operand.
+ * out (may be NULL): f32 [8][8][4][64]; block 0 writes its accumulators there as
+ * out[((wave*8 + i*2 + j)*4 + reg)*64 + lane] (lane holds row 4*(lane/16) + reg, column lane % 16 of B x A^T).
+ * Errors as above.
+ */
+coda_status coda_calib_mfma_loop16(void *stream, const void *a_frags, const void *b_frags, int64_t n_blocks,
+                                   int64_t iters, float *out);
+
 #ifdef __cplusplus
 }
 #endif

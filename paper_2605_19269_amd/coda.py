@@ -32,7 +32,7 @@ EXPORTS = ["coda_gemm", "coda_gemm_workspace_bytes", "coda_row_partial_blocks", 
            "coda_last_hip_error"]
 EXPORTS_UNFUSED = ["coda_unfused_rmsnorm_apply", "coda_unfused_swiglu_fwd", "coda_unfused_swiglu_bwd",
                    "coda_unfused_add_sumsq", "coda_unfused_accumulate"]
-EXPORTS_CALIB = ["coda_calib_mfma_loop"]
+EXPORTS_CALIB = ["coda_calib_mfma_loop", "coda_calib_mfma_loop16"]
 
 
 class coda_mat(ctypes.Structure):
@@ -85,6 +85,8 @@ _lib.coda_unfused_accumulate.restype = ctypes.c_int
 _lib.coda_unfused_accumulate.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _i64]
 _lib.coda_calib_mfma_loop.restype = ctypes.c_int
 _lib.coda_calib_mfma_loop.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp]
+_lib.coda_calib_mfma_loop16.restype = ctypes.c_int
+_lib.coda_calib_mfma_loop16.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp]
 
 
 class CodaError(RuntimeError):
@@ -283,10 +285,18 @@ def coda_unfused_accumulate(T, G, stream=None):
 
 
 # --- measurement calibration (include/coda_calib.h) ----------------------------------------------
-def coda_calib_mfma_loop(a_frags, b_frags, n_blocks, iters, out=None, stream=None):
+def _calib(fn, out_elems, a_frags, b_frags, n_blocks, iters, out, stream):
     need_a, need_b = n_blocks * 4 * 512 * 8, n_blocks * 2 * 512 * 8
     if a_frags.numel() < need_a or b_frags.numel() < need_b or a_frags.element_size() != 2 or b_frags.element_size() != 2:
         raise ValueError("fragment buffers too small: need %d and %d 16-bit elements" % (need_a, need_b))
-    if out is not None and (out.numel() < 8 * 8 * 16 * 64 or out.element_size() != 4):
-        raise ValueError("out must hold 65536 fp32 values")
-    _check(_lib.coda_calib_mfma_loop(_stream(stream), _ptr(a_frags), _ptr(b_frags), n_blocks, iters, _ptr(out)))
+    if out is not None and (out.numel() < out_elems or out.element_size() != 4):
+        raise ValueError("out must hold %d fp32 values" % out_elems)
+    _check(fn(_stream(stream), _ptr(a_frags), _ptr(b_frags), n_blocks, iters, _ptr(out)))
+
+
+def coda_calib_mfma_loop(a_frags, b_frags, n_blocks, iters, out=None, stream=None):
+    _calib(_lib.coda_calib_mfma_loop, 8 * 8 * 16 * 64, a_frags, b_frags, n_blocks, iters, out, stream)
+
+
+def coda_calib_mfma_loop16(a_frags, b_frags, n_blocks, iters, out=None, stream=None):
+    _calib(_lib.coda_calib_mfma_loop16, 8 * 8 * 4 * 64, a_frags, b_frags, n_blocks, iters, out, stream)
