@@ -153,6 +153,8 @@ def test_splitk_workspace_planning_and_errors(coda):
     assert wb(2048, 2048 + 256, 8192) == 0                  # 72 tiles: more than a quarter of the chip already busy
     assert wb(512, 512, 1024) == 0                          # contraction too short to split
     assert wb(512, 512, 4096 + 32) == 0                     # not whole tiles: edge kernel, never split
+    assert wb(256, 256, 6 * 1024 + 128) == 1024 + 1 * 2 * tile  # 196 K-steps of 32: only 2 parts get an even number each
+    assert wb(256, 256, 6 * 1024 + 64) == 0                     # 194 K-steps: no part count gives every part an even number
     assert wb(0, 512, 4096) == 0 and wb(-1, 512, 4096) == 0
     A, B = _mat(coda, P, 512, 4096), _mat(coda, P, 4096, 512)
     store = _op(coda, coda.CODA_EPI_STORE, out=P, ld_out=512)

@@ -38,8 +38,9 @@ def operands(g, M, N, K, transA, transB, a_std=1.0, b_std=0.05):
     return A, B
 
 
-# (M, N, K) -> parts: 4 tiles, K = 4096 -> 4;  1 tile, K = 8192 -> 8;  2 tiles, K = 2048 -> 2
-SHAPES = [(512, 512, 4096), (256, 256, 8192), (256, 512, 2048)]
+# (M, N, K) -> parts: 4 tiles, K = 4096 -> 4;  1 tile, K = 8192 -> 8;  2 tiles, K = 2048 -> 2;
+# 1 tile, K = 6272 (196 K-steps of 32) -> 2, the only count that gives every part an even number of steps
+SHAPES = [(512, 512, 4096), (256, 256, 8192), (256, 512, 2048), (256, 256, 6272)]
 
 
 @pytest.mark.parametrize("transA,transB", [(False, False), (False, True), (True, False)])
