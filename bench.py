@@ -312,9 +312,10 @@ def main():
         out["extra_kernels"]["f8e4m3_operands"] = f8
         del x8, w8, h8, hh8, wd8, y8, a8, b8, c8
 
-        # split-K on shapes with few output tiles: the same call with and without the workspace that enables it
+        # split-K on shapes with few output tiles, and on shapes whose last round of tiles is partly filled (320 and 384
+        # tiles: only the last 64 / 128 are shared): the same call with and without the workspace that enables it
         spk = {}
-        for (Ms, Ns, Ks) in ((512, 512, 8192), (1024, 1024, 8192), (2048, 2048, 8192)):
+        for (Ms, Ns, Ks) in ((512, 512, 8192), (1024, 1024, 8192), (2048, 2048, 8192), (5120, 4096, 8192), (6144, 4096, 8192)):
             xs, ws_, rs_ = rnd((Ms, Ks)), rnd((Ks, Ns), 0.02), rnd((Ms, Ns))
             ys = torch.empty((Ms, Ns), **b16)
             nbs = coda.coda_row_partial_blocks(Ns)

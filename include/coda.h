@@ -181,8 +181,11 @@ typedef struct coda_epi_op {
  *
  * workspace / workspace_bytes (device memory, 16-byte aligned; may be NULL): scratch for split-K.
  * Shapes made of whole 256 x 256 x 64 tiles with at most 64 output tiles and K >= 2048 leave
- * most of the chip idle; for them coda_gemm_workspace_bytes returns a non-zero size, and a call
- * that brings that much workspace lets 2 to 8 workgroups share every output tile, each
+ * most of the chip idle, and shapes with more than 256 tiles whose count modulo 256 is between 1 and
+ * 128 end with a round of tiles that fills at most half of it (long contractions only: K >= 4096).  For them
+ * coda_gemm_workspace_bytes returns a non-zero size, and a call
+ * that brings that much workspace lets 2 to 8 workgroups share every output tile (first case) or every
+ * tile of the last round (second case), each
  * contracting a contiguous part of K: partial tiles go to the workspace in fp32, the workgroup
  * that finishes last adds them up in a fixed order (the result does not depend on arrival
  * order) and runs the epilogue program on the sum.  Without a workspace (NULL) the same shape

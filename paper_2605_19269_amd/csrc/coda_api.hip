@@ -217,32 +217,51 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
     return final_seen ? CODA_OK : CODA_ERR_PROGRAM;
 }
 
-// Split-K plan: only for shapes made of whole tiles (fast kernel) that leave at least three quarters of the 256
-// compute units without a tile (measured: with 64 tiles 4 parts win 1.4x, with 128 tiles 2 parts lose to the exchange
-// of partial tiles) and whose contraction gives every part at least 32 K-steps of 32.
-// Returns the number of parts (1 = no split).
-constexpr int64_t SPLITK_CUS = 256, SPLITK_MAX = 8, SPLITK_MIN_K = 1024, SPLITK_MAX_TILES = 64;
-int plan_splitk(int64_t M, int64_t N, int64_t K, bool f8 = false)
+// Split-K plan, for shapes made of whole tiles (fast kernels) only.  Two cases:
+//  * few tiles: at most 64 output tiles leave at least three quarters of the 256 compute units without one (measured:
+//    with 64 tiles 4 parts win 1.4x, with 128 tiles 2 parts lose to the exchange of partial tiles): every tile is shared;
+//  * partly filled last round: more than 256 tiles whose count is not a multiple of 256 and whose remainder fills at
+//    most half of the chip: only the tiles of that last round are shared, so that it takes 1/parts of a round.  Worth
+//    it when the contraction length a workgroup is spared clearly outweighs the exchange (about 35 us, the time of ~1400
+//    contraction elements of a bf16 tile; the partly filled round itself runs faster than a full one): measured +16 % at
+//    320 tiles and +2 % at 384 tiles with K = 8192, +5 % at 320 tiles with K = 4096.
+// Every part gets at least 32 K-steps of 32 bf16 (64 fp8) elements and an even number of K-steps.
+constexpr int64_t SPLITK_CUS = 256, SPLITK_MAX = 8, SPLITK_MIN_K = 1024, SPLITK_MAX_TILES = 64, SPLITK_TAIL_MIN_SPARED = 3072;
+struct SplitPlan {
+    int parts;    // <= 1: no split
+    int first;    // tiles with id >= first are shared by `parts` workgroups each
+    int shared;   // number of shared tiles
+};
+SplitPlan plan_splitk(int64_t M, int64_t N, int64_t K, bool f8 = false)
 {
     using C = coda::MainCfg;
-    if (M <= 0 || N <= 0 || (M % C::BM) || (N % C::BN) || (K % (f8 ? 128 : C::BK))) return 1;
+    const SplitPlan none = {1, 0, 0};
+    if (M <= 0 || N <= 0 || (M % C::BM) || (N % C::BN) || (K % (f8 ? 128 : C::BK))) return none;
     const int64_t tiles = (M / C::BM) * (N / C::BN);
-    if (tiles > SPLITK_MAX_TILES) return 1;
-    const int64_t min_k = f8 ? 2 * SPLITK_MIN_K : SPLITK_MIN_K;   // 32 K-steps of 32 bf16 or of 64 fp8 elements per part
-    int64_t s = SPLITK_CUS / tiles;
-    if (s > K / min_k) s = K / min_k;
-    if (s > SPLITK_MAX) s = SPLITK_MAX;
-    // the fast kernels walk their K-steps (32 bf16 or 64 fp8 elements) in pairs: every part must get an even number
-    while (s >= 2 && (K / (f8 ? 64 : 32)) % (2 * s)) --s;
-    return s >= 2 ? (int)s : 1;
+    const int64_t scale = f8 ? 2 : 1;                         // an fp8 K-step covers twice the elements in the same time
+    auto fit = [&](int64_t s) {
+        if (s > K / (scale * SPLITK_MIN_K)) s = K / (scale * SPLITK_MIN_K);
+        if (s > SPLITK_MAX) s = SPLITK_MAX;
+        // the fast kernels walk their K-steps (32 bf16 or 64 fp8 elements) in pairs: every part must get an even number
+        while (s >= 2 && (K / (scale * 32)) % (2 * s)) --s;
+        return s >= 2 ? s : (int64_t)1;
+    };
+    if (tiles <= SPLITK_MAX_TILES) {
+        const int64_t s = fit(SPLITK_CUS / tiles);
+        return s >= 2 ? SplitPlan{(int)s, 0, (int)tiles} : none;
+    }
+    const int64_t rem = tiles % SPLITK_CUS;
+    if (tiles < SPLITK_CUS || rem == 0 || rem > SPLITK_CUS / 2) return none;
+    const int64_t s = fit(SPLITK_CUS / rem);
+    if (s < 2 || K - K / s < scale * SPLITK_TAIL_MIN_SPARED) return none;
+    return SplitPlan{(int)s, (int)(tiles - rem), (int)rem};
 }
-constexpr size_t SPLITK_CNT_BYTES = 1024;   // ticket counters (at most 64 tiles x 4 bytes), kept apart from the partials
-size_t splitk_bytes(int64_t M, int64_t N, int parts)
+constexpr size_t SPLITK_CNT_BYTES = 1024;   // ticket counters (at most 128 shared tiles x 4 bytes), kept apart from the partials
+size_t splitk_bytes(const SplitPlan &pl)
 {
     using C = coda::MainCfg;
-    if (parts <= 1) return 0;
-    const size_t tiles = (size_t)((M / C::BM) * (N / C::BN));
-    return SPLITK_CNT_BYTES + tiles * (size_t)parts * C::BM * C::BN * sizeof(float);
+    if (pl.parts <= 1) return 0;
+    return SPLITK_CNT_BYTES + (size_t)pl.shared * (size_t)pl.parts * C::BM * C::BN * sizeof(float);
 }
 
 __global__ void zero_counters_kernel(unsigned *c, int n)
@@ -305,16 +324,16 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
     hipError_t e;
     // split-K only when the caller brought the workspace for it; without one the shape runs unsplit
     if (workspace) {
-        const int parts = plan_splitk(M, N, K, f8);
-        const size_t need = splitk_bytes(M, N, parts);
+        const SplitPlan pl = plan_splitk(M, N, K, f8);
+        const size_t need = splitk_bytes(pl);
         if (!aligned16(workspace)) return CODA_ERR_ALIGN;
         if (workspace_bytes < need) return CODA_ERR_WORKSPACE;
-        if (parts > 1) {
-            const int tiles = (int)((M / C::BM) * (N / C::BN));
-            p.splitk = parts;
+        if (pl.parts > 1) {
+            p.splitk = pl.parts;
+            p.split_from = pl.first;
             p.ws_cnt = static_cast<unsigned *>(workspace);
             p.ws_part = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + SPLITK_CNT_BYTES);
-            hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(256), 0, s, p.ws_cnt, tiles);
+            hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(256), 0, s, p.ws_cnt, pl.shared);
             if ((e = hipGetLastError()) != hipSuccess) return launch_status(e);
         }
     }
@@ -341,7 +360,7 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
 size_t coda_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, const coda_epi_op *, int32_t)
 {
     if (M < 0 || N < 0 || K < 0 || M > INT32_MAX || N > INT32_MAX / 2 || K > INT32_MAX) return 0;
-    return splitk_bytes(M, N, plan_splitk(M, N, K));
+    return splitk_bytes(plan_splitk(M, N, K));
 }
 
 int64_t coda_row_partial_blocks(int64_t N)

@@ -69,11 +69,13 @@ struct GemmParams {
     // target column y[M] and the selected logit z_tgt[M]
     float *lse_max, *lse_sum, *lse_tgt;
     const int *lse_y;
-    // split-K (fast kernel only; splitk <= 1 = off): `splitk` workgroups share one output tile, each contracting a
-    // contiguous part of K.  Every workgroup leaves its fp32 partial tile in ws_part[tile * splitk + split] and takes a
-    // ticket from ws_cnt[tile] (zeroed before the launch); the last one to arrive adds the partials up in split order
+    // split-K (fast kernels only; splitk <= 1 = off): tiles with id >= split_from are shared by `splitk` workgroups
+    // each, every one contracting a contiguous part of K (split_from = 0: all tiles; split_from = a whole number of
+    // 256-workgroup rounds: only the tiles of the last, partly filled round).  With t = tile - split_from, a workgroup
+    // leaves its fp32 partial tile in ws_part[t * splitk + split] and takes a
+    // ticket from ws_cnt[t] (zeroed before the launch); the last one to arrive adds the partials up in split order
     // and runs the epilogue.
-    int splitk;
+    int splitk, split_from;
     float *ws_part;
     unsigned *ws_cnt;
 };
@@ -1045,13 +1047,28 @@ __device__ __forceinline__ void dl_load16(uint32_t voff, const void *sbase, uint
                  : "memory");
 }
 
+// Virtual workgroup -> (tile, part of K, parts of this tile): tiles below split_from are whole, the others are shared
+// by `splitk` workgroups each.  The grid has split_from + (tiles - split_from) * splitk workgroups.
+__device__ __forceinline__ void locate_workgroup(const GemmParams &p, int bid, int &tile_id, int &split, int &nsplit)
+{
+    nsplit = 1;
+    tile_id = bid;
+    split = 0;
+    if (p.splitk > 1 && bid >= p.split_from) {
+        const int w = bid - p.split_from;
+        nsplit = p.splitk;
+        tile_id = p.split_from + w / nsplit;
+        split = w % nsplit;
+    }
+}
+
 // ---------------------------------------------------------------------------------
 // Split-K exchange (fast kernels).  Every workgroup of a tile leaves its fp32 partial in the workspace and takes a
 // ticket; all but the last one to arrive return false (and must exit); the last one gets the sum of all partials,
 // added in split order so that it does not depend on who arrived last, and returns true.
 // ---------------------------------------------------------------------------------
 template <class C, class ACC>
-__device__ __forceinline__ bool splitk_exchange(ACC &acc, const GemmParams &p, int tile_id, int split, int nsplit, float *red, int tid)
+__device__ __forceinline__ bool splitk_exchange(ACC &acc, const GemmParams &p, int tile_id, int split, int nsplit, float *red, int tid)   // tile_id: counted from split_from
 {
     // Partial tile -> workspace in register order: float4 q of thread t at [q][t], fully coalesced.  The layout is
     // private to this exchange.
@@ -1141,10 +1158,10 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % C::WGM, wn = wave / C::WGM;
-    const int nsplit = p.splitk > 1 ? p.splitk : 1;
-    const int tile_id = (int)blockIdx.x / nsplit, split = (int)blockIdx.x % nsplit;
+    int tile_id, split, nsplit;
+    locate_workgroup(p, (int)blockIdx.x, tile_id, split, nsplit);
     int tm, tn;
-    tile_coords(tile_id, (int)gridDim.x / nsplit, p.tiles_m, p.tiles_n, tm, tn);
+    tile_coords(tile_id, p.tiles_m * p.tiles_n, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
     ACC acc;
@@ -1241,7 +1258,7 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     }
     __syncthreads();  // every wave is done with the operand ring before the epilogue reuses it
 
-    if (nsplit > 1 && !splitk_exchange<C>(acc, p, tile_id, split, nsplit, red, tid)) return;
+    if (nsplit > 1 && !splitk_exchange<C>(acc, p, tile_id - p.split_from, split, nsplit, red, tid)) return;
 
     run_epilogue<C, ACC, EPI, false, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
 }
@@ -1291,10 +1308,10 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % C::WGM, wn = wave / C::WGM;
-    const int nsplit = p.splitk > 1 ? p.splitk : 1;
-    const int tile_id = (int)blockIdx.x / nsplit, split = (int)blockIdx.x % nsplit;
+    int tile_id, split, nsplit;
+    locate_workgroup(p, (int)blockIdx.x, tile_id, split, nsplit);
     int tm, tn;
-    tile_coords(tile_id, (int)gridDim.x / nsplit, p.tiles_m, p.tiles_n, tm, tn);
+    tile_coords(tile_id, p.tiles_m * p.tiles_n, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
     using ACC = Acc32<C>;
@@ -1383,7 +1400,7 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     }
     __syncthreads();  // every wave is done with the operand ring before the epilogue reuses it
 
-    if (nsplit > 1 && !splitk_exchange<C>(acc, p, tile_id, split, nsplit, red, tid)) return;
+    if (nsplit > 1 && !splitk_exchange<C>(acc, p, tile_id - p.split_from, split, nsplit, red, tid)) return;
 
     run_epilogue<C, ACC, EPI, false, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
 }

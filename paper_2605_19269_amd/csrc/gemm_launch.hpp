@@ -10,6 +10,14 @@ using MainCfg = TileCfg<256, 256, 64, 2, 4>;   // register-staged kernel (edge t
 using FastCfg = DlCfg<256, 256, 2, 4, 4>;       // direct-to-LDS ring (whole tiles only); 128x64 wave tiles
 static_assert(MainCfg::BM % FastCfg::BM == 0 && MainCfg::BN == FastCfg::BN, "tile grids");
 
+// Workgroups of a fast-kernel launch: whole tiles below split_from, `splitk` workgroups per tile from there on.
+inline unsigned fast_grid(const GemmParams &p)
+{
+    const unsigned tiles = (unsigned)(p.tiles_m * p.tiles_n);
+    if (p.splitk <= 1) return tiles;
+    return (unsigned)p.split_from + (tiles - (unsigned)p.split_from) * (unsigned)p.splitk;
+}
+
 // `p` arrives without tile counts; they depend on the kernel chosen here.  EDGE = false promises that M, N, K
 // are whole multiples of MainCfg's tile (and therefore of the fast tile).
 template <bool AK, bool BKC, int EPI, bool EDGE>
@@ -25,8 +33,7 @@ hipError_t launch_gemm(const GemmParams &p_in, hipStream_t stream)
         using C = FastCfg;
         p.tiles_m = p.M / C::BM;
         p.tiles_n = p.N / C::BN;
-        const unsigned nsplit = p.splitk > 1 ? (unsigned)p.splitk : 1u;
-        hipLaunchKernelGGL((gemm_kernel_dl<C, AK, BKC, EPI>), dim3((unsigned)(p.tiles_m * p.tiles_n) * nsplit), dim3(C::NT), 0, stream, p);
+        hipLaunchKernelGGL((gemm_kernel_dl<C, AK, BKC, EPI>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
     }
     return hipGetLastError();
 }
@@ -39,8 +46,7 @@ hipError_t launch_gemm_f8(const GemmParams &p_in, hipStream_t stream)
     GemmParams p = p_in;
     p.tiles_m = p.M / C::BM;
     p.tiles_n = p.N / C::BN;
-    const unsigned nsplit = p.splitk > 1 ? (unsigned)p.splitk : 1u;
-    hipLaunchKernelGGL((gemm_kernel_dl_f8<C, EPI>), dim3((unsigned)(p.tiles_m * p.tiles_n) * nsplit), dim3(C::NT), 0, stream, p);
+    hipLaunchKernelGGL((gemm_kernel_dl_f8<C, EPI>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
     return hipGetLastError();
 }
 

@@ -155,6 +155,13 @@ def test_splitk_workspace_planning_and_errors(coda):
     assert wb(512, 512, 4096 + 32) == 0                     # not whole tiles: edge kernel, never split
     assert wb(256, 256, 6 * 1024 + 128) == 1024 + 1 * 2 * tile  # 196 K-steps of 32: only 2 parts get an even number each
     assert wb(256, 256, 6 * 1024 + 64) == 0                     # 194 K-steps: no part count gives every part an even number
+    # more than 256 tiles: only a partly filled last round (1 .. 128 tiles) is shared, and only when it pays
+    assert wb(5120, 4096, 4096) == 1024 + 64 * 4 * tile     # 320 tiles: the last 64 shared by 4 workgroups each
+    assert wb(6144, 4096, 8192) == 1024 + 128 * 2 * tile    # 384 tiles: the last 128 shared by 2
+    assert wb(6144, 4096, 4096) == 0                        # 2 parts would spare only 2048 of K: not worth the exchange
+    assert wb(5120, 4096, 2048) == 0                        # contraction too short
+    assert wb(7168, 4096, 4096) == 0                        # 448 tiles: the last round is three quarters full
+    assert wb(8192, 4096, 4096) == 0                        # 512 tiles: whole rounds
     assert wb(0, 512, 4096) == 0 and wb(-1, 512, 4096) == 0
     A, B = _mat(coda, P, 512, 4096), _mat(coda, P, 4096, 512)
     store = _op(coda, coda.CODA_EPI_STORE, out=P, ld_out=512)

@@ -173,3 +173,40 @@ def test_splitk_workspace_rules(oracle):
     ref = oracle.gemm_rowscale(A, B)
     G.assert_f32_signed_close(G.host_f64(o_split.t), ref, "split-K f32 store")
     G.assert_f32_signed_close(G.host_f64(o_plain.t), ref, "unsplit f32 store")
+
+
+@pytest.mark.parametrize("transB", [False, True])
+def test_splitk_last_round_only(oracle, transB):
+    """320 output tiles: the 256 tiles of the first round run whole, the 64 of the last round are shared by 4 workgroups
+    each.  Checked on sampled rows of every tile row (the program is row-local), against the oracle and against the
+    unsplit run of the same shape, and bitwise across repeats."""
+    M, N, K = 5120, 4096, 4096
+    g = np.random.Generator(np.random.PCG64(990 + transB))
+    A, B = operands(g, M, N, K, False, transB, b_std=0.02)
+    C = synth.normal_bf16(g, (M, N), 1.0)
+    rows = np.sort(np.concatenate([np.arange(0, M, 256) + 3, np.arange(0, M, 256) + 250]))
+    nblk = coda.coda_row_partial_blocks(N)
+    dA, dB, dC = G.dev_bf16(A), G.dev_bf16(B), G.dev_bf16(C)
+    ws = workspace(M, N, K)
+    assert ws.numel() == 1024 + 64 * 4 * 256 * 256 * 4
+    outs = []
+    for w in (ws, ws, None):
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        part = torch.empty((nblk, M), dtype=torch.float32, device="cuda")
+        ss = torch.empty(M, dtype=torch.float32, device="cuda")
+        coda.coda_gemm(dA, dB, [coda.add_tile(dC), coda.row_sumsq(part), coda.store(Y)], transB=transB, workspace=w)
+        coda.coda_row_finalize(part, M, nblk, sum_out=ss, d=N, eps=0.0)
+        torch.cuda.synchronize()
+        outs.append((Y, ss))
+    refD, refss = oracle.gemm_residual_sumsq(A, B, C=C, transB=transB, rows=rows)[:2]
+    idx = torch.from_numpy(rows).cuda()
+    G.assert_bf16_close(G.host_f64(outs[0][0][idx]), refD, "last-round split-K residual")
+    G.assert_sumsq_close(G.host_f64(outs[0][1][idx]), refss, "last-round split-K row sum of squares")
+    assert torch.equal(outs[0][0].view(torch.int16), outs[1][0].view(torch.int16)), "repeat differs: order-dependent sum"
+    assert torch.equal(outs[0][1], outs[1][1])
+    # against the unsplit kernel: same products, different fp32 summation order in the shared tiles only
+    d = (outs[0][0].float() - outs[2][0].float()).abs().max().item()
+    assert d <= 0.0625, d          # at most one bf16 step of values of magnitude ~4
+    eq = (outs[0][0].view(torch.int16) == outs[2][0].view(torch.int16)).view(M // 256, 256, N // 256, 256)
+    same_tiles = eq.all(dim=3).all(dim=1).sum().item()
+    assert same_tiles >= 256, "the tiles of the first round must run whole (bitwise equal to the unsplit launch): %d" % same_tiles
