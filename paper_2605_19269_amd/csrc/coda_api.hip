@@ -217,7 +217,7 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
     return final_seen ? CODA_OK : CODA_ERR_PROGRAM;
 }
 
-// Split-K plan, for shapes made of whole tiles (fast kernels) only.  Two cases:
+// Split-K plan, for shapes that take a fast kernel (K a whole number of K-steps; tiles counted with the ragged edge).  Two cases:
 //  * few tiles: at most 64 output tiles leave at least three quarters of the 256 compute units without one (measured:
 //    with 64 tiles 4 parts win 1.4x, with 128 tiles 2 parts lose to the exchange of partial tiles): every tile is shared;
 //  * partly filled last round: more than 256 tiles whose count is not a multiple of 256 and whose remainder fills at
@@ -236,8 +236,8 @@ SplitPlan plan_splitk(int64_t M, int64_t N, int64_t K, bool f8 = false)
 {
     using C = coda::MainCfg;
     const SplitPlan none = {1, 0, 0};
-    if (M <= 0 || N <= 0 || (M % C::BM) || (N % C::BN) || (K % (f8 ? 128 : C::BK))) return none;
-    const int64_t tiles = (M / C::BM) * (N / C::BN);
+    if (M <= 0 || N <= 0 || (K % (f8 ? 128 : C::BK))) return none;      // fast kernels: whole K-steps; M, N may be ragged
+    const int64_t tiles = ((M + C::BM - 1) / C::BM) * ((N + C::BN - 1) / C::BN);
     const int64_t scale = f8 ? 2 : 1;                         // an fp8 K-step covers twice the elements in the same time
     auto fit = [&](int64_t s) {
         if (s > K / (scale * SPLITK_MIN_K)) s = K / (scale * SPLITK_MIN_K);
@@ -270,21 +270,27 @@ __global__ void zero_counters_kernel(unsigned *c, int n)
     if (i < n) c[i] = 0u;
 }
 
+template <bool AK, bool BKC, int EPI>
+hipError_t dispatch_kind(int kind, const coda::GemmParams &p, hipStream_t s)
+{
+    using namespace coda;
+    switch (kind) {
+    case KIND_WHOLE: return launch_gemm<AK, BKC, EPI, KIND_WHOLE>(p, s);
+    case KIND_RAGGED_MN: return launch_gemm<AK, BKC, EPI, KIND_RAGGED_MN>(p, s);
+    default: return launch_gemm<AK, BKC, EPI, KIND_EDGE>(p, s);
+    }
+}
+
 template <bool AK, bool BKC>
-hipError_t dispatch_mode(int mode, bool edge, const coda::GemmParams &p, hipStream_t s)
+hipError_t dispatch_mode(int mode, int kind, const coda::GemmParams &p, hipStream_t s)
 {
     using namespace coda;
     switch (mode) {
-    case EPI_LINEAR:
-        return edge ? launch_gemm<AK, BKC, EPI_LINEAR, true>(p, s) : launch_gemm<AK, BKC, EPI_LINEAR, false>(p, s);
-    case EPI_SWIGLU_FWD:
-        return edge ? launch_gemm<AK, BKC, EPI_SWIGLU_FWD, true>(p, s) : launch_gemm<AK, BKC, EPI_SWIGLU_FWD, false>(p, s);
-    case EPI_SWIGLU_BWD:
-        return edge ? launch_gemm<AK, BKC, EPI_SWIGLU_BWD, true>(p, s) : launch_gemm<AK, BKC, EPI_SWIGLU_BWD, false>(p, s);
-    case EPI_RMSNORM_BWD:
-        return edge ? launch_gemm<AK, BKC, EPI_RMSNORM_BWD, true>(p, s) : launch_gemm<AK, BKC, EPI_RMSNORM_BWD, false>(p, s);
-    default:
-        return edge ? launch_gemm<AK, BKC, EPI_ACCUM, true>(p, s) : launch_gemm<AK, BKC, EPI_ACCUM, false>(p, s);
+    case EPI_LINEAR: return dispatch_kind<AK, BKC, EPI_LINEAR>(kind, p, s);
+    case EPI_SWIGLU_FWD: return dispatch_kind<AK, BKC, EPI_SWIGLU_FWD>(kind, p, s);
+    case EPI_SWIGLU_BWD: return dispatch_kind<AK, BKC, EPI_SWIGLU_BWD>(kind, p, s);
+    case EPI_RMSNORM_BWD: return dispatch_kind<AK, BKC, EPI_RMSNORM_BWD>(kind, p, s);
+    default: return dispatch_kind<AK, BKC, EPI_ACCUM>(kind, p, s);
     }
 }
 
@@ -317,7 +323,8 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
     p.N = (int)N;
     p.K = (int)K;
     if (((M + C::BM - 1) / C::BM) * ((N + C::BN - 1) / C::BN) * 2 > INT32_MAX) return CODA_ERR_SHAPE;
-    const bool edge = (M % C::BM) || (N % C::BN) || (K % C::BK);
+    // whole tiles | whole K-steps but a ragged edge in M or N | anything else
+    const int kind = (K % C::BK) ? coda::KIND_EDGE : (((M % C::BM) || (N % C::BN)) ? coda::KIND_RAGGED_MN : coda::KIND_WHOLE);
     const bool ak = !A->trans;   // A stored [M x K]: contraction index contiguous
     const bool bkc = B->trans;   // B stored [N x K]: contraction index contiguous
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -347,13 +354,13 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
         default: e = launch_gemm_f8<EPI_ACCUM>(p, s); break;
         }
     } else if (ak && !bkc)
-        e = dispatch_mode<true, false>(ps.mode, edge, p, s);
+        e = dispatch_mode<true, false>(ps.mode, kind, p, s);
     else if (ak && bkc)
-        e = dispatch_mode<true, true>(ps.mode, edge, p, s);
+        e = dispatch_mode<true, true>(ps.mode, kind, p, s);
     else if (!ak && !bkc)
-        e = dispatch_mode<false, false>(ps.mode, edge, p, s);
+        e = dispatch_mode<false, false>(ps.mode, kind, p, s);
     else
-        e = dispatch_mode<false, true>(ps.mode, edge, p, s);
+        e = dispatch_mode<false, true>(ps.mode, kind, p, s);
     return launch_status(e);
 }
 

@@ -1021,20 +1021,25 @@ struct DlCfg : TileCfg<BM_, BN_, 32, WGM_, WGN_> {
 __device__ __forceinline__ int kc16_swz(int r) { return ((r >> 2) & 1) << 1; }
 
 // Byte offset (from the tile's first element in global memory) of the chunk that lane `lane`
-// of wave-load `j` must fetch so that it lands at its swizzled LDS home.
+// of wave-load `j` must fetch so that it lands at its swizzled LDS home.  `valid` (<= ROWS) is the number of rows of
+// the operand tile that exist (a tile on the ragged edge of M or N): positions past it fetch the last existing row
+// (or 8-element chunk) again, so that no load leaves the matrix; what they feed is masked out by the epilogue.
 template <class C, int ROWS, bool KCONT>
-__device__ __forceinline__ uint32_t dl_goffset(int j, int lane, int64_t ld)
+__device__ __forceinline__ uint32_t dl_goffset(int j, int lane, int64_t ld, int valid)
 {
     if (KCONT) {  // [ROWS][32]: 64-byte rows, 16 rows per wave-load
         const int r = j * 16 + (lane >> 2);
         const int c = (lane & 3) ^ kc16_swz(r);
-        return (uint32_t)(((int64_t)r * ld + c * 8) * 2);
-    } else {      // [32][ROWS]: 2 k-rows per wave-load (ROWS = 256) or 4 (ROWS = 128)
+        const int rg = r < valid ? r : valid - 1;
+        return (uint32_t)(((int64_t)rg * ld + c * 8) * 2);
+    } else {      // [32][ROWS]: 2 k-rows per wave-load (ROWS = 256) or 4 (ROWS = 128); valid is a multiple of 8
         constexpr int CPR = ROWS / 8;  // chunks per k-row
         const int idx = j * 64 + lane;
         const int k = idx / CPR, pc = idx % CPR;
         const int g = (pc >> 1) ^ mn_swz(k);
-        return (uint32_t)(((int64_t)k * ld + (g * 2 + (pc & 1)) * 8) * 2);
+        const int col = (g * 2 + (pc & 1)) * 8;
+        const int cg = col < valid ? col : valid - 8;
+        return (uint32_t)(((int64_t)k * ld + cg) * 2);
     }
 }
 
@@ -1144,7 +1149,9 @@ __device__ __forceinline__ bf16x8 dl_frag16(const unsigned char *tile, int row_b
 // loads of tile kt+1 before step D.  The loads are issued from inline asm, invisible to the compiler's waitcnt
 // insertion; vmcnt is waited on explicitly (loads retire in order).  K-steps are walked in pairs so that the two
 // column-fragment buffers swap roles without copies: the host guarantees an even, positive count per workgroup.
-template <class C, bool AK, bool BKC, int EPI>
+// RAGGED: M and / or N are not whole numbers of tiles (K is): edge tiles clamp their operand fetches and run the
+// bounds-checked epilogue.
+template <class C, bool AK, bool BKC, int EPI, bool RAGGED>
 __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE))) void gemm_kernel_dl(const GemmParams p)
 {
     constexpr int BM = C::BM, BN = C::BN, BK = 32, S = C::STAGES;
@@ -1173,11 +1180,13 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     const int KT = (int)((int64_t)KT_all * (split + 1) / nsplit) - kbeg;
 
     // loop-invariant per-lane byte offsets of this wave's chunks; wave w issues wave-loads w*L .. w*L+L-1
+    const int valid_m = RAGGED ? (p.M - m0 < BM ? p.M - m0 : BM) : BM;
+    const int valid_n = RAGGED ? (p.N - n0 < BN ? p.N - n0 : BN) : BN;
     uint32_t offa[LA], offb[LB];
 #pragma unroll
-    for (int i = 0; i < LA; ++i) offa[i] = dl_goffset<C, BM, AK>(wave * LA + i, lane, p.lda);
+    for (int i = 0; i < LA; ++i) offa[i] = dl_goffset<C, BM, AK>(wave * LA + i, lane, p.lda, valid_m);
 #pragma unroll
-    for (int i = 0; i < LB; ++i) offb[i] = dl_goffset<C, BN, BKC>(wave * LB + i, lane, p.ldb);
+    for (int i = 0; i < LB; ++i) offb[i] = dl_goffset<C, BN, BKC>(wave * LB + i, lane, p.ldb, valid_n);
     // scalar bases of the tile's first element; advance by one K-step per tile
     const int64_t stepa = AK ? (int64_t)BK * 2 : (int64_t)BK * p.lda * 2;
     const int64_t stepb = BKC ? (int64_t)BK * 2 : (int64_t)BK * p.ldb * 2;
@@ -1260,7 +1269,7 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 
     if (nsplit > 1 && !splitk_exchange<C>(acc, p, tile_id - p.split_from, split, nsplit, red, tid)) return;
 
-    run_epilogue<C, ACC, EPI, false, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
+    run_epilogue<C, ACC, EPI, RAGGED, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
 }
 
 // ---------------------------------------------------------------------------------
@@ -1405,8 +1414,9 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     run_epilogue<C, ACC, EPI, false, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
 }
 
-// Host-side launcher, one per (operand layouts, epilogue mode, edge predication).
-template <bool AK, bool BKC, int EPI, bool EDGE>
+// Host-side launcher, one per (operand layouts, epilogue mode, kernel kind).
+enum KernelKind : int { KIND_WHOLE = 0, KIND_RAGGED_MN = 1, KIND_EDGE = 2 };
+template <bool AK, bool BKC, int EPI, int KIND>
 hipError_t launch_gemm(const GemmParams &p, hipStream_t stream);
 
 }  // namespace coda

@@ -18,22 +18,21 @@ inline unsigned fast_grid(const GemmParams &p)
     return (unsigned)p.split_from + (tiles - (unsigned)p.split_from) * (unsigned)p.splitk;
 }
 
-// `p` arrives without tile counts; they depend on the kernel chosen here.  EDGE = false promises that M, N, K
-// are whole multiples of MainCfg's tile (and therefore of the fast tile).
-template <bool AK, bool BKC, int EPI, bool EDGE>
+// `p` arrives without tile counts; they depend on the kernel chosen here.
+//   KIND_WHOLE:     M, N, K are whole multiples of MainCfg's tile (and therefore of the fast tile);
+//   KIND_RAGGED_MN: K is, M and / or N are not: fast kernel with clamped operand fetches and bounds-checked epilogue;
+//   KIND_EDGE:      anything else: register-staged kernel, predicated everywhere.
+template <bool AK, bool BKC, int EPI, int KIND>
 hipError_t launch_gemm(const GemmParams &p_in, hipStream_t stream)
 {
     GemmParams p = p_in;
-    if constexpr (EDGE) {
-        using C = MainCfg;
-        p.tiles_m = (p.M + C::BM - 1) / C::BM;
-        p.tiles_n = (p.N + C::BN - 1) / C::BN;
+    using C = std::conditional_t<KIND == KIND_EDGE, MainCfg, FastCfg>;
+    p.tiles_m = (p.M + C::BM - 1) / C::BM;
+    p.tiles_n = (p.N + C::BN - 1) / C::BN;
+    if constexpr (KIND == KIND_EDGE) {
         hipLaunchKernelGGL((gemm_kernel<C, AK, BKC, EPI, true>), dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(C::NT), 0, stream, p);
     } else {
-        using C = FastCfg;
-        p.tiles_m = p.M / C::BM;
-        p.tiles_n = p.N / C::BN;
-        hipLaunchKernelGGL((gemm_kernel_dl<C, AK, BKC, EPI>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
+        hipLaunchKernelGGL((gemm_kernel_dl<C, AK, BKC, EPI, KIND == KIND_RAGGED_MN>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
     }
     return hipGetLastError();
 }
@@ -51,8 +50,9 @@ hipError_t launch_gemm_f8(const GemmParams &p_in, hipStream_t stream)
 }
 
 #define CODA_INSTANTIATE_ONE(AK, BKC, EPI)                                                   \
-    template hipError_t launch_gemm<AK, BKC, EPI, false>(const GemmParams &, hipStream_t);   \
-    template hipError_t launch_gemm<AK, BKC, EPI, true>(const GemmParams &, hipStream_t);
+    template hipError_t launch_gemm<AK, BKC, EPI, KIND_WHOLE>(const GemmParams &, hipStream_t);      \
+    template hipError_t launch_gemm<AK, BKC, EPI, KIND_RAGGED_MN>(const GemmParams &, hipStream_t);  \
+    template hipError_t launch_gemm<AK, BKC, EPI, KIND_EDGE>(const GemmParams &, hipStream_t);
 
 #define CODA_INSTANTIATE_LAYOUT(AK, BKC)            \
     CODA_INSTANTIATE_ONE(AK, BKC, EPI_LINEAR)       \
@@ -65,8 +65,9 @@ hipError_t launch_gemm_f8(const GemmParams &p_in, hipStream_t stream)
 // unless CODA_GEMM_INSTANTIATION_UNIT is defined, every launcher is declared as instantiated elsewhere.
 #ifndef CODA_GEMM_INSTANTIATION_UNIT
 #define CODA_EXTERN_ONE(AK, BKC, EPI)                                                               \
-    extern template hipError_t launch_gemm<AK, BKC, EPI, false>(const GemmParams &, hipStream_t);  \
-    extern template hipError_t launch_gemm<AK, BKC, EPI, true>(const GemmParams &, hipStream_t);
+    extern template hipError_t launch_gemm<AK, BKC, EPI, KIND_WHOLE>(const GemmParams &, hipStream_t);      \
+    extern template hipError_t launch_gemm<AK, BKC, EPI, KIND_RAGGED_MN>(const GemmParams &, hipStream_t);  \
+    extern template hipError_t launch_gemm<AK, BKC, EPI, KIND_EDGE>(const GemmParams &, hipStream_t);
 #define CODA_EXTERN_LAYOUT(AK, BKC)            \
     CODA_EXTERN_ONE(AK, BKC, EPI_LINEAR)       \
     CODA_EXTERN_ONE(AK, BKC, EPI_SWIGLU_FWD)   \

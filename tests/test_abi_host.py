@@ -152,7 +152,8 @@ def test_splitk_workspace_planning_and_errors(coda):
     assert wb(2048, 2048, 8192) == 1024 + 64 * 4 * tile     # 64 tiles: 4 parts fill the 256 compute units
     assert wb(2048, 2048 + 256, 8192) == 0                  # 72 tiles: more than a quarter of the chip already busy
     assert wb(512, 512, 1024) == 0                          # contraction too short to split
-    assert wb(512, 512, 4096 + 32) == 0                     # not whole tiles: edge kernel, never split
+    assert wb(512, 512, 4096 + 32) == 0                     # not whole K-steps: edge kernel, never split
+    assert wb(504, 264, 4096) == 1024 + 4 * 4 * tile        # ragged M and N: 2 x 2 tiles, shared like whole ones
     assert wb(256, 256, 6 * 1024 + 128) == 1024 + 1 * 2 * tile  # 196 K-steps of 32: only 2 parts get an even number each
     assert wb(256, 256, 6 * 1024 + 64) == 0                     # 194 K-steps: no part count gives every part an even number
     # more than 256 tiles: only a partly filled last round (1 .. 128 tiles) is shared, and only when it pays

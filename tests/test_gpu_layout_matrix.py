@@ -1,6 +1,7 @@
 """GPU parity, layout x epilogue matrix: every epilogue mode of coda_gemm is instantiated once per operand
-layout (A or A^T, B or B^T).  Each (layout, mode) pair is run once on a shape that takes the fast kernel
-(whole 256 x 256 x 64 tiles) and once on a ragged shape that takes the edge kernel, against the CPU oracle."""
+layout (A or A^T, B or B^T).  Each (layout, mode) pair is run on a shape that takes the fast kernel
+(whole 256 x 256 x 64 tiles), on a shape ragged in every dimension that takes the edge kernel, and on a shape ragged
+in M and N only that takes the fast kernel with clamped operand fetches, against the CPU oracle."""
 import numpy as np
 import pytest
 import torch
@@ -11,7 +12,7 @@ from tests import gpu_util as G
 pytestmark = pytest.mark.gpu
 
 LAYOUTS = [(False, False), (False, True), (True, False), (True, True)]
-SHAPES = [(256, 512, 128), (264, 520, 72)]          # whole tiles | ragged in every dimension
+SHAPES = [(256, 512, 128), (264, 520, 72), (264, 520, 128)]   # whole tiles | ragged in every dimension | ragged in M and N only
 
 coda = None
 

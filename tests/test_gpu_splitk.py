@@ -39,8 +39,9 @@ def operands(g, M, N, K, transA, transB, a_std=1.0, b_std=0.05):
 
 
 # (M, N, K) -> parts: 4 tiles, K = 4096 -> 4;  1 tile, K = 8192 -> 8;  2 tiles, K = 2048 -> 2;
-# 1 tile, K = 6272 (196 K-steps of 32) -> 2, the only count that gives every part an even number of steps
-SHAPES = [(512, 512, 4096), (256, 256, 8192), (256, 512, 2048), (256, 256, 6272)]
+# 1 tile, K = 6272 (196 K-steps of 32) -> 2, the only count that gives every part an even number of steps;
+# 2 x 2 tiles with a ragged edge in M and N, K = 4096 -> 4
+SHAPES = [(512, 512, 4096), (256, 256, 8192), (256, 512, 2048), (256, 256, 6272), (504, 264, 4096)]
 
 
 @pytest.mark.parametrize("transA,transB", [(False, False), (False, True), (True, False)])
@@ -148,10 +149,11 @@ def test_splitk_workspace_rules(oracle):
     dA, dB = G.dev_bf16(A), G.dev_bf16(B)
     need = coda.coda_gemm_workspace_bytes(M, N, K, [])
     assert need == 1024 + 4 * 4 * 256 * 256 * 4          # counters + tiles x parts x one fp32 tile
-    # shapes that are not split ask for nothing: many tiles, short K, ragged
+    # shapes that are not split ask for nothing: many tiles, short K, K not a whole number of K-steps
     assert coda.coda_gemm_workspace_bytes(8192, 8192, 8192, []) == 0
     assert coda.coda_gemm_workspace_bytes(512, 512, 1024, []) == 0
-    assert coda.coda_gemm_workspace_bytes(520, 512, 4096, []) == 0
+    assert coda.coda_gemm_workspace_bytes(512, 512, 4096 + 8, []) == 0
+    assert coda.coda_gemm_workspace_bytes(520, 512, 4096, []) == 1024 + 6 * 4 * 256 * 256 * 4   # ragged M: 3 x 2 tiles
     out = G.Guarded(M, N, torch.bfloat16)
     small = torch.empty(need - 16, dtype=torch.uint8, device="cuda")
     with pytest.raises(coda.CodaError) as ei:
