@@ -172,7 +172,7 @@ def main():
         g_c = torch.Generator(device=dev).manual_seed(5)
         fa = torch.randn(nb_c * 4 * 512 * 8, device=dev, generator=g_c).to(torch.bfloat16)          # activations ~ N(0, 1)
         fb = (torch.randn(nb_c * 2 * 512 * 8, device=dev, generator=g_c) * 0.02).to(torch.bfloat16)   # weights ~ N(0, 0.02)
-        # the bf16 fast kernel issues v_mfma_f32_16x16x32_bf16 (loop16); the 32x32x16 loop is kept beside it
+        # the bf16 kernel issues v_mfma_f32_16x16x32_bf16 (loop16); the 32x32x16 loop is kept beside it
         ms_r = min(time_kernel(lambda: coda.coda_calib_mfma_loop16(fa, fb, nb_c, it_c), reps=3, warm=2) for _ in range(2))
         ms_r32 = min(time_kernel(lambda: coda.coda_calib_mfma_loop(fa, fb, nb_c, it_c), reps=3, warm=2) for _ in range(2))
         fa.zero_(); fb.zero_()

@@ -180,7 +180,7 @@ typedef struct coda_epi_op {
  * multiple of 128; anything else is CODA_ERR_DTYPE (layout, mixed dtypes) or CODA_ERR_SHAPE (sizes).
  *
  * workspace / workspace_bytes (device memory, 16-byte aligned; may be NULL): scratch for split-K.
- * Shapes with K a multiple of 64, at most 64 output tiles (256 x 256, counted with a ragged edge) and K >= 2048 leave
+ * Shapes with at most 64 output tiles (256 x 256, counted with a ragged edge) and K >= 2048 leave
  * most of the chip idle, and shapes with more than 256 tiles whose count modulo 256 is between 1 and
  * 128 end with a round of tiles that fills at most half of it (long contractions only: K >= 4096).  For them
  * coda_gemm_workspace_bytes returns a non-zero size, and a call

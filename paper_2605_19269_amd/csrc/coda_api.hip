@@ -217,7 +217,7 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
     return final_seen ? CODA_OK : CODA_ERR_PROGRAM;
 }
 
-// Split-K plan, for shapes that take a fast kernel (K a whole number of K-steps; tiles counted with the ragged edge).  Two cases:
+// Split-K plan (tiles and K-steps counted with their ragged edges).  Two cases:
 //  * few tiles: at most 64 output tiles leave at least three quarters of the 256 compute units without one (measured:
 //    with 64 tiles 4 parts win 1.4x, with 128 tiles 2 parts lose to the exchange of partial tiles): every tile is shared;
 //  * partly filled last round: more than 256 tiles whose count is not a multiple of 256 and whose remainder fills at
@@ -234,16 +234,16 @@ struct SplitPlan {
 };
 SplitPlan plan_splitk(int64_t M, int64_t N, int64_t K, bool f8 = false)
 {
-    using C = coda::MainCfg;
     const SplitPlan none = {1, 0, 0};
-    if (M <= 0 || N <= 0 || (K % (f8 ? 128 : C::BK))) return none;      // fast kernels: whole K-steps; M, N may be ragged
-    const int64_t tiles = ((M + C::BM - 1) / C::BM) * ((N + C::BN - 1) / C::BN);
+    if (M <= 0 || N <= 0 || K <= 0) return none;
+    const int64_t tiles = ((M + coda::TILE_M - 1) / coda::TILE_M) * ((N + coda::TILE_N - 1) / coda::TILE_N);
     const int64_t scale = f8 ? 2 : 1;                         // an fp8 K-step covers twice the elements in the same time
+    const int64_t steps = (K + scale * 64 - 1) / (scale * 64) * 2;   // K-steps of 32 bf16 / 64 fp8 elements, in whole pairs
     auto fit = [&](int64_t s) {
         if (s > K / (scale * SPLITK_MIN_K)) s = K / (scale * SPLITK_MIN_K);
         if (s > SPLITK_MAX) s = SPLITK_MAX;
-        // the fast kernels walk their K-steps (32 bf16 or 64 fp8 elements) in pairs: every part must get an even number
-        while (s >= 2 && (K / (scale * 32)) % (2 * s)) --s;
+        // the kernels walk their K-steps in pairs: every part must get an even number
+        while (s >= 2 && steps % (2 * s)) --s;
         return s >= 2 ? s : (int64_t)1;
     };
     if (tiles <= SPLITK_MAX_TILES) {
@@ -259,9 +259,8 @@ SplitPlan plan_splitk(int64_t M, int64_t N, int64_t K, bool f8 = false)
 constexpr size_t SPLITK_CNT_BYTES = 1024;   // ticket counters (at most 128 shared tiles x 4 bytes), kept apart from the partials
 size_t splitk_bytes(const SplitPlan &pl)
 {
-    using C = coda::MainCfg;
     if (pl.parts <= 1) return 0;
-    return SPLITK_CNT_BYTES + (size_t)pl.shared * (size_t)pl.parts * C::BM * C::BN * sizeof(float);
+    return SPLITK_CNT_BYTES + (size_t)pl.shared * (size_t)pl.parts * coda::TILE_M * coda::TILE_N * sizeof(float);
 }
 
 __global__ void zero_counters_kernel(unsigned *c, int n)
@@ -276,8 +275,7 @@ hipError_t dispatch_kind(int kind, const coda::GemmParams &p, hipStream_t s)
     using namespace coda;
     switch (kind) {
     case KIND_WHOLE: return launch_gemm<AK, BKC, EPI, KIND_WHOLE>(p, s);
-    case KIND_RAGGED_MN: return launch_gemm<AK, BKC, EPI, KIND_RAGGED_MN>(p, s);
-    default: return launch_gemm<AK, BKC, EPI, KIND_EDGE>(p, s);
+    default: return launch_gemm<AK, BKC, EPI, KIND_RAGGED>(p, s);
     }
 }
 
@@ -307,13 +305,12 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
     if ((st = check_operand(B, K, N)) != CODA_OK) return st;
     const bool f8 = A->dtype == CODA_F8E4M3 || B->dtype == CODA_F8E4M3;
     if (f8 && (A->dtype != B->dtype || A->trans || !B->trans)) return CODA_ERR_DTYPE;   // both 8-bit, both K-contiguous
-    if (f8 && ((M % coda::MainCfg::BM) || (N % coda::MainCfg::BN) || (K % 128))) return CODA_ERR_SHAPE;
+    if (f8 && ((M % coda::TILE_M) || (N % coda::TILE_N) || (K % 128))) return CODA_ERR_SHAPE;
     if ((K & 7) || (N & 7) || (A->trans && (M & 7))) return CODA_ERR_SHAPE;
     Parsed ps;
     if ((st = parse_program(prog, n_ops, N, ps)) != CODA_OK) return st;
     if (M == 0 || N == 0) return CODA_OK;
 
-    using C = coda::MainCfg;
     coda::GemmParams &p = ps.p;
     p.A = static_cast<const uint16_t *>(A->ptr);
     p.B = static_cast<const uint16_t *>(B->ptr);
@@ -322,9 +319,8 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
     p.M = (int)M;
     p.N = (int)N;
     p.K = (int)K;
-    if (((M + C::BM - 1) / C::BM) * ((N + C::BN - 1) / C::BN) * 2 > INT32_MAX) return CODA_ERR_SHAPE;
-    // whole tiles | whole K-steps but a ragged edge in M or N | anything else
-    const int kind = (K % C::BK) ? coda::KIND_EDGE : (((M % C::BM) || (N % C::BN)) ? coda::KIND_RAGGED_MN : coda::KIND_WHOLE);
+    if (((M + coda::TILE_M - 1) / coda::TILE_M) * ((N + coda::TILE_N - 1) / coda::TILE_N) * 2 > INT32_MAX) return CODA_ERR_SHAPE;
+    const int kind = ((K % coda::TILE_K) || (M % coda::TILE_M) || (N % coda::TILE_N)) ? coda::KIND_RAGGED : coda::KIND_WHOLE;
     const bool ak = !A->trans;   // A stored [M x K]: contraction index contiguous
     const bool bkc = B->trans;   // B stored [N x K]: contraction index contiguous
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -372,7 +368,7 @@ size_t coda_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, const coda_epi
 
 int64_t coda_row_partial_blocks(int64_t N)
 {
-    return N <= 0 ? 0 : (N + coda::MainCfg::BN - 1) / coda::MainCfg::BN;
+    return N <= 0 ? 0 : (N + coda::TILE_N - 1) / coda::TILE_N;
 }
 
 coda_status coda_lse_finalize(void *stream, const float *pmax, const float *psum, int64_t M, int64_t nblk, const float *ztgt,
@@ -387,7 +383,7 @@ coda_status coda_lse_finalize(void *stream, const float *pmax, const float *psum
 
 int64_t coda_col_partial_blocks(int64_t M)
 {
-    return M <= 0 ? 0 : (M + coda::MainCfg::BM - 1) / coda::MainCfg::BM;
+    return M <= 0 ? 0 : (M + coda::TILE_M - 1) / coda::TILE_M;
 }
 
 coda_status coda_col_finalize(void *stream, const float *partials, int64_t N, int64_t nblk, float *out)

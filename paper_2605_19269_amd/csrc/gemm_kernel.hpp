@@ -1,7 +1,7 @@
 // gemm_kernel.hpp -- bf16 MFMA GEMM mainloop + epilogue program for gfx950 (MI355X).
 //
-// D = op(A) op(B) with fp32 accumulation on the matrix cores (v_mfma_f32_16x16x32_bf16 in the fast kernel,
-// v_mfma_f32_32x32x16_bf16 in the edge kernel, v_mfma_f32_32x32x64_f8f6f4 for 8-bit operands), followed by
+// D = op(A) op(B) with fp32 accumulation on the matrix cores (v_mfma_f32_16x16x32_bf16 for bf16 operands,
+// v_mfma_f32_32x32x64_f8f6f4 for 8-bit operands), followed by
 // the epilogue primitives of the paper's Section 3.1 applied to the accumulators
 // while they are still in registers (kernel forms: Appendix "List of Kernels",
 // Kernels 1 - 10, plus the accumulating weight gradient of Theorem 1).
@@ -16,7 +16,7 @@
 // register arithmetic, and a row's columns of a block live in just two (four) lanes,
 // so a row reduction is in-lane adds plus one (two) cross-lane exchanges.
 //
-// Operand staging.  Tiles are copied global -> registers -> LDS in 16-byte chunks
+// Operand staging.  Tiles are copied global -> LDS in 16-byte chunks
 // exactly as they lie in memory.  An operand whose contraction index is
 // contiguous in memory ("K-contiguous": A as stored [M x K], B stored [N x K]) is
 // kept as [rows][BK] and fragments are read with ds_read_b128.  An operand whose
@@ -83,12 +83,6 @@ struct GemmParams {
 // ---------------------------------------------------------------------------------
 // LDS layouts
 // ---------------------------------------------------------------------------------
-// K-contiguous tile [ROWS][BK]: 16-byte chunk c of row r.
-template <int BK>
-__device__ __forceinline__ uint32_t lds_kc(int r, int c)
-{
-    return (uint32_t)(r * (BK * 2) + (((c ^ (r >> 1)) & (BK / 8 - 1)) << 4));
-}
 // MN-contiguous tile [BK][ROWS]: 32-byte granule gr (16 elements) of k-row k.
 // The transposing read serves 32 lanes per LDS cycle: four k-rows (k & 3) of two adjacent granules.
 // XOR-ing the granule with 2*(k & 3) sends those eight 32-byte pieces to eight different bank groups.
@@ -145,84 +139,9 @@ struct TileCfg {
     static constexpr int FM = WTM / 32, FN = WTN / 32;
     static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    static constexpr int CHA = BM * BK / 8 / NT, CHB = BN * BK / 8 / NT;  // 16-byte chunks per thread
     static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tiles are multiples of 32");
-    static_assert(BK % 16 == 0 && (BM * BK / 8) % NT == 0 && (BN * BK / 8) % NT == 0, "chunking");
     static_assert(BM >= 128 && BN >= 128, "granule swizzle needs >= 8 granules per k-row");
 };
-
-// Global -> register loads of one operand tile (chunks laid out as in memory).
-template <class C, int ROWS, int CH, bool KCONT, bool EDGE>
-__device__ __forceinline__ void tile_gload(u32x4 (&r)[CH], const uint16_t *__restrict__ base, int64_t ld,
-                                           int row0, int k0, int rows_total, int K, int tid)
-{
-#pragma unroll
-    for (int it = 0; it < CH; ++it) {
-        const int ci = tid + it * C::NT;
-        int rr, kk;  // row (output index) and k of the chunk's first element
-        if (KCONT) {
-            rr = ci / (C::BK / 8);
-            kk = (ci % (C::BK / 8)) * 8;
-        } else {
-            kk = ci / (ROWS / 8);
-            rr = (ci % (ROWS / 8)) * 8;
-        }
-        const int gr = row0 + rr, gk = k0 + kk;
-        const uint16_t *src = KCONT ? base + (int64_t)gr * ld + gk : base + (int64_t)gk * ld + gr;
-        if (EDGE) {
-            const bool ok = gr < rows_total && gk < K;
-            u32x4 z = {0u, 0u, 0u, 0u};
-            r[it] = ok ? *reinterpret_cast<const u32x4 *>(src) : z;
-        } else {
-            r[it] = *reinterpret_cast<const u32x4 *>(src);
-        }
-    }
-}
-
-// Register -> LDS stores of one operand tile.
-template <class C, int ROWS, int CH, bool KCONT>
-__device__ __forceinline__ void tile_lstore(const u32x4 (&r)[CH], unsigned char *tile, int tid)
-{
-#pragma unroll
-    for (int it = 0; it < CH; ++it) {
-        const int ci = tid + it * C::NT;
-        uint32_t off;
-        if (KCONT) {
-            off = lds_kc<C::BK>(ci / (C::BK / 8), ci % (C::BK / 8));
-        } else {
-            const int kk = ci / (ROWS / 8), c8 = ci % (ROWS / 8);
-            off = lds_mn<ROWS>(kk, c8 >> 1) + ((c8 & 1) << 4);
-        }
-        *reinterpret_cast<u32x4 *>(tile + off) = r[it];
-    }
-}
-
-// One MFMA operand fragment (32 rows x 16 k) from an LDS tile.
-//   lane l holds row (l % 32), k = 8*(l/32) .. 8*(l/32)+7 of the 16-wide k-slice `ks`.
-template <class C, int ROWS, bool KCONT>
-__device__ __forceinline__ bf16x8 frag_load(const unsigned char *tile, int row_base, int ks, int lane)
-{
-    if (KCONT) {
-        const int r = row_base + (lane & 31);
-        const int c = ks * 2 + (lane >> 5);
-        return *reinterpret_cast<const bf16x8 *>(tile + lds_kc<C::BK>(r, c));
-    } else {
-        // transposing read: within each 16-lane group, lane i supplies the address of k-row
-        // (i/4), columns 4*(i%4)..+3 and receives column i of those four k-rows.
-        const int i = lane & 15, nh = (lane >> 4) & 1, h = lane >> 5;
-        const int gr = (row_base >> 4) + nh;
-        const int k_lo = ks * 16 + 8 * h + (i >> 2);
-        const uint32_t sub = (uint32_t)((i & 3) << 3);
-        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-        const uint32_t o0 = lds_mn<ROWS>(k_lo, gr) + sub;
-        const uint32_t o1 = lds_mn<ROWS>(k_lo + 4, gr) + sub;
-        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tile + o0));
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tile + o1));
-        typedef __attribute__((ext_vector_type(8))) short s16x8;
-        s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        return __builtin_bit_cast(bf16x8, v);
-    }
-}
 
 // ---------------------------------------------------------------------------------
 // Row staging through LDS (epilogue I/O).
@@ -389,7 +308,7 @@ __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? l
 // groups of four consecutive output columns ("units").  With LR rows per block and LQ = 64 / LR lanes per row:
 //   row of block i:   i * LR + lane % LR
 //   unit u of a row:  columns u * 4 * LQ + 4 * (lane / LR) .. + 3
-// Acc32: v_mfma_f32_32x32x16_bf16 (LR 32, 2 lanes per row, 8 units per 32x32 block pair);
+// Acc32: v_mfma_f32_32x32x64_f8f6f4 and the 32x32 bf16 shapes (LR 32, 2 lanes per row, 4 units per 32x32 block);
 // Acc16: v_mfma_f32_16x16x32_bf16 (LR 16, 4 lanes per row, one unit per 16x16 block).
 // ---------------------------------------------------------------------------------
 template <class C>
@@ -920,70 +839,8 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
     }
 }
 
-template <class C, bool AK, bool BKC, int EPI, bool EDGE>
-__global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmParams p)
-{
-    constexpr int BM = C::BM, BN = C::BN, BK = C::BK, FM = C::FM, FN = C::FN;
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * C::STAGE_BYTES];
-    __shared__ float red[2 * C::WGN * C::BM];   // row-reduction exchange; second half: sum-exp of the log-sum-exp partials
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave % C::WGM, wn = wave / C::WGM;
-    int tm, tn;
-    tile_coords(blockIdx.x, gridDim.x, p.tiles_m, p.tiles_n, tm, tn);
-    const int m0 = tm * BM, n0 = tn * BN;
-
-    using ACC = Acc32<C>;
-    ACC acc;
-    acc_zero(acc);
-
-    const int KT = (p.K + BK - 1) / BK;
-    u32x4 ra[C::CHA], rb[C::CHB];
-
-    if (KT > 0) {
-        tile_gload<C, BM, C::CHA, AK, EDGE>(ra, p.A, p.lda, m0, 0, p.M, p.K, tid);
-        tile_gload<C, BN, C::CHB, BKC, EDGE>(rb, p.B, p.ldb, n0, 0, p.N, p.K, tid);
-        tile_lstore<C, BM, C::CHA, AK>(ra, smem, tid);
-        tile_lstore<C, BN, C::CHB, BKC>(rb, smem + C::A_BYTES, tid);
-    }
-    __syncthreads();
-
-    for (int kt = 0; kt < KT; ++kt) {
-        const unsigned char *sa = smem + (kt & 1) * C::STAGE_BYTES;
-        const unsigned char *sb = sa + C::A_BYTES;
-        const bool more = kt + 1 < KT;
-        if (more) {
-            tile_gload<C, BM, C::CHA, AK, EDGE>(ra, p.A, p.lda, m0, (kt + 1) * BK, p.M, p.K, tid);
-            tile_gload<C, BN, C::CHB, BKC, EDGE>(rb, p.B, p.ldb, n0, (kt + 1) * BK, p.N, p.K, tid);
-        }
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 fa[FM], fb[FN];
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-                fa[i] = frag_load<C, BM, AK>(sa, wm * C::WTM + i * 32, ks, lane);
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-                fb[j] = frag_load<C, BN, BKC>(sb, wn * C::WTN + j * 32, ks, lane);
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-                    acc.a[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc.a[i][j], 0, 0, 0);
-        }
-        if (more) {
-            unsigned char *da = smem + ((kt + 1) & 1) * C::STAGE_BYTES;
-            tile_lstore<C, BM, C::CHA, AK>(ra, da, tid);
-            tile_lstore<C, BN, C::CHB, BKC>(rb, da + C::A_BYTES, tid);
-        }
-        __syncthreads();
-    }
-
-    run_epilogue<C, ACC, EPI, EDGE, 2 * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
-}
-
 // ---------------------------------------------------------------------------------
-// Fast path (no edge tiles): multi-stage LDS ring filled by direct-to-LDS global loads.
+// Mainloops: multi-stage LDS ring filled by direct-to-LDS global loads.
 //
 // global_load_lds_dwordx4 moves 16 bytes per lane from global memory straight into LDS
 // (lane L of the issuing wave lands at M0-base + 16*L), so operand tiles never pass
@@ -991,17 +848,9 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmParams p)
 // by the lane, so the XOR swizzle is applied on the global side: lane L fetches the
 // chunk whose swizzled home is position L.  Per-lane global offsets are loop-invariant
 // (32-bit, in VGPRs); only the 64-bit scalar base advances along K.
-//
-// Pipeline per K-step kt of BK = 32 (two 16-wide MFMA slices), STAGES-deep ring:
-//   A  issue loads of tile kt+STAGES-1 into the slot freed by tile kt-1
-//   B  read slice-1 fragments of tile kt; 16 MFMAs on slice 0 (fragments already in VGPRs)
-//   C  wait until this wave's loads of tile kt+1 have landed; workgroup barrier
-//   D  read slice-0 fragments of tile kt+1; 16 MFMAs on slice 1
-// The barrier sits between two MFMA blocks whose operands are already in registers, so
-// LDS latency is never exposed; it orders (i) every wave's reads of tile kt before the
-// slot is refilled in step A of kt+1 and (ii) all loads of tile kt+1 before step D.
 // The loads are issued from inline asm, invisible to the compiler's waitcnt insertion;
-// vmcnt is waited on explicitly (loads retire in order).
+// vmcnt is waited on explicitly (loads retire in order).  The K-step pipelines are
+// described at the kernels.
 // ---------------------------------------------------------------------------------
 template <int BM_, int BN_, int WGM_, int WGN_, int STAGES_, int WPE_ = 2>
 struct DlCfg : TileCfg<BM_, BN_, 32, WGM_, WGN_> {
@@ -1040,6 +889,19 @@ __device__ __forceinline__ uint32_t dl_goffset(int j, int lane, int64_t ld, int 
         const int col = (g * 2 + (pc & 1)) * 8;
         const int cg = col < valid ? col : valid - 8;
         return (uint32_t)(((int64_t)k * ld + cg) * 2);
+    }
+}
+
+// First contraction index, within the 32-wide operand tile, of the 8-element chunk (K-contiguous) or of the k-row
+// (MN-contiguous) that lane `lane` of wave-load `j` fetches.
+template <int ROWS, bool KCONT>
+__device__ __forceinline__ int dl_chunk_k(int j, int lane)
+{
+    if (KCONT) {
+        const int r = j * 16 + (lane >> 2);
+        return ((lane & 3) ^ kc16_swz(r)) * 8;
+    } else {
+        return (j * 64 + lane) / (ROWS / 8);
     }
 }
 
@@ -1149,8 +1011,9 @@ __device__ __forceinline__ bf16x8 dl_frag16(const unsigned char *tile, int row_b
 // loads of tile kt+1 before step D.  The loads are issued from inline asm, invisible to the compiler's waitcnt
 // insertion; vmcnt is waited on explicitly (loads retire in order).  K-steps are walked in pairs so that the two
 // column-fragment buffers swap roles without copies: the host guarantees an even, positive count per workgroup.
-// RAGGED: M and / or N are not whole numbers of tiles (K is): edge tiles clamp their operand fetches and run the
-// bounds-checked epilogue.
+// RAGGED: M, N or K is not a whole number of tiles.  Tiles on the edge of M or N clamp their operand fetches and run the
+// bounds-checked epilogue; K is rounded up to whole pairs of K-steps and the tile fill stores zeros at the positions
+// past K.
 template <class C, bool AK, bool BKC, int EPI, bool RAGGED>
 __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE))) void gemm_kernel_dl(const GemmParams p)
 {
@@ -1174,8 +1037,9 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     ACC acc;
     acc_zero(acc);
 
-    // this workgroup's part of the contraction: K-steps [kbeg, kbeg + KT)
-    const int KT_all = p.K / BK;
+    // this workgroup's part of the contraction: K-steps [kbeg, kbeg + KT); a ragged K is rounded up to whole pairs of
+    // K-steps, the positions past K are zero-filled by the tile fill
+    const int KT_all = RAGGED ? ((p.K + 2 * BK - 1) / (2 * BK)) * 2 : p.K / BK;
     const int kbeg = (int)((int64_t)KT_all * split / nsplit);
     const int KT = (int)((int64_t)KT_all * (split + 1) / nsplit) - kbeg;
 
@@ -1198,6 +1062,24 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
         const uint32_t slot = lds0 + (uint32_t)(t % S) * C::STAGE_BYTES;
         const unsigned char *sa = ga + (int64_t)t * stepa;
         const unsigned char *sb = gb + (int64_t)t * stepb;
+        if (RAGGED && (kbeg + t + 1) * BK > p.K) {
+            // the tile reaches past K: a lane whose chunk lies past K stores zeros at its LDS position instead of fetching
+            const int k_left = p.K - (kbeg + t) * BK;              // contraction elements of this tile that exist (may be <= 0)
+            unsigned char *ls = smem + (t % S) * C::STAGE_BYTES;
+#pragma unroll
+            for (int i = 0; i < LA; ++i) {
+                const int wl = wave * LA + i;
+                if (dl_chunk_k<BM, AK>(wl, lane) < k_left) dl_load16(offa[i], sa, slot + (uint32_t)wl * 1024u);
+                else *reinterpret_cast<u32x4 *>(ls + wl * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int i = 0; i < LB; ++i) {
+                const int wl = wave * LB + i;
+                if (dl_chunk_k<BN, BKC>(wl, lane) < k_left) dl_load16(offb[i], sb, slot + C::A_BYTES + (uint32_t)wl * 1024u);
+                else *reinterpret_cast<u32x4 *>(ls + C::A_BYTES + wl * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < LA; ++i) dl_load16(offa[i], sa, slot + (uint32_t)(wave * LA + i) * 1024u);
 #pragma unroll
@@ -1228,7 +1110,9 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
         read_a(fah, kt, 1);                                              // B
         mma(fal, fbc, 0);
         if (!last) {
-            if (refill) {                                                // C
+            // C: tile kt+1 must have landed, tiles kt+2 and kt+3 may be in flight.  The count is exact only when both issued
+            // all their loads: a tile that reaches past K issues fewer (zero-filled positions), then everything is waited for
+            if (refill && (!RAGGED || (kbeg + kt + S) * BK <= p.K)) {
                 asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
             } else {
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -1245,7 +1129,7 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 #pragma unroll
         for (int t = 0; t < S - 1; ++t)
             if (t < KT) issue(t);
-        if (KT >= S - 1) {
+        if (KT >= S - 1 && (!RAGGED || (kbeg + S - 1) * BK <= p.K)) {
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
         } else {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -1415,7 +1299,7 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 }
 
 // Host-side launcher, one per (operand layouts, epilogue mode, kernel kind).
-enum KernelKind : int { KIND_WHOLE = 0, KIND_RAGGED_MN = 1, KIND_EDGE = 2 };
+enum KernelKind : int { KIND_WHOLE = 0, KIND_RAGGED = 1 };
 template <bool AK, bool BKC, int EPI, int KIND>
 hipError_t launch_gemm(const GemmParams &p, hipStream_t stream);
 

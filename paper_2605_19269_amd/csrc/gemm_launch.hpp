@@ -1,4 +1,4 @@
-// gemm_launch.hpp -- host launchers for gemm_kernel, instantiated per layout pair.
+// gemm_launch.hpp -- host launchers of the GEMM+epilogue kernels, instantiated per layout pair.
 #pragma once
 #include "gemm_kernel.hpp"
 
@@ -6,9 +6,9 @@
 
 namespace coda {
 
-using MainCfg = TileCfg<256, 256, 64, 2, 4>;   // register-staged kernel (edge tiles)
-using FastCfg = DlCfg<256, 256, 2, 4, 4>;       // direct-to-LDS ring (whole tiles only); 128x64 wave tiles
-static_assert(MainCfg::BM % FastCfg::BM == 0 && MainCfg::BN == FastCfg::BN, "tile grids");
+using FastCfg = DlCfg<256, 256, 2, 4, 4>;       // direct-to-LDS ring of four K-steps of 32; 128x64 wave tiles
+constexpr int TILE_M = FastCfg::BM, TILE_N = FastCfg::BN;
+constexpr int TILE_K = 64;                      // the kernels walk K-steps of 32 in pairs
 
 // Workgroups of a fast-kernel launch: whole tiles below split_from, `splitk` workgroups per tile from there on.
 inline unsigned fast_grid(const GemmParams &p)
@@ -18,22 +18,18 @@ inline unsigned fast_grid(const GemmParams &p)
     return (unsigned)p.split_from + (tiles - (unsigned)p.split_from) * (unsigned)p.splitk;
 }
 
-// `p` arrives without tile counts; they depend on the kernel chosen here.
-//   KIND_WHOLE:     M, N, K are whole multiples of MainCfg's tile (and therefore of the fast tile);
-//   KIND_RAGGED_MN: K is, M and / or N are not: fast kernel with clamped operand fetches and bounds-checked epilogue;
-//   KIND_EDGE:      anything else: register-staged kernel, predicated everywhere.
+// `p` arrives without tile counts.
+//   KIND_WHOLE:  M, N, K are whole multiples of TILE_M, TILE_N, TILE_K;
+//   KIND_RAGGED: anything else (K, N multiples of 8): clamped operand fetches on the edges of M and N, zero-filled K
+//                tail, bounds-checked epilogue.
 template <bool AK, bool BKC, int EPI, int KIND>
 hipError_t launch_gemm(const GemmParams &p_in, hipStream_t stream)
 {
+    using C = FastCfg;
     GemmParams p = p_in;
-    using C = std::conditional_t<KIND == KIND_EDGE, MainCfg, FastCfg>;
     p.tiles_m = (p.M + C::BM - 1) / C::BM;
     p.tiles_n = (p.N + C::BN - 1) / C::BN;
-    if constexpr (KIND == KIND_EDGE) {
-        hipLaunchKernelGGL((gemm_kernel<C, AK, BKC, EPI, true>), dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(C::NT), 0, stream, p);
-    } else {
-        hipLaunchKernelGGL((gemm_kernel_dl<C, AK, BKC, EPI, KIND == KIND_RAGGED_MN>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
-    }
+    hipLaunchKernelGGL((gemm_kernel_dl<C, AK, BKC, EPI, KIND == KIND_RAGGED>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -50,9 +46,8 @@ hipError_t launch_gemm_f8(const GemmParams &p_in, hipStream_t stream)
 }
 
 #define CODA_INSTANTIATE_ONE(AK, BKC, EPI)                                                   \
-    template hipError_t launch_gemm<AK, BKC, EPI, KIND_WHOLE>(const GemmParams &, hipStream_t);      \
-    template hipError_t launch_gemm<AK, BKC, EPI, KIND_RAGGED_MN>(const GemmParams &, hipStream_t);  \
-    template hipError_t launch_gemm<AK, BKC, EPI, KIND_EDGE>(const GemmParams &, hipStream_t);
+    template hipError_t launch_gemm<AK, BKC, EPI, KIND_WHOLE>(const GemmParams &, hipStream_t);   \
+    template hipError_t launch_gemm<AK, BKC, EPI, KIND_RAGGED>(const GemmParams &, hipStream_t);
 
 #define CODA_INSTANTIATE_LAYOUT(AK, BKC)            \
     CODA_INSTANTIATE_ONE(AK, BKC, EPI_LINEAR)       \
@@ -65,9 +60,8 @@ hipError_t launch_gemm_f8(const GemmParams &p_in, hipStream_t stream)
 // unless CODA_GEMM_INSTANTIATION_UNIT is defined, every launcher is declared as instantiated elsewhere.
 #ifndef CODA_GEMM_INSTANTIATION_UNIT
 #define CODA_EXTERN_ONE(AK, BKC, EPI)                                                               \
-    extern template hipError_t launch_gemm<AK, BKC, EPI, KIND_WHOLE>(const GemmParams &, hipStream_t);      \
-    extern template hipError_t launch_gemm<AK, BKC, EPI, KIND_RAGGED_MN>(const GemmParams &, hipStream_t);  \
-    extern template hipError_t launch_gemm<AK, BKC, EPI, KIND_EDGE>(const GemmParams &, hipStream_t);
+    extern template hipError_t launch_gemm<AK, BKC, EPI, KIND_WHOLE>(const GemmParams &, hipStream_t);   \
+    extern template hipError_t launch_gemm<AK, BKC, EPI, KIND_RAGGED>(const GemmParams &, hipStream_t);
 #define CODA_EXTERN_LAYOUT(AK, BKC)            \
     CODA_EXTERN_ONE(AK, BKC, EPI_LINEAR)       \
     CODA_EXTERN_ONE(AK, BKC, EPI_SWIGLU_FWD)   \

@@ -152,7 +152,8 @@ def test_splitk_workspace_planning_and_errors(coda):
     assert wb(2048, 2048, 8192) == 1024 + 64 * 4 * tile     # 64 tiles: 4 parts fill the 256 compute units
     assert wb(2048, 2048 + 256, 8192) == 0                  # 72 tiles: more than a quarter of the chip already busy
     assert wb(512, 512, 1024) == 0                          # contraction too short to split
-    assert wb(512, 512, 4096 + 32) == 0                     # not whole K-steps: edge kernel, never split
+    assert wb(512, 512, 4096 + 32) == 0                     # 130 K-steps (ragged K rounds up to pairs): no even split
+    assert wb(512, 512, 4096 + 72) == 1024 + 4 * 3 * tile   # 132 K-steps: 3 parts of 44
     assert wb(504, 264, 4096) == 1024 + 4 * 4 * tile        # ragged M and N: 2 x 2 tiles, shared like whole ones
     assert wb(256, 256, 6 * 1024 + 128) == 1024 + 1 * 2 * tile  # 196 K-steps of 32: only 2 parts get an even number each
     assert wb(256, 256, 6 * 1024 + 64) == 0                     # 194 K-steps: no part count gives every part an even number

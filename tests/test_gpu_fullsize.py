@@ -1,5 +1,5 @@
 """Full-size parity: the benchmark workloads at their real shapes, launched exactly as bench.py launches
-them (same programs, same layouts, whole-tile fast kernel), checked on a deterministic sample of output rows
+them (same programs, same layouts, whole-tile kernel instantiation), checked on a deterministic sample of output rows
 that the oracle computes one by one.  Every epilogue on the path is row-local, so sampled rows are exact; the
 weight gradient is sampled over its own output rows."""
 import numpy as np

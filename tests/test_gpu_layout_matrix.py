@@ -1,7 +1,7 @@
 """GPU parity, layout x epilogue matrix: every epilogue mode of coda_gemm is instantiated once per operand
-layout (A or A^T, B or B^T).  Each (layout, mode) pair is run on a shape that takes the fast kernel
-(whole 256 x 256 x 64 tiles), on a shape ragged in every dimension that takes the edge kernel, and on a shape ragged
-in M and N only that takes the fast kernel with clamped operand fetches, against the CPU oracle."""
+layout (A or A^T, B or B^T).  Each (layout, mode) pair is run on a shape of whole 256 x 256 x 64 tiles, on a shape
+ragged in every dimension (clamped fetches, zero-filled K tail, bounds-checked epilogue) and on a shape ragged
+in M and N only, against the CPU oracle."""
 import numpy as np
 import pytest
 import torch

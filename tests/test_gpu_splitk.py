@@ -40,8 +40,8 @@ def operands(g, M, N, K, transA, transB, a_std=1.0, b_std=0.05):
 
 # (M, N, K) -> parts: 4 tiles, K = 4096 -> 4;  1 tile, K = 8192 -> 8;  2 tiles, K = 2048 -> 2;
 # 1 tile, K = 6272 (196 K-steps of 32) -> 2, the only count that gives every part an even number of steps;
-# 2 x 2 tiles with a ragged edge in M and N, K = 4096 -> 4
-SHAPES = [(512, 512, 4096), (256, 256, 8192), (256, 512, 2048), (256, 256, 6272), (504, 264, 4096)]
+# 2 x 2 tiles with a ragged edge in M and N, K = 4096 -> 4; the same with a ragged K = 4168 (132 K-steps) -> 3
+SHAPES = [(512, 512, 4096), (256, 256, 8192), (256, 512, 2048), (256, 256, 6272), (504, 264, 4096), (504, 264, 4168)]
 
 
 @pytest.mark.parametrize("transA,transB", [(False, False), (False, True), (True, False)])
@@ -149,7 +149,7 @@ def test_splitk_workspace_rules(oracle):
     dA, dB = G.dev_bf16(A), G.dev_bf16(B)
     need = coda.coda_gemm_workspace_bytes(M, N, K, [])
     assert need == 1024 + 4 * 4 * 256 * 256 * 4          # counters + tiles x parts x one fp32 tile
-    # shapes that are not split ask for nothing: many tiles, short K, K not a whole number of K-steps
+    # shapes that are not split ask for nothing: many tiles, short K, a K-step count that no part count divides evenly
     assert coda.coda_gemm_workspace_bytes(8192, 8192, 8192, []) == 0
     assert coda.coda_gemm_workspace_bytes(512, 512, 1024, []) == 0
     assert coda.coda_gemm_workspace_bytes(512, 512, 4096 + 8, []) == 0
