@@ -35,7 +35,7 @@ coda_status coda_calib_mfma_loop(void *stream, const void *a_frags, const void *
                                  int64_t iters, float *out);
 
 /*
- * The same measurement on v_mfma_f32_16x16x32_bf16, the instruction of the bf16 fast kernel (it draws less
+ * The same measurement on v_mfma_f32_16x16x32_bf16, the instruction of the bf16 GEMM kernel (it draws less
  * power per FLOP than 32x32x16, so its ceiling on non-trivial operands is higher).  Same fragment inputs and
  * launch shape; each iteration runs 32 MFMAs (each of the 4 x 2 accumulator tiles four times), the same
  * FLOP count per iteration as coda_calib_mfma_loop: n_blocks * 8 * 16 * 32768 * iters FLOP in total.

@@ -57,7 +57,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
 }
 
-// The same loop on v_mfma_f32_16x16x32_bf16, the instruction of the bf16 fast kernel: 32 MFMAs per iteration
+// The same loop on v_mfma_f32_16x16x32_bf16, the instruction of the bf16 GEMM kernel: 32 MFMAs per iteration
 // (each of the 4 x 2 accumulator tiles four times), the same FLOP count per iteration as above.
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 

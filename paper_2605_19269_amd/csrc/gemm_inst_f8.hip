@@ -1,4 +1,4 @@
-// Instantiations of the 8-bit-operand fast kernel (A [M x K], B [N x K], OCP E4M3), one per epilogue mode.
+// Instantiations of the 8-bit-operand kernel (A [M x K], B [N x K], OCP E4M3), one per epilogue mode.
 #define CODA_GEMM_INSTANTIATION_UNIT
 #include "gemm_launch.hpp"
 

@@ -69,7 +69,7 @@ struct GemmParams {
     // target column y[M] and the selected logit z_tgt[M]
     float *lse_max, *lse_sum, *lse_tgt;
     const int *lse_y;
-    // split-K (fast kernels only; splitk <= 1 = off): tiles with id >= split_from are shared by `splitk` workgroups
+    // split-K (splitk <= 1 = off): tiles with id >= split_from are shared by `splitk` workgroups
     // each, every one contracting a contiguous part of K (split_from = 0: all tiles; split_from = a whole number of
     // 256-workgroup rounds: only the tiles of the last, partly filled round).  With t = tile - split_from, a workgroup
     // leaves its fp32 partial tile in ws_part[t * splitk + split] and takes a
@@ -930,7 +930,7 @@ __device__ __forceinline__ void locate_workgroup(const GemmParams &p, int bid, i
 }
 
 // ---------------------------------------------------------------------------------
-// Split-K exchange (fast kernels).  Every workgroup of a tile leaves its fp32 partial in the workspace and takes a
+// Split-K exchange.  Every workgroup of a tile leaves its fp32 partial in the workspace and takes a
 // ticket; all but the last one to arrive return false (and must exit); the last one gets the sum of all partials,
 // added in split order so that it does not depend on who arrived last, and returns true.
 // ---------------------------------------------------------------------------------
@@ -999,7 +999,7 @@ __device__ __forceinline__ bf16x8 dl_frag16(const unsigned char *tile, int row_b
     }
 }
 
-// bf16 fast kernel.  One K-step of 32 is ONE v_mfma_f32_16x16x32_bf16 per 16x16 block (this shape draws less power per
+// bf16 kernel.  One K-step of 32 is ONE v_mfma_f32_16x16x32_bf16 per 16x16 block (this shape draws less power per
 // FLOP than 32x32x16 and sustains a higher clock on non-trivial operands); the wave's 128 x 64 tile is 8 x 4 blocks.
 // Per K-step the work is split in two halves of the wave's rows, so that the fragment reads of one half run under the
 // MFMAs of the other, with the workgroup barrier between them:
