@@ -331,6 +331,20 @@ def main():
             del xs, ws_, rs_, ys, wsp
         out["extra_kernels"]["split_k_residual_sumsq"] = spk
 
+        # ragged shapes (plain bf16 store): clamped fetches on the M / N edge, zero-filled K tail, same mainloop;
+        # the vendor GEMM (torch.matmul) beside each as outside context
+        rag = {}
+        for (Mr, Nr, Kr) in ((8200, 8192, 8192), (8192, 8192, 8200), (8100, 16384, 2048), (4000, 4000, 4000)):
+            xr, wr = rnd((Mr, Kr)), rnd((Kr, Nr), 0.02)
+            yr = torch.empty((Mr, Nr), **b16)
+            ms_r = min(time_kernel(lambda: coda.coda_gemm(xr, wr, [coda.store(yr)]), reps=10, warm=3) for _ in range(2))
+            ms_v = min(time_kernel(lambda: torch.matmul(xr, wr, out=yr), reps=10, warm=3) for _ in range(2))
+            flr = 2.0 * Mr * Nr * Kr
+            rag["%dx%dx%d" % (Mr, Nr, Kr)] = {"ms": round(ms_r, 4), "tflops": round(flr / ms_r * 1e-9, 1),
+                                               "vendor_gemm_ms": round(ms_v, 4), "vendor_gemm_tflops": round(flr / ms_v * 1e-9, 1)}
+            del xr, wr, yr
+        out["extra_kernels"]["ragged_shapes_plain_store"] = rag
+
         # outside context, not a path of this library: the vendor GEMM (torch.matmul -> hipBLASLt) on the shapes of the step,
         # plain bf16 output, no epilogue work
         ctx = {}
