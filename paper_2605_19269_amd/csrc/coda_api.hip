@@ -299,7 +299,8 @@ extern "C" {
 coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_mat *A, const coda_mat *B,
                       const coda_epi_op *prog, int32_t n_ops, void *workspace, size_t workspace_bytes)
 {
-    if (M < 0 || N < 0 || K < 0 || M > INT32_MAX || N > INT32_MAX / 2 || K > INT32_MAX) return CODA_ERR_SHAPE;
+    // the kernels index in 32 bits; K is rounded up to whole pairs of K-steps (64 elements) there
+    if (M < 0 || N < 0 || K < 0 || M > INT32_MAX - 256 || N > INT32_MAX / 2 || K > INT32_MAX - 64) return CODA_ERR_SHAPE;
     coda_status st;
     if ((st = check_operand(A, M, K)) != CODA_OK) return st;
     if ((st = check_operand(B, K, N)) != CODA_OK) return st;
@@ -362,7 +363,7 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
 
 size_t coda_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, const coda_epi_op *, int32_t)
 {
-    if (M < 0 || N < 0 || K < 0 || M > INT32_MAX || N > INT32_MAX / 2 || K > INT32_MAX) return 0;
+    if (M < 0 || N < 0 || K < 0 || M > INT32_MAX - 256 || N > INT32_MAX / 2 || K > INT32_MAX - 64) return 0;
     return splitk_bytes(plan_splitk(M, N, K));
 }
 
