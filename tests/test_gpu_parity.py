@@ -52,6 +52,49 @@ def test_plain_gemm_store_bf16(oracle, M, N, K, transA, transB):
     G.assert_bf16_close(G.host_f64(out.t), ref, "plain gemm")
 
 
+def _random_ragged_cases(n, seed):
+    """Seeded shapes around the tile boundaries: M any (a multiple of 8 when A is stored transposed), N and K multiples
+    of 8; K below, at and just past multiples of the 32 / 64-element K-steps; one layout and one pitch padding each."""
+    g = np.random.Generator(np.random.PCG64(seed))
+    cases = []
+    for i in range(n):
+        transA, transB = bool(g.integers(2)), bool(g.integers(2))
+        M = int(g.choice([1, 7, 8, 255, 256, 257, 300, 511, 520]))
+        if transA:
+            M = max(8, M // 8 * 8)
+        N = int(g.choice([8, 24, 248, 256, 264, 504, 520]))
+        K = int(g.choice([8, 24, 32, 40, 56, 64, 72, 120, 128, 136, 184, 192, 200, 320, 328]))
+        cases.append((M, N, K, transA, transB, int(g.choice([0, 8, 24]))))
+    return cases
+
+
+@pytest.mark.parametrize("M,N,K,transA,transB,pad", _random_ragged_cases(28, seed=2024))
+def test_ragged_shapes_residual_sumsq(oracle, M, N, K, transA, transB, pad):
+    """Ragged M / N / K through the one mainloop (clamped edge fetches, zero-filled K tail), padded operand pitches,
+    guarded outputs: row scale + residual + row sum of squares against the oracle."""
+    g = rng(4000 + 7 * M + 3 * N + K + 2 * transA + transB)
+    a_shape, b_shape = ((K, M) if transA else (M, K)), ((N, K) if transB else (K, N))
+    Ap = synth.normal_bf16(g, (a_shape[0], a_shape[1] + pad), 1.0)
+    Bp = synth.normal_bf16(g, (b_shape[0], b_shape[1] + pad), 0.3)
+    A, B = np.ascontiguousarray(Ap[:, :a_shape[1]]), np.ascontiguousarray(Bp[:, :b_shape[1]])
+    dA, dB = G.dev_bf16(Ap)[:, :a_shape[1]], G.dev_bf16(Bp)[:, :b_shape[1]]      # pitch > width
+    C = synth.normal_bf16(g, (M, N), 1.0)
+    r = synth.uniform_f32(g, (M,), 0.5, 1.5)
+    Y = G.Guarded(M, N, torch.bfloat16)
+    nblk = coda.coda_row_partial_blocks(N)
+    part = torch.full((nblk, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    dr, dC = G.dev_f32(r), G.dev_bf16(C)
+    coda.coda_gemm(dA, dB, [coda.row_scale(dr), coda.add_tile(dC), coda.row_sumsq(part), coda.store(Y.t)],
+                   transA=transA, transB=transB)
+    ss = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_row_finalize(part, M, nblk, sum_out=ss, d=N, eps=0.0)
+    torch.cuda.synchronize()
+    refD, refss = oracle.gemm_residual_sumsq(A, B, r=r.astype(np.float64), C=C, transA=transA, transB=transB)[:2]
+    Y.check_guards(); Y.written()
+    G.assert_bf16_close(G.host_f64(Y.t), refD, "ragged row scale + residual")
+    G.assert_sumsq_close(G.host_f64(ss), refss, "ragged row sum of squares")
+
+
 @pytest.mark.parametrize("transA,transB", [(False, False), (True, False)])
 def test_plain_gemm_store_f32(oracle, transA, transB):
     M, N, K = 520, 264, 136
