@@ -132,11 +132,13 @@ def mat(t, trans=False):
 
 
 def _op(kind, flags=0, in_=None, out=None, out2=None, in2=None, in3=None, in4=None, out3=None, i0=0, i1=0):
-    return coda_epi_op(kind, flags, _ptr(in_), _ptr(out), _ptr(out2), _ld(in_), _ld(out), _ptr(in2), _ptr(in3),
-                       _ptr(in4), _ptr(out3), i0, i1)
+    op = coda_epi_op(kind, flags, _ptr(in_), _ptr(out), _ptr(out2), _ld(in_), _ld(out), _ptr(in2), _ptr(in3),
+                     _ptr(in4), _ptr(out3), i0, i1)
+    op._keep = (in_, out, out2, in2, in3, in4, out3)     # the op owns a reference, so a temporary passed inline survives
+    return op
 
 
-# --- epilogue op constructors (keep the tensors alive until the call returns) ----------------
+# --- epilogue op constructors (each op holds its tensors for as long as the op object lives) ---
 def row_scale(r):
     return _op(CODA_EPI_ROW_SCALE, in_=r)
 
@@ -157,7 +159,9 @@ def rmsnorm_bwd(C, r, z, gamma, c_out=None, dgamma_out=None, atomic=False):
 
 def lse_partial(y, pmax, psum, ztgt):
     """y: int32 [M] targets; pmax, psum: f32 [nblk x M]; ztgt: f32 [M]."""
-    return coda_epi_op(CODA_EPI_LSE_PARTIAL, 0, None, _ptr(pmax), _ptr(psum), 0, 0, None, _ptr(y), None, _ptr(ztgt), 0, 0)
+    op = coda_epi_op(CODA_EPI_LSE_PARTIAL, 0, None, _ptr(pmax), _ptr(psum), 0, 0, None, _ptr(y), None, _ptr(ztgt), 0, 0)
+    op._keep = (y, pmax, psum, ztgt)
+    return op
 
 
 def add_tile(C):

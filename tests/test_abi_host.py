@@ -170,3 +170,17 @@ def test_splitk_workspace_planning_and_errors(coda):
     need = wb(512, 512, 4096)
     assert coda.coda_gemm_raw(None, 512, 512, 4096, A, B, [store], P, need - 1) == coda.CODA_ERR_WORKSPACE
     assert coda.coda_gemm_raw(None, 512, 512, 4096, A, B, [store], P + 4, need) == coda.CODA_ERR_ALIGN
+
+
+def test_epilogue_op_keeps_its_tensors_alive():
+    """An op built from a temporary tensor must keep that tensor's memory from being recycled before the launch."""
+    import weakref
+    import torch
+    from paper_2605_19269_amd import coda
+    t = torch.zeros(8)
+    ref = weakref.ref(t)
+    op = coda.row_scale(t)
+    del t
+    assert ref() is not None and op.in_ == ref().data_ptr()
+    del op
+    assert ref() is None

@@ -482,3 +482,66 @@ def test_kernel8_logits_lse_partials(oracle, M, N, K, with_r, transB):
     d = np.abs(G.host_f64(lse) - reflse)
     assert (d <= 1e-3 * np.maximum(np.abs(reflse), 1.0)).all(), "lse max delta %.3g" % d.max()
     G.assert_f32_signed_close(G.host_f64(loss), reflse - refzt, "per-token loss")
+
+
+# Gate pre-activations from deep saturation on both sides (where exp(-g) overflows or underflows fp32) through the
+# linear region around zero: the kernels' sigmoid must go to exactly 0 / 1 there without producing NaN or Inf.
+EXTREME_GATES = np.array([-1e4, -120.0, -100.0, -89.0, -88.0, -87.0, -60.0, -30.0, -17.0, -10.0, -1.0, -1e-3, -1e-30, 0.0,
+                          1e-30, 1e-3, 1.0, 10.0, 17.0, 30.0, 60.0, 87.0, 88.0, 89.0, 100.0, 120.0, 1e4], np.float32)
+
+
+def _extreme_pairs(g, rows, pairs):
+    """[rows x 2*pairs] bf16 bits: even columns (gates) cycle through EXTREME_GATES, shifted per row; odd columns
+    (up-projection values) are standard normal."""
+    Z = G.bits_to_f64(synth.normal_bf16(g, (rows, 2 * pairs), 1.0)).astype(np.float32)
+    idx = (np.arange(rows)[:, None] * 5 + np.arange(pairs)[None, :]) % EXTREME_GATES.size
+    Z[:, 0::2] = EXTREME_GATES[idx]
+    return synth.f32_to_bf16_bits(Z)
+
+
+def test_swiglu_forward_saturated_gates(oracle):
+    M, N, K = 256, 512, 64
+    g = rng(31)
+    A = np.zeros((M, K), np.float32)
+    A[np.arange(M), np.arange(M) % K] = 1.0             # one-hot rows: row i of A*B is row i % K of B, exactly
+    A = synth.f32_to_bf16_bits(A)
+    B = _extreme_pairs(g, K, N // 2)
+    H = G.Guarded(M, N // 2, torch.bfloat16)
+    Z = G.Guarded(M, N, torch.bfloat16)
+    coda.coda_gemm(G.dev_bf16(A), G.dev_bf16(B), [coda.swiglu_fwd(Z.t), coda.store(H.t)])
+    torch.cuda.synchronize()
+    refH, refZ = oracle.gemm_rowscale_swiglu(A, B, want_preact=True)
+    H.check_guards(); H.written(); Z.check_guards(); Z.written()
+    got = G.host_f64(H.t)
+    assert np.isfinite(got).all()
+    assert (G.host_bits(Z.t) == B[np.arange(M) % K]).all(), "pre-activation must be the selected rows of B, bit for bit"
+    G.assert_bf16_close(got, refH, "swiglu fwd, saturated gates")
+    gates = G.bits_to_f64(B[np.arange(M) % K])[:, 0::2]
+    assert (got[gates <= -100.0] == 0.0).all(), "deeply negative gates must give exactly zero"
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (264, 200, 72)])
+def test_swiglu_backward_saturated_gates(oracle, M, N, K):
+    g = rng(32)
+    A = synth.normal_bf16(g, (M, K), 0.125)
+    Bt = synth.normal_bf16(g, (N, K), 1.0)
+    Z = _extreme_pairs(g, M, N)
+    dZ = G.Guarded(M, 2 * N, torch.bfloat16)
+    O = G.Guarded(M, N, torch.bfloat16)
+    nblk = coda.coda_row_partial_blocks(N)
+    part = torch.full((nblk, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    ops = [coda.swiglu_bwd(G.dev_bf16(Z), act_out=O.t, stat_out=part), coda.store(dZ.t)]
+    coda.coda_gemm(G.dev_bf16(A), G.dev_bf16(Bt), ops, transB=True)
+    stat = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_row_finalize(part, M, nblk, sum_out=stat, d=1, eps=0.0)
+    torch.cuda.synchronize()
+    refdZ, refO, refstat = oracle.gemm_swiglu_bwd(A, Bt, Z, transB=True)
+    dZ.check_guards(); dZ.written(); O.check_guards(); O.written()
+    got, gotO = G.host_f64(dZ.t), G.host_f64(O.t)
+    assert np.isfinite(got).all() and np.isfinite(gotO).all() and np.isfinite(G.host_f64(stat)).all()
+    # elementwise against |ref| alone: the 1e4 gates would otherwise inflate an rms-based allowance
+    d = np.abs(got - refdZ)
+    assert (d <= 1e-2 + 1e-2 * np.abs(refdZ)).all(), "dZ: max delta %.3g" % d.max()
+    d = np.abs(gotO - refO)
+    assert (d <= 1e-2 + 1e-2 * np.abs(refO)).all(), "activation: max delta %.3g" % d.max()
+    G.assert_f32_signed_close(G.host_f64(stat), refstat, "row statistic")
