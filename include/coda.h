@@ -175,9 +175,10 @@ typedef struct coda_epi_op {
  * 8-bit operands: A and B may both be CODA_F8E4M3 (ld in elements = bytes, a multiple of 16).  The contraction
  * runs on the fp8 matrix cores with fp32 accumulation of the exact products, and every epilogue program
  * above applies unchanged (outputs stay bf16 / fp32; quantisation scales of the operands are the caller's
- * and fold into ROW_SCALE).  This variant exists for whole tiles only: both operands stored with the contraction
- * index contiguous (A [M x K] with trans = 0, B [N x K] with trans = 1), M and N multiples of 256, K a
- * multiple of 128; anything else is CODA_ERR_DTYPE (layout, mixed dtypes) or CODA_ERR_SHAPE (sizes).
+ * and fold into ROW_SCALE).  This variant exists for one layout: both operands stored with the contraction
+ * index contiguous (A [M x K] with trans = 0, B [N x K] with trans = 1); K must be a multiple of 16 and N a
+ * multiple of 8, M is free (edge tiles are predicated as for bf16).  Anything else is CODA_ERR_DTYPE (layout,
+ * mixed dtypes) or CODA_ERR_SHAPE (sizes).
  *
  * workspace / workspace_bytes (device memory, 16-byte aligned; may be NULL): scratch for split-K.
  * Shapes with at most 64 output tiles (256 x 256, counted with a ragged edge) and K >= 2048 leave

@@ -292,6 +292,25 @@ hipError_t dispatch_mode(int mode, int kind, const coda::GemmParams &p, hipStrea
     }
 }
 
+template <int EPI>
+hipError_t dispatch_kind_f8(int kind, const coda::GemmParams &p, hipStream_t s)
+{
+    using namespace coda;
+    return kind == KIND_WHOLE ? launch_gemm_f8<EPI, KIND_WHOLE>(p, s) : launch_gemm_f8<EPI, KIND_RAGGED>(p, s);
+}
+
+hipError_t dispatch_mode_f8(int mode, int kind, const coda::GemmParams &p, hipStream_t s)
+{
+    using namespace coda;
+    switch (mode) {
+    case EPI_LINEAR: return dispatch_kind_f8<EPI_LINEAR>(kind, p, s);
+    case EPI_SWIGLU_FWD: return dispatch_kind_f8<EPI_SWIGLU_FWD>(kind, p, s);
+    case EPI_SWIGLU_BWD: return dispatch_kind_f8<EPI_SWIGLU_BWD>(kind, p, s);
+    case EPI_RMSNORM_BWD: return dispatch_kind_f8<EPI_RMSNORM_BWD>(kind, p, s);
+    default: return dispatch_kind_f8<EPI_ACCUM>(kind, p, s);
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -299,14 +318,14 @@ extern "C" {
 coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_mat *A, const coda_mat *B,
                       const coda_epi_op *prog, int32_t n_ops, void *workspace, size_t workspace_bytes)
 {
-    // the kernels index in 32 bits; K is rounded up to whole pairs of K-steps (64 elements) there
-    if (M < 0 || N < 0 || K < 0 || M > INT32_MAX - 256 || N > INT32_MAX / 2 || K > INT32_MAX - 64) return CODA_ERR_SHAPE;
+    // the kernels index in 32 bits; K is rounded up to whole pairs of K-steps (64 bf16 or 128 8-bit elements) there
+    if (M < 0 || N < 0 || K < 0 || M > INT32_MAX - 256 || N > INT32_MAX / 2 || K > INT32_MAX - 128) return CODA_ERR_SHAPE;
     coda_status st;
     if ((st = check_operand(A, M, K)) != CODA_OK) return st;
     if ((st = check_operand(B, K, N)) != CODA_OK) return st;
     const bool f8 = A->dtype == CODA_F8E4M3 || B->dtype == CODA_F8E4M3;
     if (f8 && (A->dtype != B->dtype || A->trans || !B->trans)) return CODA_ERR_DTYPE;   // both 8-bit, both K-contiguous
-    if (f8 && ((M % coda::TILE_M) || (N % coda::TILE_N) || (K % 128))) return CODA_ERR_SHAPE;
+    if (f8 && (K & 15)) return CODA_ERR_SHAPE;                                           // whole 16-byte chunks along K
     if ((K & 7) || (N & 7) || (A->trans && (M & 7))) return CODA_ERR_SHAPE;
     Parsed ps;
     if ((st = parse_program(prog, n_ops, N, ps)) != CODA_OK) return st;
@@ -321,7 +340,8 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
     p.N = (int)N;
     p.K = (int)K;
     if (((M + coda::TILE_M - 1) / coda::TILE_M) * ((N + coda::TILE_N - 1) / coda::TILE_N) * 2 > INT32_MAX) return CODA_ERR_SHAPE;
-    const int kind = ((K % coda::TILE_K) || (M % coda::TILE_M) || (N % coda::TILE_N)) ? coda::KIND_RAGGED : coda::KIND_WHOLE;
+    const int64_t k_pair = f8 ? 2 * coda::TILE_K : coda::TILE_K;   // elements of a pair of K-steps
+    const int kind = ((K % k_pair) || (M % coda::TILE_M) || (N % coda::TILE_N)) ? coda::KIND_RAGGED : coda::KIND_WHOLE;
     const bool ak = !A->trans;   // A stored [M x K]: contraction index contiguous
     const bool bkc = B->trans;   // B stored [N x K]: contraction index contiguous
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -343,13 +363,7 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
     }
     if (f8) {
         using namespace coda;
-        switch (ps.mode) {
-        case EPI_LINEAR: e = launch_gemm_f8<EPI_LINEAR>(p, s); break;
-        case EPI_SWIGLU_FWD: e = launch_gemm_f8<EPI_SWIGLU_FWD>(p, s); break;
-        case EPI_SWIGLU_BWD: e = launch_gemm_f8<EPI_SWIGLU_BWD>(p, s); break;
-        case EPI_RMSNORM_BWD: e = launch_gemm_f8<EPI_RMSNORM_BWD>(p, s); break;
-        default: e = launch_gemm_f8<EPI_ACCUM>(p, s); break;
-        }
+        e = dispatch_mode_f8(ps.mode, kind, p, s);
     } else if (ak && !bkc)
         e = dispatch_mode<true, false>(ps.mode, kind, p, s);
     else if (ak && bkc)

@@ -1173,12 +1173,21 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 // ---------------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 
+// `valid`: rows of the operand tile that exist; positions past it fetch the last existing row again (see dl_goffset).
 template <class C>
-__device__ __forceinline__ uint32_t dl_goffset_f8(int j, int lane, int64_t ld)
+__device__ __forceinline__ uint32_t dl_goffset_f8(int j, int lane, int64_t ld, int valid)
 {
     const int r = j * 16 + (lane >> 2);
     const int c = (lane & 3) ^ ((r >> 2) & 3);
-    return (uint32_t)((int64_t)r * ld + c * 16);
+    const int rg = r < valid ? r : valid - 1;
+    return (uint32_t)((int64_t)rg * ld + c * 16);
+}
+
+// First contraction index, within the 64-wide operand tile, of the 16-byte chunk that lane `lane` of wave-load `j` fetches.
+__device__ __forceinline__ int dl_chunk_k_f8(int j, int lane)
+{
+    const int r = j * 16 + (lane >> 2);
+    return ((lane & 3) ^ ((r >> 2) & 3)) * 16;
 }
 
 __device__ __forceinline__ i32x8 dl_frag_f8(const unsigned char *tile, int row_base, int lane)
@@ -1189,7 +1198,9 @@ __device__ __forceinline__ i32x8 dl_frag_f8(const unsigned char *tile, int row_b
     return i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
 }
 
-template <class C, int EPI>
+// RAGGED as in the bf16 kernel: clamped fetches and the bounds-checked epilogue on the edges of M and N; K (a multiple of
+// 16) is rounded up to whole pairs of K-steps, with zeros stored at the positions past it.
+template <class C, int EPI, bool RAGGED>
 __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE))) void gemm_kernel_dl_f8(const GemmParams p)
 {
     constexpr int BM = C::BM, BN = C::BN, BKB = 64, FM = C::FM, FN = C::FN, S = C::STAGES, HM = FM / 2;
@@ -1212,15 +1223,17 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     acc_zero(acc);
 
     // this workgroup's K-steps [kbeg, kbeg + KT); the host guarantees an even, positive count
-    const int KT_all = p.K / BKB;
+    const int KT_all = RAGGED ? ((p.K + 2 * BKB - 1) / (2 * BKB)) * 2 : p.K / BKB;
     const int kbeg = (int)((int64_t)KT_all * split / nsplit);
     const int KT = (int)((int64_t)KT_all * (split + 1) / nsplit) - kbeg;
 
+    const int valid_m = RAGGED ? (p.M - m0 < BM ? p.M - m0 : BM) : BM;
+    const int valid_n = RAGGED ? (p.N - n0 < BN ? p.N - n0 : BN) : BN;
     uint32_t offa[LA], offb[LB];
 #pragma unroll
-    for (int i = 0; i < LA; ++i) offa[i] = dl_goffset_f8<C>(wave * LA + i, lane, p.lda);
+    for (int i = 0; i < LA; ++i) offa[i] = dl_goffset_f8<C>(wave * LA + i, lane, p.lda, valid_m);
 #pragma unroll
-    for (int i = 0; i < LB; ++i) offb[i] = dl_goffset_f8<C>(wave * LB + i, lane, p.ldb);
+    for (int i = 0; i < LB; ++i) offb[i] = dl_goffset_f8<C>(wave * LB + i, lane, p.ldb, valid_n);
     const unsigned char *ga = reinterpret_cast<const unsigned char *>(p.A) + (int64_t)m0 * p.lda + (int64_t)kbeg * BKB;
     const unsigned char *gb = reinterpret_cast<const unsigned char *>(p.B) + (int64_t)n0 * p.ldb + (int64_t)kbeg * BKB;
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
@@ -1229,6 +1242,24 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
         const uint32_t slot = lds0 + (uint32_t)(t % S) * C::STAGE_BYTES;
         const unsigned char *sa = ga + (int64_t)t * BKB;
         const unsigned char *sb = gb + (int64_t)t * BKB;
+        if (RAGGED && (kbeg + t + 1) * BKB > p.K) {
+            // the tile reaches past K: a lane whose chunk lies past K stores zeros at its LDS position instead of fetching
+            const int k_left = p.K - (kbeg + t) * BKB;
+            unsigned char *ls = smem + (t % S) * C::STAGE_BYTES;
+#pragma unroll
+            for (int i = 0; i < LA; ++i) {
+                const int wl = wave * LA + i;
+                if (dl_chunk_k_f8(wl, lane) < k_left) dl_load16(offa[i], sa, slot + (uint32_t)wl * 1024u);
+                else *reinterpret_cast<u32x4 *>(ls + wl * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int i = 0; i < LB; ++i) {
+                const int wl = wave * LB + i;
+                if (dl_chunk_k_f8(wl, lane) < k_left) dl_load16(offb[i], sb, slot + C::A_BYTES + (uint32_t)wl * 1024u);
+                else *reinterpret_cast<u32x4 *>(ls + C::A_BYTES + wl * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < LA; ++i) dl_load16(offa[i], sa, slot + (uint32_t)(wave * LA + i) * 1024u);
 #pragma unroll
@@ -1259,7 +1290,8 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
         read_a(fah, kt, 1);                                              // B
         mma(fal, fbc, 0);
         if (!last) {
-            if (refill) {                                                // C
+            // C: exact count only when tiles kt+2 and kt+3 issued all their loads (see the bf16 kernel)
+            if (refill && (!RAGGED || (kbeg + kt + S) * BKB <= p.K)) {
                 asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
             } else {
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -1275,7 +1307,7 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 #pragma unroll
         for (int t = 0; t < S - 1; ++t)
             if (t < KT) issue(t);
-        if (KT >= S - 1) {
+        if (KT >= S - 1 && (!RAGGED || (kbeg + S - 1) * BKB <= p.K)) {
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
         } else {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -1295,7 +1327,7 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 
     if (nsplit > 1 && !splitk_exchange<C>(acc, p, tile_id - p.split_from, split, nsplit, red, tid)) return;
 
-    run_epilogue<C, ACC, EPI, false, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
+    run_epilogue<C, ACC, EPI, RAGGED, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
 }
 
 // Host-side launcher, one per (operand layouts, epilogue mode, kernel kind).

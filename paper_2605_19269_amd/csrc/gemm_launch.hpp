@@ -33,15 +33,15 @@ hipError_t launch_gemm(const GemmParams &p_in, hipStream_t stream)
     return hipGetLastError();
 }
 
-// 8-bit operands: whole tiles only (M, N multiples of 256, K a multiple of 128), both operands K-contiguous.
-template <int EPI>
+// 8-bit operands, both K-contiguous.  KIND_WHOLE: M, N multiples of 256 and K a multiple of 128.
+template <int EPI, int KIND>
 hipError_t launch_gemm_f8(const GemmParams &p_in, hipStream_t stream)
 {
     using C = FastCfg;
     GemmParams p = p_in;
-    p.tiles_m = p.M / C::BM;
-    p.tiles_n = p.N / C::BN;
-    hipLaunchKernelGGL((gemm_kernel_dl_f8<C, EPI>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
+    p.tiles_m = (p.M + C::BM - 1) / C::BM;
+    p.tiles_n = (p.N + C::BN - 1) / C::BN;
+    hipLaunchKernelGGL((gemm_kernel_dl_f8<C, EPI, KIND == KIND_RAGGED>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -72,11 +72,16 @@ CODA_EXTERN_LAYOUT(true, false)
 CODA_EXTERN_LAYOUT(true, true)
 CODA_EXTERN_LAYOUT(false, false)
 CODA_EXTERN_LAYOUT(false, true)
-extern template hipError_t launch_gemm_f8<EPI_LINEAR>(const GemmParams &, hipStream_t);
-extern template hipError_t launch_gemm_f8<EPI_SWIGLU_FWD>(const GemmParams &, hipStream_t);
-extern template hipError_t launch_gemm_f8<EPI_SWIGLU_BWD>(const GemmParams &, hipStream_t);
-extern template hipError_t launch_gemm_f8<EPI_ACCUM>(const GemmParams &, hipStream_t);
-extern template hipError_t launch_gemm_f8<EPI_RMSNORM_BWD>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_gemm_f8<EPI_LINEAR, KIND_WHOLE>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_gemm_f8<EPI_LINEAR, KIND_RAGGED>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_gemm_f8<EPI_SWIGLU_FWD, KIND_WHOLE>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_gemm_f8<EPI_SWIGLU_FWD, KIND_RAGGED>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_gemm_f8<EPI_SWIGLU_BWD, KIND_WHOLE>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_gemm_f8<EPI_SWIGLU_BWD, KIND_RAGGED>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_gemm_f8<EPI_ACCUM, KIND_WHOLE>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_gemm_f8<EPI_ACCUM, KIND_RAGGED>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_gemm_f8<EPI_RMSNORM_BWD, KIND_WHOLE>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_gemm_f8<EPI_RMSNORM_BWD, KIND_RAGGED>(const GemmParams &, hipStream_t);
 #endif
 
 }  // namespace coda

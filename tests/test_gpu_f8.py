@@ -1,6 +1,6 @@
 """GPU parity of the 8-bit-operand variant (OCP E4M3 A [M x K] and B [N x K], fp32 accumulation, the same epilogue
 programs) against the CPU oracle, which decodes the very same bytes by the format's definition and then applies its
-ordinary GEMM definitions.  Covers the decoding of every finite code, every epilogue mode, and split-K."""
+ordinary GEMM definitions.  Covers the decoding of every finite code, every epilogue mode, ragged shapes, and split-K."""
 import numpy as np
 import pytest
 import torch
@@ -33,7 +33,8 @@ def operands(oracle, g, M, N, K, a_std=1.0, b_std=1.0):
     return A8, B8, oracle.f8e4m3_to_bf16_bits(A8), oracle.f8e4m3_to_bf16_bits(B8)
 
 
-SHAPES = [(256, 256, 128), (512, 768, 384), (256, 512, 2048)]
+# whole tiles | ragged in M, N and K (K past a whole pair of 64-element K-steps by 16 and by 80 elements)
+SHAPES = [(256, 256, 128), (512, 768, 384), (256, 512, 2048), (264, 520, 208), (200, 264, 144)]
 
 
 def test_every_finite_code_is_decoded_as_e4m3(oracle):
@@ -54,7 +55,7 @@ def test_every_finite_code_is_decoded_as_e4m3(oracle):
 
 
 # without a workspace | with one, on shapes the 8-bit plan splits 4-way and 2-way
-@pytest.mark.parametrize("M,N,K,split", [(m, n, k, False) for m, n, k in SHAPES] + [(256, 256, 8192, True), (512, 512, 4096, True)])
+@pytest.mark.parametrize("M,N,K,split", [(m, n, k, False) for m, n, k in SHAPES] + [(256, 256, 8192, True), (512, 512, 4096, True), (504, 264, 4304, True)] + [(8, 8, 16, False), (1, 256, 64, False)])
 def test_f8_linear_program(oracle, M, N, K, split):
     g = np.random.Generator(np.random.PCG64(1100 + M + K))
     A8, B8, A16, B16 = operands(oracle, g, M, N, K)
@@ -187,8 +188,7 @@ def test_f8_argument_errors(oracle):
     out = G.Guarded(M, N, torch.bfloat16)
     for a, b, kw, status in [(A8, Bb, dict(transB=True), "CODA_ERR_DTYPE"),            # mixed operand types
                              (A8, Bn, dict(), "CODA_ERR_DTYPE"),                        # B not K-contiguous
-                             (A8[:128], B8, dict(transB=True), "CODA_ERR_SHAPE"),       # M not a whole tile
-                             (A8[:, :64], B8[:, :64], dict(transB=True), "CODA_ERR_SHAPE")]:   # K not a multiple of 128
+                             (A8[:, :72], B8[:, :72], dict(transB=True), "CODA_ERR_SHAPE")]:   # K not a multiple of 16
         with pytest.raises(coda.CodaError) as ei:
             coda.coda_gemm(a, b, [coda.store(out.t)], **kw)
         assert ei.value.status == getattr(coda, status)
