@@ -545,3 +545,42 @@ def test_swiglu_backward_saturated_gates(oracle, M, N, K):
     d = np.abs(gotO - refO)
     assert (d <= 1e-2 + 1e-2 * np.abs(refO)).all(), "activation: max delta %.3g" % d.max()
     G.assert_f32_signed_close(G.host_f64(stat), refstat, "row statistic")
+
+
+def test_repeat_launches_are_bitwise_identical_and_leave_inputs_alone():
+    """With two-pass partials nothing depends on the order in which workgroups run: the same launch twice gives the same
+    bits in every output (tile outputs, row partials, column partials), and no input buffer changes.  Atomic row sums may
+    differ in the last bits between runs; their spread is bounded here."""
+    M, N, K = 1024, 1280, 520
+    g = rng(77)
+    A, Bt = synth.normal_bf16(g, (M, K), 1.0), synth.normal_bf16(g, (N, K), 0.05)
+    C, Z = synth.normal_bf16(g, (M, N), 1.0), synth.normal_bf16(g, (M, 2 * N), 1.0)
+    r = synth.uniform_f32(g, (M,), 0.5, 1.5)
+    dA, dB, dC, dZ, dr = G.dev_bf16(A), G.dev_bf16(Bt), G.dev_bf16(C), G.dev_bf16(Z), G.dev_f32(r)
+    inputs = [dA, dB, dC, dZ, dr]
+    before = [t.clone() for t in inputs]
+    nblk = coda.coda_row_partial_blocks(N)
+
+    def run_all():
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        part = torch.empty((nblk, M), dtype=torch.float32, device="cuda")
+        coda.coda_gemm(dA, dB, [coda.row_scale(dr), coda.add_tile(dC), coda.row_sumsq(part), coda.store(Y)], transB=True)
+        H = torch.empty((M, N // 2), dtype=torch.bfloat16, device="cuda")
+        coda.coda_gemm(dA, dB, [coda.row_scale(dr), coda.swiglu_fwd(), coda.store(H)], transB=True)
+        dZo = torch.empty((M, 2 * N), dtype=torch.bfloat16, device="cuda")
+        stat = torch.empty((nblk, M), dtype=torch.float32, device="cuda")
+        coda.coda_gemm(dA, dB, [coda.swiglu_bwd(dZ, stat_out=stat), coda.store(dZo)], transB=True)
+        ss_atomic = torch.zeros(M, dtype=torch.float32, device="cuda")
+        Y2 = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        coda.coda_gemm(dA, dB, [coda.add_tile(dC), coda.row_sumsq(ss_atomic, atomic=True), coda.store(Y2)], transB=True)
+        torch.cuda.synchronize()
+        return [Y, part, H, dZo, stat, Y2], ss_atomic
+
+    first, at1 = run_all()
+    second, at2 = run_all()
+    for a, b in zip(first, second):
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+    for t, t0 in zip(inputs, before):
+        assert torch.equal(t.view(torch.uint8), t0.view(torch.uint8)), "an input buffer was modified"
+    rel = ((at1 - at2).abs() / at1.abs().clamp_min(1e-30)).max().item()
+    assert rel <= 1e-5, "atomic row sums differ by %.3g between runs" % rel
