@@ -98,7 +98,7 @@ def main():
 
     def fused_step(rec=None):
         def mark(name, fn):
-            if rec is None:
+            if rec is None or name not in rec:
                 fn()
             else:
                 a, b = ev(), ev()
@@ -129,8 +129,13 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    rec = {k: [] for k in kernels}
+    # Timed region: HIP events bracket only the dominant kernel (each event pair costs the step about 6 us of launch gaps);
+    # the other three kernels get their events in a second, untimed pass of the same step.
+    rec = {"up": []}
     sec = run(fused_step, args.steps, args.warmup, rec)
+    rec_rest = {k: [] for k in kernels if k != "up"}
+    run(fused_step, args.steps, 2, rec_rest)
+    rec.update(rec_rest)
     kern_all = {k: np.array([a.elapsed_time(b) for a, b in rec[k]]) for k in kernels}
     kern_ms = {k: float(kern_all[k].mean()) for k in kernels}
     kern_tflops = {k: flops[k] / (kern_ms[k] * 1e-3) * 1e-12 for k in kernels}
@@ -148,6 +153,8 @@ def main():
         "kernels": {k: {"ms": round(kern_ms[k], 4), "ms_std": round(float(kern_all[k].std()), 4),
                         "ms_min": round(float(kern_all[k].min()), 4), "tflops": round(kern_tflops[k], 1),
                         "pct_peak": round(100.0 * kern_tflops[k] / PEAK_BF16_TFLOPS, 2)} for k in kernels},
+        "kernels_note": "up: HIP events inside the timed region; down, bwd_act, bwd_wgt: events in a second pass of the same "
+                        "step right after it (every event pair adds about 6 us of launch gap to a step)",
         "roofline": {"kernel": "gemm_kernel<EPI_SWIGLU_FWD> (up-projection: row scale + SwiGLU)", "bound": "mfma",
                      "achieved": round(kern_tflops["up"], 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(kern_tflops["up"] / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES},
@@ -187,6 +194,21 @@ def main():
                                    "N(0,1) x N(0,0.02) operands and on zeros: the chip lowers its clock under its power limit "
                                    "when operand bits toggle")
         del fa, fb
+
+    # ---- the same fused step captured once into a HIP graph and replayed (context; `value` is the eager step) ------
+    if not args.no_extras:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fused_step(None)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            fused_step(None)
+        gsec = run(lambda _rec: graph.replay(), args.steps, args.warmup)
+        out["fused_step_hip_graph_replay"] = {"ms_per_step": round(gsec * 1e3, 4), "tflops": round(total_flops / gsec * 1e-12, 2)}
+        del graph
 
     # ---- further GEMM+epilogue kernels measured on their own (not part of `value`) -----------------------------
     if not args.no_extras:
