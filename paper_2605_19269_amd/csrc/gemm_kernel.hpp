@@ -771,8 +771,45 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
                 stage_fence();
             }
         }
+    } else if constexpr (EPI == EPI_ACCUM) {
+        // ---- in-place fp32 accumulate: 16 bytes per lane, direct.  Loads and stores go through the same pointer, so the
+        // compiler cannot move a load above an earlier store on its own, and unit by unit only a handful of loads would
+        // be in flight per wave.  The units are walked in batches of QB with the loads of the next batch issued ahead of
+        // the adds and stores of the current one (two register buffers).
+        constexpr int NQ = NB * NU, QB = 8, NBATCH = NQ / QB;
+        static_assert(NQ % QB == 0, "whole batches");
+        float *outp = reinterpret_cast<float *>(p.out);
+        f32x4 buf[2][QB];
+        auto where = [&](int q, bool &ok) -> float * {
+            const int i = q / NU, u = q % NU;
+            const int m = mw + i * LR + lrow, n = nw + u * UC + lcol;
+            ok = !EDGE || (m < p.M && n < p.N);
+            return outp + (int64_t)m * p.ld_out + n;
+        };
+        auto fetch = [&](f32x4(&b)[QB], int batch) {
+#pragma unroll
+            for (int k = 0; k < QB; ++k) {
+                bool ok;
+                const float *gp = where(batch * QB + k, ok);
+                b[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (ok) b[k] = *reinterpret_cast<const f32x4 *>(gp);
+            }
+        };
+        fetch(buf[0], 0);
+#pragma unroll
+        for (int b = 0; b < NBATCH; ++b) {
+            if (b + 1 < NBATCH) fetch(buf[(b + 1) & 1], b + 1);
+#pragma unroll
+            for (int k = 0; k < QB; ++k) {
+                const int q = b * QB + k;
+                bool ok;
+                float *gp = where(q, ok);
+                const f32x4 v = buf[b & 1][k] + acc.get(q / NU, q % NU);
+                if (ok) *reinterpret_cast<f32x4 *>(gp) = v;
+            }
+        }
     } else {
-        // ---- fp32 outputs (f32 store of the linear program, in-place fp32 accumulate): 16 bytes per lane, direct
+        // ---- fp32 store of the linear program: 16 bytes per lane, direct
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             const int m = mw + i * LR + lrow;
@@ -809,10 +846,6 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
                     }
                     if (ok) *reinterpret_cast<f32x4 *>(gp) = v;
                     asm volatile("" : "+v"(rsum[i]));
-                } else if (ok) {
-                    f32x4 cur = *reinterpret_cast<const f32x4 *>(gp);
-                    cur += v;
-                    *reinterpret_cast<f32x4 *>(gp) = cur;
                 }
             }
         }
