@@ -376,6 +376,18 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
     float rsum[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) rsum[i] = 0.0f;
+    // row scales of the lane's NB rows, all fetched here in one go: a load per block inside the passes below would sit
+    // behind that pass's stores and expose one memory round trip per block
+    float rsv[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) rsv[i] = 1.0f;
+    if ((EPI == EPI_LINEAR || EPI == EPI_SWIGLU_FWD) && p.row_scale) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int m = mw + i * LR + lrow;
+            rsv[i] = (!EDGE || m < p.M) ? p.row_scale[m] : 0.0f;
+        }
+    }
 
     if (EPI == EPI_LINEAR && p.lse_max) {
         // ---- log-sum-exp partials of this 256-column tile (Kernels 3 / 8) on the fp32 values v = acc * r, before rounding:
@@ -386,7 +398,7 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
         for (int i = 0; i < NB; ++i) {
             const int m = mw + i * LR + lrow;
             const bool mok = !EDGE || m < p.M;
-            const float rs = p.row_scale ? (mok ? p.row_scale[m] : 0.0f) : 1.0f;
+            const float rs = rsv[i];
             const int yy = mok ? p.lse_y[m] : -1;
             float mx = NEG_INF;
 #pragma unroll
@@ -539,8 +551,8 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
             const int r0 = ps * P;
 #pragma unroll
             for (int fi = 0; fi < FPP; ++fi) {
-                const int i = ps * FPP + fi, m = mw + i * LR + lrow;
-                const float rs = p.row_scale ? ((!EDGE || m < p.M) ? p.row_scale[m] : 0.0f) : 1.0f;
+                const int i = ps * FPP + fi;
+                const float rs = rsv[i];
 #pragma unroll
                 for (int u = 0; u < NU; ++u) {
                     const f32x4 v = acc.get(i, u) * rs;
@@ -556,8 +568,8 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
                 stage_fence();
 #pragma unroll
                 for (int fi = 0; fi < FPP; ++fi) {
-                    const int i = ps * FPP + fi, m = mw + i * LR + lrow;
-                    const float rs = p.row_scale ? ((!EDGE || m < p.M) ? p.row_scale[m] : 0.0f) : 1.0f;
+                    const int i = ps * FPP + fi;
+                    const float rs = rsv[i];
 #pragma unroll
                     for (int u = 0; u < NU; ++u) {
                         const f32x4 v = acc.get(i, u) * rs;
@@ -682,9 +694,8 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
             stage_fence();
 #pragma unroll
             for (int fi = 0; fi < FPP; ++fi) {
-                const int i = ps * FPP + fi, m = mw + i * LR + lrow;
-                const bool mok = !EDGE || m < p.M;
-                const float rs = p.row_scale ? (mok ? p.row_scale[m] : 0.0f) : 1.0f;
+                const int i = ps * FPP + fi;
+                const float rs = rsv[i];
 #pragma unroll
                 for (int u = 0; u < NU; ++u) {
                     const int nl = u * UC + lcol;
@@ -727,7 +738,7 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
                 for (int fi = 0; fi < FPP; ++fi) {
                     const int i = ps * FPP + fi, m = mw + i * LR + lrow;
                     const bool mok = !EDGE || m < p.M;
-                    const float rs = p.row_scale ? (mok ? p.row_scale[m] : 0.0f) : 1.0f;
+                    const float rs = rsv[i];
                     // RoPE: table row of this token and the frequency index of the lane's first pair; units follow each
                     // other UC / 2 <= 8 pairs apart and rope_half is a multiple of 4, so the index wraps at most twice per step
                     const int64_t trow = (p.rope_cos && mok) ? (int64_t)p.rope_pos[m] * p.rope_half : 0;
@@ -814,8 +825,7 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
         for (int i = 0; i < NB; ++i) {
             const int m = mw + i * LR + lrow;
             const bool mok = !EDGE || m < p.M;
-            float rs = 1.0f;
-            if (EPI == EPI_LINEAR && p.row_scale) rs = mok ? p.row_scale[m] : 0.0f;
+            const float rs = rsv[i];
             const bool rope = EPI == EPI_LINEAR && p.rope_cos;
             const int64_t trow = (rope && mok) ? (int64_t)p.rope_pos[m] * p.rope_half : 0;
             int rf = rope ? ((nw + lcol) >> 1) % p.rope_half : 0;
