@@ -411,26 +411,32 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
         // per lane and row the maximum and the sum of exp(v - max) over its values, merged over the lanes that share the
         // row and then over the four column waves with the usual rescaling rule.
         constexpr float NEG_INF = -__builtin_inff();
+        int yv[NB];                                                 // target columns of the lane's rows, fetched in one go
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int m = mw + i * LR + lrow;
+            yv[i] = (!EDGE || m < p.M) ? p.lse_y[m] : -1;
+        }
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             const int m = mw + i * LR + lrow;
             const bool mok = !EDGE || m < p.M;
             const float rs = rsv[i];
-            const int yy = mok ? p.lse_y[m] : -1;
+            const int yy = yv[i];
             float mx = NEG_INF;
 #pragma unroll
             for (int u = 0; u < NU; ++u) {
                 const int n = nw + u * UC + lcol;
                 if (mok && (!EDGE || n < p.N)) {
-                    const f32x4 a = acc.get(i, u);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float v = a[e] * rs;
-                        mx = fmaxf(mx, v);
-                        if (n + e == yy) p.lse_tgt[m] = v;
-                    }
+                    const f32x4 a = acc.get(i, u) * rs;
+                    mx = fmaxf(fmaxf(mx, fmaxf(a[0], a[1])), fmaxf(a[2], a[3]));
+                    const unsigned e = (unsigned)(yy - n);          // the target column falls into this unit iff e < 4
+                    if (e < 4u) p.lse_tgt[m] = e == 0 ? a[0] : (e == 1 ? a[1] : (e == 2 ? a[2] : a[3]));
                 }
             }
+            // exp(a * rs - mx) as one multiply-add and one base-2 exponential per element
+            constexpr float LOG2E = 1.4426950408889634f;
+            const float c2 = rs * LOG2E, d2 = -mx * LOG2E;
             float sm = 0.0f;
 #pragma unroll
             for (int u = 0; u < NU; ++u) {
@@ -438,7 +444,7 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
                 if (mok && (!EDGE || n < p.N)) {
                     const f32x4 a = acc.get(i, u);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) sm += __expf(a[e] * rs - mx);
+                    for (int e = 0; e < 4; ++e) sm += __builtin_amdgcn_exp2f(__builtin_fmaf(a[e], c2, d2));
                 }
             }
 #pragma unroll
