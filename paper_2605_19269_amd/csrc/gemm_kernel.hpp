@@ -494,6 +494,23 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
 #pragma unroll
         for (int ps = 0; ps < WTM / P; ++ps) {
             const int r0 = ps * P;
+            // the pass's row factors and the wave's gamma values first, so that they travel with the tile loads instead of
+            // waiting, block by block, behind the previous pass's stores
+            float rrv[FPP], zzv[FPP];
+            f32x4 gmv[NU];
+#pragma unroll
+            for (int fi = 0; fi < FPP; ++fi) {
+                const int m = mw + (ps * FPP + fi) * LR + lrow;
+                const bool mok = !EDGE || m < p.M;
+                rrv[fi] = mok ? p.rn_r[m] : 0.0f;
+                zzv[fi] = mok ? p.rn_z[m] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                const int nl = u * UC + lcol;
+                gmv[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (!EDGE || nw + nl < p.N) gmv[u] = *reinterpret_cast<const f32x4 *>(p.rn_gamma + nw + nl);
+            }
             stage_load<RB, P, EDGE, true>(reg, reinterpret_cast<const unsigned char *>(p.rn_c + (int64_t)(mw + r0) * p.ld_rn_c + nw),
                                     p.ld_rn_c * 2, rows_ok - r0, cols_ok * 2, lane);
             if (p.add)
@@ -504,14 +521,13 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
             for (int fi = 0; fi < FPP; ++fi) {
                 const int i = ps * FPP + fi, m = mw + i * LR + lrow;
                 const bool mok = !EDGE || m < p.M;
-                const float rr = mok ? p.rn_r[m] : 0.0f, zz = mok ? p.rn_z[m] : 0.0f;
+                const float rr = rrv[fi], zz = zzv[fi];
 #pragma unroll
                 for (int u = 0; u < NU; ++u) {
                     const int nl = u * UC + lcol;
                     const bool ok = mok && (!EDGE || nw + nl < p.N);
                     const uint32_t ua = St::template unit_addr<LR>(ulane, fi, u * UC * 2);
-                    f32x4 gm = {0.f, 0.f, 0.f, 0.f};
-                    if (ok) gm = *reinterpret_cast<const f32x4 *>(p.rn_gamma + nw + nl);
+                    const f32x4 gm = gmv[u];
                     const u32x2 cw = *reinterpret_cast<const u32x2 *>(reg + ua);
                     const f32x4 d = acc.get(i, u);
                     const f32x4 cn = f32x4{bf16_lo(cw[0]), bf16_hi(cw[0]), bf16_lo(cw[1]), bf16_hi(cw[1])} * rr;
