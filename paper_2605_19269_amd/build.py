@@ -8,6 +8,7 @@ binding loads.  hipcc cross-compiles for gfx950 without a GPU present.
 """
 import concurrent.futures
 import os
+import re
 import subprocess
 import sys
 
@@ -15,6 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libcoda.so")
+RESOURCES = os.path.join(HERE, "libcoda.resources.txt")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 VALU ops.
@@ -36,11 +38,52 @@ def _compile(src, force):
     newest = max(os.path.getmtime(p) for p in [path] + _headers())
     if not force and os.path.exists(obj) and os.path.getmtime(obj) >= newest:
         return obj, ""
-    r = subprocess.run([HIPCC] + FLAGS + ["-c", path, "-o", obj], capture_output=True, text=True)
-    log = "\n".join(l for l in (r.stdout + r.stderr).splitlines() if "packed-fp32-ops" not in l)
+    r = subprocess.run([HIPCC] + FLAGS + ["-Rpass-analysis=kernel-resource-usage", "-c", path, "-o", obj],
+                       capture_output=True, text=True)
+    text = r.stdout + r.stderr
+    with open(obj + ".resources", "w") as f:
+        f.write(_resource_table(text))
+    log = "\n".join(_strip_remarks(text))
     if r.returncode != 0:
         raise RuntimeError("hipcc failed on %s:\n%s" % (src, log))
     return obj, log
+
+
+_REMARK = re.compile(r"remark:\s+(Function Name|VGPRs|AGPRs|ScratchSize \[bytes/lane\]|VGPRs Spill|SGPRs Spill|LDS Size \[bytes/block\]): (\S+)")
+
+
+def _resource_table(text):
+    """One line per kernel from the compiler's resource-usage remarks: name vgprs agprs scratch_bytes vgpr_spills lds_bytes."""
+    rows, cur = [], None
+    for line in text.splitlines():
+        m = _REMARK.search(line)
+        if not m:
+            continue
+        key, val = m.group(1), m.group(2)
+        if key == "Function Name":
+            cur = {"name": val}
+            rows.append(cur)
+        elif cur is not None:
+            cur[key] = val
+    return "".join("%s %s %s %s %s %s\n" % (k["name"], k.get("VGPRs", "?"), k.get("AGPRs", "?"), k.get("ScratchSize [bytes/lane]", "?"),
+                                            k.get("VGPRs Spill", "?"), k.get("LDS Size [bytes/block]", "?")) for k in rows)
+
+
+def _strip_remarks(text):
+    """Compiler output without the resource-usage remarks (each is followed by a source line and a caret line)."""
+    out, skip = [], 0
+    for line in text.splitlines():
+        if skip:
+            skip -= 1
+            continue
+        if "-Rpass-analysis=kernel-resource-usage" in line:
+            skip = 2 if "Function Name" in line else 0
+            continue
+        if "packed-fp32-ops" not in line and "remark generated" not in line and "remarks generated" not in line:
+            out.append(line)
+    if not any("warning:" in l or "error:" in l for l in out):
+        out = [l for l in out if not l.startswith("In file included from")]   # include trails of the dropped remarks
+    return out
 
 
 def build(force=False, jobs=None):
@@ -58,6 +101,11 @@ def build(force=False, jobs=None):
                            capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
+    # registers, scratch and LDS of every kernel in the library, as the compiler reported them (read by the host tests)
+    with open(RESOURCES, "w") as f:
+        for o in objs:
+            if os.path.exists(o + ".resources"):
+                f.write(open(o + ".resources").read())
     return LIB
 
 

@@ -237,8 +237,8 @@ __device__ __forceinline__ void stage_load(unsigned char *reg, const unsigned ch
 
 // P rows x RB bytes: region -> global.  STREAM: stores carry the non-temporal hint (the output is not read again by this
 // kernel and should not displace operand panels in L2).  Measured on the benchmark shapes: +2.5 % on the down-projection,
-// +2 to +6 % on the QKV kernels, neutral on the up-projection; the SwiGLU backward, whose 268 MB output leaves in chip-wide
-// bursts, loses 2.4 % with it and keeps ordinary stores.
+// +2 to +6 % on the QKV kernels; the SwiGLU forward (no gain, half-line rows) and the SwiGLU backward, whose 268 MB output
+// leaves in chip-wide bursts (-2.4 % with the hint), keep ordinary stores.
 template <int RB, int P, bool EDGE, bool STREAM = true>
 __device__ __forceinline__ void stage_store(const unsigned char *reg, unsigned char *g, int64_t pitch, int rows_ok,
                                             int bytes_ok, int lane)
@@ -393,24 +393,28 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
     float rsum[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) rsum[i] = 0.0f;
-    // row scales of the lane's NB rows, all fetched here in one go: a load per block inside the passes below would sit
-    // behind that pass's stores and expose one memory round trip per block
-    float rsv[NB];
+    // Row scales of the lane's NB rows, all fetched in one go at the head of the program branch that uses them: a load
+    // per block inside the passes would sit behind that pass's stores and expose one memory round trip per block.
+    // (Fetched per branch, not once up here, so that they are not live across the other branches' code.)
+    auto fetch_row_scales = [&](float(&rsv)[NB]) {
 #pragma unroll
-    for (int i = 0; i < NB; ++i) rsv[i] = 1.0f;
-    if ((EPI == EPI_LINEAR || EPI == EPI_SWIGLU_FWD) && p.row_scale) {
+        for (int i = 0; i < NB; ++i) rsv[i] = 1.0f;
+        if (p.row_scale) {
 #pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            const int m = mw + i * LR + lrow;
-            rsv[i] = (!EDGE || m < p.M) ? p.row_scale[m] : 0.0f;
+            for (int i = 0; i < NB; ++i) {
+                const int m = mw + i * LR + lrow;
+                rsv[i] = (!EDGE || m < p.M) ? p.row_scale[m] : 0.0f;
+            }
         }
-    }
+    };
 
     if (EPI == EPI_LINEAR && p.lse_max) {
         // ---- log-sum-exp partials of this 256-column tile (Kernels 3 / 8) on the fp32 values v = acc * r, before rounding:
         // per lane and row the maximum and the sum of exp(v - max) over its values, merged over the lanes that share the
         // row and then over the four column waves with the usual rescaling rule.
         constexpr float NEG_INF = -__builtin_inff();
+        float rsv[NB];
+        fetch_row_scales(rsv);
         int yv[NB];                                                 // target columns of the lane's rows, fetched in one go
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
@@ -585,6 +589,8 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
         static_assert(P % LR == 0 && WTM % P == 0, "staging pass");
         uint16_t *outp = reinterpret_cast<uint16_t *>(p.out);
         const uint32_t ulane_h = Stage<RBH>::template unit_lane<4, LR>(lane), ulane_z = Stage<RBZ>::template unit_lane<8, LR>(lane);
+        float rsv[NB];
+        fetch_row_scales(rsv);
 #pragma unroll
         for (int ps = 0; ps < WTM / P; ++ps) {
             const int r0 = ps * P;
@@ -601,7 +607,9 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
                 }
             }
             stage_fence();
-            stage_store<RBH, P, EDGE>(reg, reinterpret_cast<unsigned char *>(outp + (int64_t)(mw + r0) * p.ld_out + (nw >> 1)),
+            // ordinary stores: a wave's H rows are 64-byte halves of 128-byte lines, which L2 merges with the neighbouring
+            // wave's halves; with the streaming hint the L2 -> fabric write counter reads 10 % above the output bytes
+            stage_store<RBH, P, EDGE, false>(reg, reinterpret_cast<unsigned char *>(outp + (int64_t)(mw + r0) * p.ld_out + (nw >> 1)),
                                       p.ld_out * 2, rows_ok - r0, cols_ok, lane);
             if (p.out2) {
                 stage_fence();
@@ -707,6 +715,8 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
         const uint32_t ulane = St::template unit_lane<8, LR>(lane);
         const uint32_t rlane = St::row_lane(lane);
         const int f0 = (nw >> 1) % p.rope_half;                        // first frequency index of this wave's columns
+        float rsv[NB];
+        fetch_row_scales(rsv);
         unsigned char *rcos = reg + P * RB, *rsin = reg + 2 * P * RB;
         uint16_t *outp = reinterpret_cast<uint16_t *>(p.out);
         u32x4 tc[4], ts[4];
@@ -765,6 +775,8 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
         for (int sw = 0; sw < sweeps; ++sw) {
             uint16_t *dst = sw == 0 ? reinterpret_cast<uint16_t *>(p.out) : p.side;
             const int64_t ldd = sw == 0 ? p.ld_out : p.ld_side;
+            float rsv[NB];
+            fetch_row_scales(rsv);
 #pragma unroll
             for (int ps = 0; ps < WTM / P; ++ps) {
                 const int r0 = ps * P;
@@ -860,6 +872,8 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
         }
     } else {
         // ---- fp32 store of the linear program: 16 bytes per lane, direct
+        float rsv[NB];
+        fetch_row_scales(rsv);
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             const int m = mw + i * LR + lrow;
