@@ -194,3 +194,38 @@ def test_f8_argument_errors(oracle):
         assert ei.value.status == getattr(coda, status)
     torch.cuda.synchronize()
     out.check_guards()
+
+
+def test_f8_full_size_up_and_down_projection_sampled_rows(oracle):
+    """The 8-bit kernels at the benchmark's 1B shapes, launched as bench.py launches them, checked on sampled output rows
+    (every epilogue here is row-local, so the oracle computes exactly those rows)."""
+    g = np.random.Generator(np.random.PCG64(1400))
+    M, d, F = 8192, 2048, 8192
+    rows = synth.sample_rows(M, 32, seed=5)
+    # up-projection: row scale + SwiGLU
+    X8, W8 = synth.normal_f8e4m3(g, (M, d), 1.0), synth.normal_f8e4m3(g, (2 * F, d), 1.0)
+    r = synth.uniform_f32(g, (M,), 0.01, 0.03)
+    H = torch.empty((M, F), dtype=torch.bfloat16, device="cuda")
+    dr = G.dev_f32(r)
+    coda.coda_gemm(dev_u8(X8), dev_u8(W8), [coda.row_scale(dr), coda.swiglu_fwd(), coda.store(H)], transB=True)
+    torch.cuda.synchronize()
+    ref = oracle.gemm_rowscale_swiglu(oracle.f8e4m3_to_bf16_bits(X8), oracle.f8e4m3_to_bf16_bits(W8), r=r.astype(np.float64),
+                                      transB=True, rows=rows)
+    G.assert_bf16_close(G.host_f64(H[torch.from_numpy(rows).cuda()]), ref, "f8 1B up")
+    del H
+    # down-projection: row scale (dequantisation) + residual + row sum of squares
+    H8, Wd8 = synth.normal_f8e4m3(g, (M, F), 1.0), synth.normal_f8e4m3(g, (d, F), 1.0)
+    R = synth.normal_bf16(g, (M, d), 1.0)
+    r2 = synth.uniform_f32(g, (M,), 0.005, 0.015)
+    Y = torch.empty((M, d), dtype=torch.bfloat16, device="cuda")
+    nblk = coda.coda_row_partial_blocks(d)
+    part = torch.empty((nblk, M), dtype=torch.float32, device="cuda")
+    ss = torch.empty(M, dtype=torch.float32, device="cuda")
+    dr2, dR = G.dev_f32(r2), G.dev_bf16(R)
+    coda.coda_gemm(dev_u8(H8), dev_u8(Wd8), [coda.row_scale(dr2), coda.add_tile(dR), coda.row_sumsq(part), coda.store(Y)], transB=True)
+    coda.coda_row_finalize(part, M, nblk, sum_out=ss, d=d, eps=0.0)
+    torch.cuda.synchronize()
+    refY, refss = oracle.gemm_residual_sumsq(oracle.f8e4m3_to_bf16_bits(H8), oracle.f8e4m3_to_bf16_bits(Wd8), r=r2.astype(np.float64),
+                                             C=R, transB=True, rows=rows)[:2]
+    G.assert_bf16_close(G.host_f64(Y[torch.from_numpy(rows).cuda()]), refY, "f8 1B down")
+    G.assert_sumsq_close(ss.cpu().numpy()[rows], refss, "f8 1B down sumsq")
