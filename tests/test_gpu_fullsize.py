@@ -224,3 +224,61 @@ def test_llama1b_forward_gemms_on_f8e4m3_operands(oracle):
                                              C=Rb, transB=True, rows=rows)[:2]
     G.assert_bf16_close(rows_of(Y, rows), refY, "1B down, E4M3 operands")
     G.assert_sumsq_close(ss.cpu().numpy()[rows], refss, "1B down sumsq, E4M3 operands")
+
+
+def test_operands_and_outputs_beyond_4_gib(oracle):
+    """Byte offsets past 2^32 in an operand (A: 140000 x 16384 bf16 = 4.6 GB) and in an output (140000 x 16384 bf16),
+    with a ragged M: sampled rows, most of them past the 4 GiB mark, against the oracle on exactly those rows."""
+    M = 140000
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    rows = np.concatenate([[0, 1, 131071, 131072, M - 1],
+                           np.random.Generator(np.random.PCG64(12)).integers(131072, M, size=19)]).astype(np.int64)
+    drows = torch.from_numpy(rows).cuda()
+
+    def bits(t):
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+    # large A, narrow output
+    K, N = 16384, 256
+    A = torch.randn((M, K), generator=gen, device="cuda", dtype=torch.bfloat16)
+    B = (torch.randn((K, N), generator=gen, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+    r = torch.rand(M, generator=gen, device="cuda", dtype=torch.float32) + 0.5
+    out = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    coda.coda_gemm(A, B, [coda.row_scale(r), coda.store(out)])
+    torch.cuda.synchronize()
+    ref = oracle.gemm_rowscale(bits(A[drows]), bits(B), r=r[drows].cpu().numpy().astype(np.float64))
+    G.assert_bf16_close(G.host_f64(out[drows]), ref, "A beyond 4 GiB")
+    del A, out
+    torch.cuda.empty_cache()
+    # short contraction, large output (pairwise forward halves it: H is 140000 x 16384, its pre-activation twice that)
+    K, N = 64, 32768
+    A = torch.randn((M, K), generator=gen, device="cuda", dtype=torch.bfloat16)
+    B = (torch.randn((K, N), generator=gen, device="cuda", dtype=torch.float32) * 0.2).to(torch.bfloat16)
+    H = torch.empty((M, N // 2), dtype=torch.bfloat16, device="cuda")
+    Z = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    coda.coda_gemm(A, B, [coda.row_scale(r), coda.swiglu_fwd(Z), coda.store(H)])
+    torch.cuda.synchronize()
+    refH, refZ = oracle.gemm_rowscale_swiglu(bits(A[drows]), bits(B), r=r[drows].cpu().numpy().astype(np.float64), want_preact=True)
+    G.assert_bf16_close(G.host_f64(H[drows]), refH, "H beyond 4 GiB")
+    G.assert_bf16_close(G.host_f64(Z[drows]), refZ, "Z beyond 4 GiB")
+
+
+def test_transposed_operand_beyond_4_gib_with_k_tail(oracle):
+    """A stored [K x M] with K = 140000 tokens (4.6 GB; K is not a multiple of the K-step): the weight-gradient form
+    G += A^T B in fp32, checked on sampled output rows (= columns of the stored A)."""
+    Kt, M, N = 140000, 16384, 256
+    gen = torch.Generator(device="cuda").manual_seed(13)
+    A = torch.randn((Kt, M), generator=gen, device="cuda", dtype=torch.bfloat16)
+    B = (torch.randn((Kt, N), generator=gen, device="cuda", dtype=torch.float32) * 1e-2).to(torch.bfloat16)
+    G0 = torch.randn((M, N), generator=gen, device="cuda", dtype=torch.float32) * 1e-3
+    Gw = G0.clone()
+    coda.coda_gemm(A, B, [coda.accum_f32(Gw)], transA=True)
+    torch.cuda.synchronize()
+    cols = np.concatenate([[0, 255, 256, M - 1], np.random.Generator(np.random.PCG64(14)).integers(0, M, size=12)]).astype(np.int64)
+    dcols = torch.from_numpy(cols).cuda()
+
+    def bits(t):
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+    ref = oracle.gemm_accumulate(bits(A[:, dcols]), bits(B), G0[dcols].cpu().numpy(), transA=True)
+    G.assert_f32_signed_close(G.host_f64(Gw[dcols]), ref, "A^T beyond 4 GiB")
