@@ -584,3 +584,33 @@ def test_repeat_launches_are_bitwise_identical_and_leave_inputs_alone():
         assert torch.equal(t.view(torch.uint8), t0.view(torch.uint8)), "an input buffer was modified"
     rel = ((at1 - at2).abs() / at1.abs().clamp_min(1e-30)).max().item()
     assert rel <= 1e-5, "atomic row sums differ by %.3g between runs" % rel
+
+
+def test_both_operands_k_contiguous_long_k_whole_tiles(oracle):
+    """Whole tiles, A [M x K] and B [N x K], K long enough that every XCD starts its K loop at a different offset
+    (12 tiles cover all eight start offsets): linear program and SwiGLU backward, element by element."""
+    M, N, K = 1024, 768, 1024
+    g = rng(88)
+    A, Bt = synth.normal_bf16(g, (M, K), 1.0), synth.normal_bf16(g, (N, K), 0.05)
+    C = synth.normal_bf16(g, (M, N), 1.0)
+    Y = G.Guarded(M, N, torch.bfloat16)
+    nblk = coda.coda_row_partial_blocks(N)
+    part = torch.full((nblk, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    dA, dB, dC = G.dev_bf16(A), G.dev_bf16(Bt), G.dev_bf16(C)
+    coda.coda_gemm(dA, dB, [coda.add_tile(dC), coda.row_sumsq(part), coda.store(Y.t)], transB=True)
+    ss = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_row_finalize(part, M, nblk, sum_out=ss, d=N, eps=0.0)
+    torch.cuda.synchronize()
+    refD, refss = oracle.gemm_residual_sumsq(A, Bt, C=C, transB=True)[:2]
+    Y.check_guards(); Y.written()
+    G.assert_bf16_close(G.host_f64(Y.t), refD, "residual output")
+    G.assert_sumsq_close(G.host_f64(ss), refss, "row sum of squares")
+    A2 = synth.normal_bf16(g, (M, K), 1e-2)
+    Z = synth.normal_bf16(g, (M, 2 * N), 1.0)
+    dZ = G.Guarded(M, 2 * N, torch.bfloat16)
+    dZin, dA2 = G.dev_bf16(Z), G.dev_bf16(A2)
+    coda.coda_gemm(dA2, dB, [coda.swiglu_bwd(dZin), coda.store(dZ.t)], transB=True)
+    torch.cuda.synchronize()
+    refdZ = oracle.gemm_swiglu_bwd(A2, Bt, Z, transB=True)[0]
+    dZ.check_guards(); dZ.written()
+    G.assert_bf16_close(G.host_f64(dZ.t), refdZ, "dZ")
