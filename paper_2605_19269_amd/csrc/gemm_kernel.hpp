@@ -1001,6 +1001,31 @@ __device__ __forceinline__ int dl_chunk_k(int j, int lane)
     }
 }
 
+// K-contiguous A operand, fetched two K-steps at a time ("pair"): [ROWS][64] tiles with 128-byte rows, so that a wave-load
+// covers 8 rows x one whole 128-byte line instead of 16 rows x half a line (half the L1 -> L2 requests for the same bytes:
+// +2.4 % up-projection, +3.9 % down-projection, +2 to +3 % on the 8B-shape kernels).  Chunk c (of 8) of row r sits at chunk
+// position c ^ (r & 7): conflict-free for the 16-row fragment read (timed over the XOR maps of the row bits).
+template <class C, int ROWS>
+__device__ __forceinline__ uint32_t dl_goffset_pair(int j, int lane, int64_t ld, int valid)
+{
+    const int r = j * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ (r & 7);
+    const int rg = r < valid ? r : valid - 1;
+    return (uint32_t)(((int64_t)rg * ld + c * 8) * 2);
+}
+// first contraction index, within the 64-wide pair, of the chunk that lane `lane` of wave-load `j` fetches
+__device__ __forceinline__ int dl_chunk_k_pair(int j, int lane)
+{
+    const int r = j * 8 + (lane >> 3);
+    return ((lane & 7) ^ (r & 7)) * 8;
+}
+// fragment of K-step h (0 / 1) of the pair: lane -> row row_base + lane % 16, elements 32 h + 8 (lane / 16) .. + 7
+__device__ __forceinline__ bf16x8 dl_frag16_pair(const unsigned char *tile, int row_base, int lane, int h)
+{
+    const int r = row_base + (lane & 15), c = h * 4 + (lane >> 4);
+    return *reinterpret_cast<const bf16x8 *>(tile + r * 128 + ((c ^ (r & 7)) << 4));
+}
+
 __device__ __forceinline__ void dl_load16(uint32_t voff, const void *sbase, uint32_t lds_addr)
 {
     // M0 carries the wave-uniform LDS destination; one wait state between the M0 write and its use.
@@ -1099,7 +1124,9 @@ __device__ __forceinline__ bf16x8 dl_frag16(const unsigned char *tile, int row_b
 // FLOP than 32x32x16 and sustains a higher clock on non-trivial operands); the wave's 128 x 64 tile is 8 x 4 blocks.
 // Per K-step the work is split in two halves of the wave's rows, so that the fragment reads of one half run under the
 // MFMAs of the other, with the workgroup barrier between them:
-//   A  issue loads of tile kt+S-1 into the slot freed by tile kt-1
+//   A  issue loads of tile kt+S-1 into the slot freed by tile kt-1 (a K-contiguous A operand: half of the wave's loads
+//      of the PAIR of K-steps kt+S, kt+S+1 for even kt / the other half for odd kt, into the slot freed by the pair that
+//      ended with kt-1: 128-byte rows, whole cache lines per request)
 //   B  read the row fragments of the upper half of tile kt; MFMAs of the lower half (fragments already in VGPRs)
 //   C  wait until this wave's loads of tile kt+1 have landed; workgroup barrier
 //   D  read the lower-half row fragments and the column fragments of tile kt+1; MFMAs of the upper half
@@ -1118,8 +1145,17 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     constexpr int NI = ACC::NB, NJ = ACC::NU, HM = NI / 2;
     constexpr int LA = C::LA, LB = C::LB;
     static_assert(NI % 2 == 0, "two row halves");
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[S * C::STAGE_BYTES];
-    __shared__ float red[2 * C::WGN * C::BM];   // row-reduction exchange; second half: sum-exp of the log-sum-exp partials
+    // PAIRED (A K-contiguous): three pair slots of A (two K-steps each) followed by four single-step slots of B, 160 KB;
+    // otherwise four slots of [A | B].  The epilogue stages through the first EPI_RING bytes either way; `red` (row-reduction
+    // exchange; second half: sum-exp of the log-sum-exp partials) follows them and, when PAIRED, lies inside the B slots, which
+    // are free once the mainloop is over.
+    constexpr bool PAIRED = AK;
+    constexpr int EPI_RING = S * C::STAGE_BYTES, RED_BYTES = 2 * C::WGN * C::BM * 4;
+    constexpr int A_REGION = PAIRED ? 3 * 2 * C::A_BYTES : 0;
+    constexpr int LDS_BYTES = PAIRED ? A_REGION + S * C::B_BYTES : EPI_RING + RED_BYTES;
+    static_assert(S == 4 && LDS_BYTES >= EPI_RING + RED_BYTES && LDS_BYTES <= 160 * 1024, "LDS plan");
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[LDS_BYTES];
+    float *red = reinterpret_cast<float *>(smem + EPI_RING);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1142,9 +1178,16 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     // loop-invariant per-lane byte offsets of this wave's chunks; wave w issues wave-loads w*L .. w*L+L-1
     const int valid_m = RAGGED ? (p.M - m0 < BM ? p.M - m0 : BM) : BM;
     const int valid_n = RAGGED ? (p.N - n0 < BN ? p.N - n0 : BN) : BN;
-    uint32_t offa[LA], offb[LB];
+    // A: LA wave-loads per wave and K-step, or (PAIRED) LAP per wave and pair of K-steps
+    constexpr int LAP = 2 * LA;
+    uint32_t offa[PAIRED ? LAP : LA], offb[LB];
+    if (PAIRED) {
 #pragma unroll
-    for (int i = 0; i < LA; ++i) offa[i] = dl_goffset<C, BM, AK>(wave * LA + i, lane, p.lda, valid_m);
+        for (int i = 0; i < LAP; ++i) offa[i] = dl_goffset_pair<C, BM>(wave * LAP + i, lane, p.lda, valid_m);
+    } else {
+#pragma unroll
+        for (int i = 0; i < LA; ++i) offa[i] = dl_goffset<C, BM, AK>(wave * LA + i, lane, p.lda, valid_m);
+    }
 #pragma unroll
     for (int i = 0; i < LB; ++i) offb[i] = dl_goffset<C, BN, BKC>(wave * LB + i, lane, p.ldb, valid_n);
     // scalar bases of the tile's first element; advance by one K-step per tile
@@ -1160,43 +1203,66 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     // backward (their epilogue bursts no longer coincide chip-wide), nothing on a plain store; the other layouts lose 1-2 %
     // with it and walk K from zero.  The order of the fp32 additions of a tile depends on its XCD, not on timing.
     const int rot = (AK && BKC && !RAGGED && nsplit == 1) ? ((((int)blockIdx.x & 7) * (KT / 8)) & ~1) : 0;
-    auto issue = [&](int t) {  // loads of tile t into slot t % S
-        const uint32_t slot = lds0 + (uint32_t)(t % S) * C::STAGE_BYTES;
+    auto rotated = [&](int t) {   // position along K of the workgroup's t-th K-step (rot and KT are even: pairs stay pairs)
         int tg = t + rot;
         if (tg >= KT) tg -= KT;
-        const unsigned char *sa = ga + (int64_t)tg * stepa;
-        const unsigned char *sb = gb + (int64_t)tg * stepb;
-        if (RAGGED && (kbeg + t + 1) * BK > p.K) {
-            // the tile reaches past K: a lane whose chunk lies past K stores zeros at its LDS position instead of fetching
-            const int k_left = p.K - (kbeg + t) * BK;              // contraction elements of this tile that exist (may be <= 0)
-            unsigned char *ls = smem + (t % S) * C::STAGE_BYTES;
+        return tg;
+    };
+    // LDS byte offsets of the slot that holds K-step t of A (PAIRED: the pair that contains t) and of B
+    auto a_slot = [&](int t) { return PAIRED ? ((t >> 1) % 3) * (2 * C::A_BYTES) : (t % S) * C::STAGE_BYTES; };
+    auto b_slot = [&](int t) { return PAIRED ? A_REGION + (t % S) * C::B_BYTES : (t % S) * C::STAGE_BYTES + C::A_BYTES; };
+    // loads of A for K-step t (PAIRED: for K-steps t and t + 1, t even).  A K-step (pair) that reaches past K: a lane whose
+    // chunk lies past K stores zeros at its LDS position instead of fetching.
+    // PAIRED: `part` 0 / 1 issues the first / second half of the wave's loads of the pair, so that every K-step issues the
+    // same number of loads; -1 issues all of them.
+    auto issue_a = [&](int t, int part) {
+        constexpr int L = PAIRED ? LAP : LA, SPAN = PAIRED ? 2 : 1;
+        const int slot = a_slot(t);
+        const unsigned char *sa = ga + (int64_t)rotated(t) * stepa;
+        const int i0 = part == 1 ? L / 2 : 0, i1 = part == 0 ? L / 2 : L;
+        if (RAGGED && (kbeg + t + SPAN) * BK > p.K) {
+            const int k_left = p.K - (kbeg + t) * BK;              // contraction elements from t on that exist (may be <= 0)
 #pragma unroll
-            for (int i = 0; i < LA; ++i) {
-                const int wl = wave * LA + i;
-                if (dl_chunk_k<BM, AK>(wl, lane) < k_left) dl_load16(offa[i], sa, slot + (uint32_t)wl * 1024u);
-                else *reinterpret_cast<u32x4 *>(ls + wl * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
-            }
-#pragma unroll
-            for (int i = 0; i < LB; ++i) {
-                const int wl = wave * LB + i;
-                if (dl_chunk_k<BN, BKC>(wl, lane) < k_left) dl_load16(offb[i], sb, slot + C::A_BYTES + (uint32_t)wl * 1024u);
-                else *reinterpret_cast<u32x4 *>(ls + C::A_BYTES + wl * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+            for (int i = 0; i < L; ++i) {
+                if (i < i0 || i >= i1) continue;
+                const int wl = wave * L + i;
+                const int ck = PAIRED ? dl_chunk_k_pair(wl, lane) : dl_chunk_k<BM, AK>(wl, lane);
+                if (ck < k_left) dl_load16(offa[i], sa, lds0 + (uint32_t)(slot + wl * 1024));
+                else *reinterpret_cast<u32x4 *>(smem + slot + wl * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
             }
             return;
         }
 #pragma unroll
-        for (int i = 0; i < LA; ++i) dl_load16(offa[i], sa, slot + (uint32_t)(wave * LA + i) * 1024u);
+        for (int i = 0; i < L; ++i)
+            if (i >= i0 && i < i1) dl_load16(offa[i], sa, lds0 + (uint32_t)(slot + (wave * L + i) * 1024));
+    };
+    auto issue_b = [&](int t) {
+        const int slot = b_slot(t);
+        const unsigned char *sb = gb + (int64_t)rotated(t) * stepb;
+        if (RAGGED && (kbeg + t + 1) * BK > p.K) {
+            const int k_left = p.K - (kbeg + t) * BK;
 #pragma unroll
-        for (int i = 0; i < LB; ++i) dl_load16(offb[i], sb, slot + C::A_BYTES + (uint32_t)(wave * LB + i) * 1024u);
+            for (int i = 0; i < LB; ++i) {
+                const int wl = wave * LB + i;
+                if (dl_chunk_k<BN, BKC>(wl, lane) < k_left) dl_load16(offb[i], sb, lds0 + (uint32_t)(slot + wl * 1024));
+                else *reinterpret_cast<u32x4 *>(smem + slot + wl * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+            }
+            return;
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) dl_load16(offb[i], sb, lds0 + (uint32_t)(slot + (wave * LB + i) * 1024));
     };
     bf16x8 fal[HM], fah[HM], fb0[NJ], fb1[NJ];
     auto read_a = [&](bf16x8(&fa)[HM], int t, int half) {
-        const unsigned char *sa = smem + (t % S) * C::STAGE_BYTES;
+        const unsigned char *sa = smem + a_slot(t);
 #pragma unroll
-        for (int i = 0; i < HM; ++i) fa[i] = dl_frag16<BM, AK>(sa, wm * C::WTM + (half * HM + i) * 16, lane);
+        for (int i = 0; i < HM; ++i) {
+            const int row = wm * C::WTM + (half * HM + i) * 16;
+            fa[i] = PAIRED ? dl_frag16_pair(sa, row, lane, t & 1) : dl_frag16<BM, AK>(sa, row, lane);
+        }
     };
     auto read_b = [&](bf16x8(&fb)[NJ], int t) {
-        const unsigned char *sb = smem + (t % S) * C::STAGE_BYTES + C::A_BYTES;
+        const unsigned char *sb = smem + b_slot(t);
 #pragma unroll
         for (int j = 0; j < NJ; ++j) fb[j] = dl_frag16<BN, BKC>(sb, wn * C::WTN + j * 16, lane);
     };
@@ -1207,16 +1273,32 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
             for (int j = 0; j < NJ; ++j)
                 acc.a[half * HM + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc.a[half * HM + i][j], 0, 0, 0);
     };
-    // `steady`: the caller knows that tile kt+S-1 exists (no refill test in the body)
-    auto step = [&](int kt, const bf16x8(&fbc)[NJ], bf16x8(&fbn)[NJ], bool last, bool steady) {
+    // Refill issued in step kt: B of K-step kt+S-1 into the slot freed by kt-1; A of K-step kt+S-1 likewise, or (PAIRED) half
+    // of the loads of the pair kt+S, kt+S+1 (kt even; the other half in step kt+1) into the slot freed by the pair kt-2, kt-1.
+    // Either way every step issues LA+LB loads per wave, A first, and (S-2)*(LA+LB) loads of later K-steps are in flight when
+    // everything that K-step kt+1 needs has landed -- provided all of them were issued in full (`exact`); otherwise
+    // everything is waited for.
+    // `steady`: the caller knows that every refill of this step exists (no test in the body); `even`: kt is even.
+    auto step = [&](int kt, const bf16x8(&fbc)[NJ], bf16x8(&fbn)[NJ], bool last, bool steady, bool even) {
         const bool refill = steady || kt + S - 1 < KT;
-        if (refill) issue(kt + S - 1);                                   // A
+        bool exact;
+        if (PAIRED) {
+            const int tp = (kt & ~1) + S;                                 // first K-step of the pair being fetched
+            if (steady || tp + 1 < KT) issue_a(tp, even ? 0 : 1);         // A
+            if (refill) issue_b(kt + S - 1);
+            exact = steady && (!RAGGED || (kbeg + (kt | 1) + S + 1) * BK <= p.K);
+        } else {
+            if (refill) {
+                issue_a(kt + S - 1, -1);                                  // A
+                issue_b(kt + S - 1);
+            }
+            exact = refill && (!RAGGED || (kbeg + kt + S) * BK <= p.K);
+        }
         read_a(fah, kt, 1);                                              // B
         mma(fal, fbc, 0);
         if (!last) {
-            // C: tile kt+1 must have landed, tiles kt+2 and kt+3 may be in flight.  The count is exact only when both issued
-            // all their loads: a tile that reaches past K issues fewer (zero-filled positions), then everything is waited for
-            if (refill && (!RAGGED || (kbeg + kt + S) * BK <= p.K)) {
+            // C: K-step kt+1 must have landed, the loads of kt+2 and kt+3 may be in flight
+            if (exact) {
                 asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
             } else {
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -1229,11 +1311,25 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     };
 
     if (KT > 0) {
-        // prologue: fill S-1 slots; only tile 0 has to have landed (loads retire in order)
+        // prologue: fill the ring; only K-step 0 has to have landed (loads retire in order)
+        bool exact;
+        if (PAIRED) {
+            issue_a(0, -1);
+            issue_b(0);
+            if (1 < KT) issue_b(1);
+            if (2 < KT) issue_a(2, -1);
+            if (2 < KT) issue_b(2);
+            exact = KT >= S && (!RAGGED || (kbeg + S) * BK <= p.K);      // B 1, A 2-3, B 2 all issued in full
+        } else {
 #pragma unroll
-        for (int t = 0; t < S - 1; ++t)
-            if (t < KT) issue(t);
-        if (KT >= S - 1 && (!RAGGED || (kbeg + S - 1) * BK <= p.K)) {
+            for (int t = 0; t < S - 1; ++t)
+                if (t < KT) {
+                    issue_a(t, -1);
+                    issue_b(t);
+                }
+            exact = KT >= S - 1 && (!RAGGED || (kbeg + S - 1) * BK <= p.K);
+        }
+        if (exact) {
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
         } else {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -1242,16 +1338,16 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
         read_a(fal, 0, 0);
         read_b(fb0, 0);
         int kt = 0;
-        for (; kt + S < KT; kt += 2) {            // both steps refill: branch-free body
-            step(kt, fb0, fb1, false, true);
-            step(kt + 1, fb1, fb0, false, true);
+        for (; kt + S + (PAIRED ? 1 : 0) < KT; kt += 2) {   // every refill of both steps exists: branch-free body
+            step(kt, fb0, fb1, false, true, true);
+            step(kt + 1, fb1, fb0, false, true, false);
         }
         for (; kt < KT - 2; kt += 2) {            // ring runs dry
-            step(kt, fb0, fb1, false, false);
-            step(kt + 1, fb1, fb0, false, false);
+            step(kt, fb0, fb1, false, false, true);
+            step(kt + 1, fb1, fb0, false, false, false);
         }
-        step(KT - 2, fb0, fb1, false, false);
-        step(KT - 1, fb1, fb0, true, false);
+        step(KT - 2, fb0, fb1, false, false, true);
+        step(KT - 1, fb1, fb0, true, false, false);
     }
     __syncthreads();  // every wave is done with the operand ring before the epilogue reuses it
 
