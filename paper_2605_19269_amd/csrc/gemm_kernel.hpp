@@ -1390,6 +1390,29 @@ __device__ __forceinline__ int dl_chunk_k_f8(int j, int lane)
     return ((lane & 3) ^ ((r >> 2) & 3)) * 16;
 }
 
+// A fetched for two K-steps at a time, as in the bf16 kernel: [256][128 B] tiles, chunk c (of 8) of row r at position
+// c ^ ((r >> 1) & 7), which is conflict-free for the 32-row fragment read (timed; c ^ (r & 7) costs a 2-way conflict here).
+__device__ __forceinline__ uint32_t dl_goffset_pair_f8(int j, int lane, int64_t ld, int valid)
+{
+    const int r = j * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    const int rg = r < valid ? r : valid - 1;
+    return (uint32_t)((int64_t)rg * ld + c * 16);
+}
+__device__ __forceinline__ int dl_chunk_k_pair_f8(int j, int lane)
+{
+    const int r = j * 8 + (lane >> 3);
+    return ((lane & 7) ^ ((r >> 1) & 7)) * 16;
+}
+// fragment of K-step hs (0 / 1) of the pair: bytes 64 hs + 32 (lane / 32) .. + 31 of row row_base + lane % 32
+__device__ __forceinline__ i32x8 dl_frag_pair_f8(const unsigned char *tile, int row_base, int lane, int hs)
+{
+    const int r = row_base + (lane & 31), c = hs * 4 + 2 * (lane >> 5), sw = (r >> 1) & 7;
+    const u32x4 lo = *reinterpret_cast<const u32x4 *>(tile + r * 128 + ((c ^ sw) << 4));
+    const u32x4 hi = *reinterpret_cast<const u32x4 *>(tile + r * 128 + (((c + 1) ^ sw) << 4));
+    return i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+}
+
 __device__ __forceinline__ i32x8 dl_frag_f8(const unsigned char *tile, int row_base, int lane)
 {
     const int r = row_base + (lane & 31), h = lane >> 5, sw = (r >> 2) & 3;
@@ -1404,10 +1427,15 @@ template <class C, int EPI, bool RAGGED>
 __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE))) void gemm_kernel_dl_f8(const GemmParams p)
 {
     constexpr int BM = C::BM, BN = C::BN, BKB = 64, FM = C::FM, FN = C::FN, S = C::STAGES, HM = FM / 2;
-    constexpr int LA = C::LA, LB = C::LB;
+    constexpr int LA = C::LA, LB = C::LB, LAP = 2 * LA;
     static_assert(FM % 2 == 0, "two row halves");
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[S * C::STAGE_BYTES];
-    __shared__ float red[2 * C::WGN * C::BM];
+    // LDS plan of the bf16 kernel with a K-contiguous A: three pair slots of A, four single-step slots of B, 160 KB; the
+    // epilogue stages through the first EPI_RING bytes and `red` follows them (inside B slots that are free by then).
+    constexpr int EPI_RING = S * C::STAGE_BYTES, RED_BYTES = 2 * C::WGN * C::BM * 4;
+    constexpr int A_REGION = 3 * 2 * C::A_BYTES, LDS_BYTES = A_REGION + S * C::B_BYTES;
+    static_assert(S == 4 && LDS_BYTES >= EPI_RING + RED_BYTES && LDS_BYTES <= 160 * 1024, "LDS plan");
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[LDS_BYTES];
+    float *red = reinterpret_cast<float *>(smem + EPI_RING);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1429,50 +1457,62 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 
     const int valid_m = RAGGED ? (p.M - m0 < BM ? p.M - m0 : BM) : BM;
     const int valid_n = RAGGED ? (p.N - n0 < BN ? p.N - n0 : BN) : BN;
-    uint32_t offa[LA], offb[LB];
+    uint32_t offa[LAP], offb[LB];
 #pragma unroll
-    for (int i = 0; i < LA; ++i) offa[i] = dl_goffset_f8<C>(wave * LA + i, lane, p.lda, valid_m);
+    for (int i = 0; i < LAP; ++i) offa[i] = dl_goffset_pair_f8(wave * LAP + i, lane, p.lda, valid_m);
 #pragma unroll
     for (int i = 0; i < LB; ++i) offb[i] = dl_goffset_f8<C>(wave * LB + i, lane, p.ldb, valid_n);
     const unsigned char *ga = reinterpret_cast<const unsigned char *>(p.A) + (int64_t)m0 * p.lda + (int64_t)kbeg * BKB;
     const unsigned char *gb = reinterpret_cast<const unsigned char *>(p.B) + (int64_t)n0 * p.ldb + (int64_t)kbeg * BKB;
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
 
-    auto issue = [&](int t) {
-        const uint32_t slot = lds0 + (uint32_t)(t % S) * C::STAGE_BYTES;
+    auto a_slot = [&](int t) { return ((t >> 1) % 3) * (2 * C::A_BYTES); };      // the pair that contains K-step t
+    auto b_slot = [&](int t) { return A_REGION + (t % S) * C::B_BYTES; };
+    // loads of A for the pair of K-steps t, t + 1 (t even): `part` 0 / 1 = first / second half of the wave's loads, -1 = all
+    auto issue_a = [&](int t, int part) {
+        const int slot = a_slot(t);
         const unsigned char *sa = ga + (int64_t)t * BKB;
-        const unsigned char *sb = gb + (int64_t)t * BKB;
-        if (RAGGED && (kbeg + t + 1) * BKB > p.K) {
-            // the tile reaches past K: a lane whose chunk lies past K stores zeros at its LDS position instead of fetching
+        const int i0 = part == 1 ? LAP / 2 : 0, i1 = part == 0 ? LAP / 2 : LAP;
+        if (RAGGED && (kbeg + t + 2) * BKB > p.K) {
+            // the pair reaches past K: a lane whose chunk lies past K stores zeros at its LDS position instead of fetching
             const int k_left = p.K - (kbeg + t) * BKB;
-            unsigned char *ls = smem + (t % S) * C::STAGE_BYTES;
 #pragma unroll
-            for (int i = 0; i < LA; ++i) {
-                const int wl = wave * LA + i;
-                if (dl_chunk_k_f8(wl, lane) < k_left) dl_load16(offa[i], sa, slot + (uint32_t)wl * 1024u);
-                else *reinterpret_cast<u32x4 *>(ls + wl * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
-            }
-#pragma unroll
-            for (int i = 0; i < LB; ++i) {
-                const int wl = wave * LB + i;
-                if (dl_chunk_k_f8(wl, lane) < k_left) dl_load16(offb[i], sb, slot + C::A_BYTES + (uint32_t)wl * 1024u);
-                else *reinterpret_cast<u32x4 *>(ls + C::A_BYTES + wl * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+            for (int i = 0; i < LAP; ++i) {
+                if (i < i0 || i >= i1) continue;
+                const int wl = wave * LAP + i;
+                if (dl_chunk_k_pair_f8(wl, lane) < k_left) dl_load16(offa[i], sa, lds0 + (uint32_t)(slot + wl * 1024));
+                else *reinterpret_cast<u32x4 *>(smem + slot + wl * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
             }
             return;
         }
 #pragma unroll
-        for (int i = 0; i < LA; ++i) dl_load16(offa[i], sa, slot + (uint32_t)(wave * LA + i) * 1024u);
+        for (int i = 0; i < LAP; ++i)
+            if (i >= i0 && i < i1) dl_load16(offa[i], sa, lds0 + (uint32_t)(slot + (wave * LAP + i) * 1024));
+    };
+    auto issue_b = [&](int t) {
+        const int slot = b_slot(t);
+        const unsigned char *sb = gb + (int64_t)t * BKB;
+        if (RAGGED && (kbeg + t + 1) * BKB > p.K) {
+            const int k_left = p.K - (kbeg + t) * BKB;
 #pragma unroll
-        for (int i = 0; i < LB; ++i) dl_load16(offb[i], sb, slot + C::A_BYTES + (uint32_t)(wave * LB + i) * 1024u);
+            for (int i = 0; i < LB; ++i) {
+                const int wl = wave * LB + i;
+                if (dl_chunk_k_f8(wl, lane) < k_left) dl_load16(offb[i], sb, lds0 + (uint32_t)(slot + wl * 1024));
+                else *reinterpret_cast<u32x4 *>(smem + slot + wl * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+            }
+            return;
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) dl_load16(offb[i], sb, lds0 + (uint32_t)(slot + (wave * LB + i) * 1024));
     };
     i32x8 fal[HM], fah[HM], fb0[FN], fb1[FN];
     auto read_a = [&](i32x8(&fa)[HM], int t, int half) {
-        const unsigned char *sa = smem + (t % S) * C::STAGE_BYTES;
+        const unsigned char *sa = smem + a_slot(t);
 #pragma unroll
-        for (int i = 0; i < HM; ++i) fa[i] = dl_frag_f8(sa, wm * C::WTM + (half * HM + i) * 32, lane);
+        for (int i = 0; i < HM; ++i) fa[i] = dl_frag_pair_f8(sa, wm * C::WTM + (half * HM + i) * 32, lane, t & 1);
     };
     auto read_b = [&](i32x8(&fb)[FN], int t) {
-        const unsigned char *sb = smem + (t % S) * C::STAGE_BYTES + C::A_BYTES;
+        const unsigned char *sb = smem + b_slot(t);
 #pragma unroll
         for (int j = 0; j < FN; ++j) fb[j] = dl_frag_f8(sb, wn * C::WTN + j * 32, lane);
     };
@@ -1484,14 +1524,16 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
                 acc.a[half * HM + i][j] =
                     __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j], fa[i], acc.a[half * HM + i][j], 0, 0, 0, 0, 0, 0);
     };
-    auto step = [&](int kt, const i32x8(&fbc)[FN], i32x8(&fbn)[FN], bool last) {
-        const bool refill = kt + S - 1 < KT;
-        if (refill) issue(kt + S - 1);                                   // A
+    // refills and waits as in the bf16 kernel with a paired A: every step issues LA + LB loads per wave, A first
+    auto step = [&](int kt, const i32x8(&fbc)[FN], i32x8(&fbn)[FN], bool last, bool steady, bool even) {
+        const int tp = (kt & ~1) + S;                                    // first K-step of the pair being fetched
+        if (steady || tp + 1 < KT) issue_a(tp, even ? 0 : 1);            // A
+        if (steady || kt + S - 1 < KT) issue_b(kt + S - 1);
+        const bool exact = steady && (!RAGGED || (kbeg + (kt | 1) + S + 1) * BKB <= p.K);
         read_a(fah, kt, 1);                                              // B
         mma(fal, fbc, 0);
         if (!last) {
-            // C: exact count only when tiles kt+2 and kt+3 issued all their loads (see the bf16 kernel)
-            if (refill && (!RAGGED || (kbeg + kt + S) * BKB <= p.K)) {
+            if (exact) {                                                 // C
                 asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
             } else {
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -1504,10 +1546,12 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     };
 
     if (KT > 0) {
-#pragma unroll
-        for (int t = 0; t < S - 1; ++t)
-            if (t < KT) issue(t);
-        if (KT >= S - 1 && (!RAGGED || (kbeg + S - 1) * BKB <= p.K)) {
+        issue_a(0, -1);
+        issue_b(0);
+        if (1 < KT) issue_b(1);
+        if (2 < KT) issue_a(2, -1);
+        if (2 < KT) issue_b(2);
+        if (KT >= S && (!RAGGED || (kbeg + S) * BKB <= p.K)) {
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
         } else {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -1516,12 +1560,17 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
         read_a(fal, 0, 0);
         read_b(fb0, 0);
         // two K-steps per trip, so that the two column-fragment buffers swap roles without copies
-        for (int kt = 0; kt < KT - 2; kt += 2) {
-            step(kt, fb0, fb1, false);
-            step(kt + 1, fb1, fb0, false);
+        int kt = 0;
+        for (; kt + S + 1 < KT; kt += 2) {        // every refill of both steps exists
+            step(kt, fb0, fb1, false, true, true);
+            step(kt + 1, fb1, fb0, false, true, false);
         }
-        step(KT - 2, fb0, fb1, false);
-        step(KT - 1, fb1, fb0, true);
+        for (; kt < KT - 2; kt += 2) {            // ring runs dry
+            step(kt, fb0, fb1, false, false, true);
+            step(kt + 1, fb1, fb0, false, false, false);
+        }
+        step(KT - 2, fb0, fb1, false, false, true);
+        step(KT - 1, fb1, fb0, true, false, false);
     }
     __syncthreads();  // every wave is done with the operand ring before the epilogue reuses it
 

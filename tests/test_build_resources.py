@@ -59,6 +59,6 @@ def test_spills_of_the_8bit_kernels(kernels):
         if mode == 4:
             # RMSNorm backward on the 32-row accumulator layout: the bounds-checked variant is far over the register
             # budget (correct, slow; no benchmark shape uses it)
-            assert r["spill"] <= (600 if ragged else 40), (name, r)
+            assert r["spill"] <= (800 if ragged else 40), (name, r)
         else:
             assert r["spill"] <= 24, (name, r)
