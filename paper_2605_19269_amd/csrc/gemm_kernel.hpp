@@ -1353,7 +1353,11 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 
     if (nsplit > 1 && !splitk_exchange<C>(acc, p, tile_id - p.split_from, split, nsplit, red, tid)) return;
 
-    run_epilogue<C, ACC, EPI, RAGGED, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
+    // a tile that lies wholly inside the matrix takes the epilogue without bounds checks
+    if (RAGGED && (m0 + BM > p.M || n0 + BN > p.N))
+        run_epilogue<C, ACC, EPI, true, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
+    else
+        run_epilogue<C, ACC, EPI, false, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
 }
 
 // ---------------------------------------------------------------------------------

@@ -46,7 +46,9 @@ def test_spills_stay_out_of_the_step_kernels(kernels):
     assert g[(0, 0, 3, 0)]["scratch"] == 0                      # weight gradient: fp32 accumulate
     assert g[(1, 1, 2, 0)]["spill"] <= 4                        # SwiGLU backward: four epilogue-only spills
     for key, r in g.items():
-        limit = 40 if key[2] == 4 else 20                       # RMSNorm backward holds two staged tiles and spills more
+        # RMSNorm backward holds two staged tiles and spills more; the ragged instances carry both the bounds-checked and
+        # the plain epilogue (interior tiles take the plain one)
+        limit = (72 if key[3] else 40) if key[2] == 4 else (40 if key[3] else 20)
         assert r["spill"] <= limit, (key, r)
 
 
