@@ -614,3 +614,22 @@ def test_both_operands_k_contiguous_long_k_whole_tiles(oracle):
     refdZ = oracle.gemm_swiglu_bwd(A2, Bt, Z, transB=True)[0]
     dZ.check_guards(); dZ.written()
     G.assert_bf16_close(G.host_f64(dZ.t), refdZ, "dZ")
+
+
+@pytest.mark.parametrize("transA,transB", LAYOUTS)
+@pytest.mark.parametrize("pad", [8, 40])
+def test_whole_tiles_with_padded_operand_pitches(oracle, transA, transB, pad):
+    """Whole-tile kernels on operands whose rows do not start on 128-byte boundaries (pitch = width + pad elements)."""
+    M, N, K = 512, 512, 256
+    g = rng(300 + pad)
+    a_shape, b_shape = ((K, M) if transA else (M, K)), ((N, K) if transB else (K, N))
+    Ap = synth.normal_bf16(g, (a_shape[0], a_shape[1] + pad), 1.0)
+    Bp = synth.normal_bf16(g, (b_shape[0], b_shape[1] + pad), 0.3)
+    dA, dB = G.dev_bf16(Ap)[:, :a_shape[1]], G.dev_bf16(Bp)[:, :b_shape[1]]
+    out = G.Guarded(M, N, torch.bfloat16)
+    coda.coda_gemm(dA, dB, [coda.store(out.t)], transA=transA, transB=transB)
+    torch.cuda.synchronize()
+    ref = oracle.gemm_rowscale(np.ascontiguousarray(Ap[:, :a_shape[1]]), np.ascontiguousarray(Bp[:, :b_shape[1]]),
+                               transA=transA, transB=transB)
+    out.check_guards(); out.written()
+    G.assert_bf16_close(G.host_f64(out.t), ref, "padded pitches")
