@@ -633,3 +633,19 @@ def test_whole_tiles_with_padded_operand_pitches(oracle, transA, transB, pad):
                                transA=transA, transB=transB)
     out.check_guards(); out.written()
     G.assert_bf16_close(G.host_f64(out.t), ref, "padded pitches")
+
+
+@pytest.mark.parametrize("K", [64, 128, 192, 256, 320, 384, 448, 512, 640])
+@pytest.mark.parametrize("transA,transB", LAYOUTS)
+def test_whole_tiles_every_short_k(oracle, K, transA, transB):
+    """One whole tile per workgroup, K-step counts 2 .. 20: prologue only, ring never full, first steady trips, run-dry
+    steps (and with a K-contiguous A: pairs of K-steps in a ring of three pair slots)."""
+    M, N = 256, 512
+    g = rng(400 + K)
+    A, B = operands(g, M, N, K, transA, transB)
+    out = G.Guarded(M, N, torch.bfloat16)
+    coda.coda_gemm(G.dev_bf16(A), G.dev_bf16(B), [coda.store(out.t)], transA=transA, transB=transB)
+    torch.cuda.synchronize()
+    ref = oracle.gemm_rowscale(A, B, transA=transA, transB=transB)
+    out.check_guards(); out.written()
+    G.assert_bf16_close(G.host_f64(out.t), ref, "K = %d" % K)
