@@ -55,7 +55,8 @@ def test_every_finite_code_is_decoded_as_e4m3(oracle):
 
 
 # without a workspace | with one, on shapes the 8-bit plan splits 4-way and 2-way
-@pytest.mark.parametrize("M,N,K,split", [(m, n, k, False) for m, n, k in SHAPES] + [(256, 256, 8192, True), (512, 512, 4096, True), (504, 264, 4304, True)] + [(8, 8, 16, False), (1, 256, 64, False)])
+@pytest.mark.parametrize("M,N,K,split", [(m, n, k, False) for m, n, k in SHAPES] + [(256, 256, 8192, True), (512, 512, 4096, True), (504, 264, 4304, True)] + [(8, 8, 16, False), (1, 256, 64, False)]
+                         + [(256, 256, k, False) for k in (256, 512, 640, 768)])   # K-step counts 4, 8, 10, 12: ring fill and run-dry
 def test_f8_linear_program(oracle, M, N, K, split):
     g = np.random.Generator(np.random.PCG64(1100 + M + K))
     A8, B8, A16, B16 = operands(oracle, g, M, N, K)
