@@ -1362,15 +1362,16 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 
 // ---------------------------------------------------------------------------------
 // 8-bit operands (OCP E4M3), both stored with the contraction index contiguous: A [M x K], B [N x K] bytes.
-// One K-step is 64 elements = 64 bytes per row, so operand tiles, ring stages and the direct-to-LDS fill have the byte
-// geometry of the bf16 kernel's 32-element step (the chunk swizzle is its own: row bits 2..3 folded into the chunk index,
-// which is bank-conflict-free for the 32-row fragment read).  v_mfma_f32_32x32x64_f8f6f4 takes 32 bytes
+// One K-step is 64 elements = 64 bytes per row, so operand tiles, LDS slots and the direct-to-LDS fill have the byte
+// geometry of the bf16 kernel's 32-element step with a K-contiguous A: A in pair slots (128-byte rows), B in single-step
+// slots (whose chunk swizzle is its own: row bits 2..3 folded into the chunk index, which is bank-conflict-free for the
+// 32-row fragment read).  v_mfma_f32_32x32x64_f8f6f4 takes 32 bytes
 // per lane and operand: lane (row = lane % 32, half = lane / 32) holds bytes 32*half .. 32*half+31 of its row's 64;
 // both operands are loaded with the same rule, so every product pairs bytes of equal k.  The accumulator layout is
 // that of v_mfma_f32_32x32x16_bf16 (Acc32), and the epilogues are shared.
 // Per K-step (one MFMA per 32x32 block) the work is split in two halves of the wave's rows, so that the
 // fragment reads of one half run under the MFMAs of the other, with the workgroup barrier between them:
-//   A  issue loads of tile kt+S-1
+//   A  issue loads: B of tile kt+S-1, half of A's loads of the pair kt+S, kt+S+1 (kt even) / the other half (kt odd)
 //   B  read the row fragments of the upper half of tile kt; MFMAs of the lower half
 //   C  wait for this wave's loads of tile kt+1; barrier
 //   D  read the lower-half row fragments and the column fragments of tile kt+1; MFMAs of the upper half
