@@ -172,6 +172,10 @@ typedef struct coda_epi_op {
  * multiple of 8; and M a multiple of 8 when A is used transposed.  No other
  * divisibility is required (edge tiles are predicated).
  *
+ * Reproducibility: the order of the fp32 additions behind an output element depends only on the shapes, layouts and the
+ * element's position, never on timing; with CODA_REDUCE_PARTIALS every output of a call is bitwise identical from call
+ * to call (CODA_REDUCE_ATOMIC sums may differ in their last bits).
+ *
  * 8-bit operands: A and B may both be CODA_F8E4M3 (ld in elements = bytes, a multiple of 16).  The contraction
  * runs on the fp8 matrix cores with fp32 accumulation of the exact products, and every epilogue program
  * above applies unchanged (outputs stay bf16 / fp32; quantisation scales of the operands are the caller's
