@@ -605,6 +605,12 @@ def test_both_operands_k_contiguous_long_k_whole_tiles(oracle):
     Y.check_guards(); Y.written()
     G.assert_bf16_close(G.host_f64(Y.t), refD, "residual output")
     G.assert_sumsq_close(G.host_f64(ss), refss, "row sum of squares")
+    # the K order of a tile depends on its position only: a second launch gives the same bits
+    Y2 = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    part2 = torch.empty_like(part)
+    coda.coda_gemm(dA, dB, [coda.add_tile(dC), coda.row_sumsq(part2), coda.store(Y2)], transB=True)
+    torch.cuda.synchronize()
+    assert torch.equal(Y2.view(torch.int16), Y.t.contiguous().view(torch.int16)) and torch.equal(part2.view(torch.int32), part.view(torch.int32))
     A2 = synth.normal_bf16(g, (M, K), 1e-2)
     Z = synth.normal_bf16(g, (M, 2 * N), 1.0)
     dZ = G.Guarded(M, 2 * N, torch.bfloat16)
