@@ -1126,7 +1126,8 @@ __device__ __forceinline__ bf16x8 dl_frag16(const unsigned char *tile, int row_b
 // MFMAs of the other, with the workgroup barrier between them:
 //   A  issue loads of tile kt+S-1 into the slot freed by tile kt-1 (a K-contiguous A operand: half of the wave's loads
 //      of the PAIR of K-steps kt+S, kt+S+1 for even kt / the other half for odd kt, into the slot freed by the pair that
-//      ended with kt-1: 128-byte rows, whole cache lines per request)
+//      ended with kt-1: 128-byte rows, whole cache lines per request; a K-contiguous B beside it is fetched in pairs too,
+//      the whole pair kt+3, kt+4 in odd steps right behind the barrier of step C)
 //   B  read the row fragments of the upper half of tile kt; MFMAs of the lower half (fragments already in VGPRs)
 //   C  wait until this wave's loads of tile kt+1 have landed; workgroup barrier
 //   D  read the lower-half row fragments and the column fragments of tile kt+1; MFMAs of the upper half
@@ -1145,13 +1146,14 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     constexpr int NI = ACC::NB, NJ = ACC::NU, HM = NI / 2;
     constexpr int LA = C::LA, LB = C::LB;
     static_assert(NI % 2 == 0, "two row halves");
-    // PAIRED (A K-contiguous): three pair slots of A (two K-steps each) followed by four single-step slots of B, 160 KB;
-    // otherwise four slots of [A | B].  The epilogue stages through the first EPI_RING bytes either way; `red` (row-reduction
+    // PAIRED (A K-contiguous): three pair slots of A (two K-steps each) followed by four single-step slots of B -- or, when
+    // B is K-contiguous as well (PAIRB), by two pair slots of B -- 160 KB; otherwise four slots of [A | B].  The epilogue stages through the first EPI_RING bytes either way; `red` (row-reduction
     // exchange; second half: sum-exp of the log-sum-exp partials) follows them and, when PAIRED, lies inside the B slots, which
     // are free once the mainloop is over.
     constexpr bool PAIRED = AK;
     constexpr int EPI_RING = S * C::STAGE_BYTES, RED_BYTES = 2 * C::WGN * C::BM * 4;
     constexpr int A_REGION = PAIRED ? 3 * 2 * C::A_BYTES : 0;
+    constexpr bool PAIRB = AK && BKC;    // B K-contiguous as well: two pair slots of B instead of four single-step slots
     constexpr int LDS_BYTES = PAIRED ? A_REGION + S * C::B_BYTES : EPI_RING + RED_BYTES;
     static_assert(S == 4 && LDS_BYTES >= EPI_RING + RED_BYTES && LDS_BYTES <= 160 * 1024, "LDS plan");
     __shared__ __attribute__((aligned(1024))) unsigned char smem[LDS_BYTES];
@@ -1180,7 +1182,8 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     const int valid_n = RAGGED ? (p.N - n0 < BN ? p.N - n0 : BN) : BN;
     // A: LA wave-loads per wave and K-step, or (PAIRED) LAP per wave and pair of K-steps
     constexpr int LAP = 2 * LA;
-    uint32_t offa[PAIRED ? LAP : LA], offb[LB];
+    constexpr int LBP = 2 * LB;
+    uint32_t offa[PAIRED ? LAP : LA], offb[PAIRB ? LBP : LB];
     if (PAIRED) {
 #pragma unroll
         for (int i = 0; i < LAP; ++i) offa[i] = dl_goffset_pair<C, BM>(wave * LAP + i, lane, p.lda, valid_m);
@@ -1188,8 +1191,13 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 #pragma unroll
         for (int i = 0; i < LA; ++i) offa[i] = dl_goffset<C, BM, AK>(wave * LA + i, lane, p.lda, valid_m);
     }
+    if (PAIRB) {
 #pragma unroll
-    for (int i = 0; i < LB; ++i) offb[i] = dl_goffset<C, BN, BKC>(wave * LB + i, lane, p.ldb, valid_n);
+        for (int i = 0; i < LBP; ++i) offb[i] = dl_goffset_pair<C, BN>(wave * LBP + i, lane, p.ldb, valid_n);
+    } else {
+#pragma unroll
+        for (int i = 0; i < LB; ++i) offb[i] = dl_goffset<C, BN, BKC>(wave * LB + i, lane, p.ldb, valid_n);
+    }
     // scalar bases of the tile's first element; advance by one K-step per tile
     const int64_t stepa = AK ? (int64_t)BK * 2 : (int64_t)BK * p.lda * 2;
     const int64_t stepb = BKC ? (int64_t)BK * 2 : (int64_t)BK * p.ldb * 2;
@@ -1210,7 +1218,10 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     };
     // LDS byte offsets of the slot that holds K-step t of A (PAIRED: the pair that contains t) and of B
     auto a_slot = [&](int t) { return PAIRED ? ((t >> 1) % 3) * (2 * C::A_BYTES) : (t % S) * C::STAGE_BYTES; };
-    auto b_slot = [&](int t) { return PAIRED ? A_REGION + (t % S) * C::B_BYTES : (t % S) * C::STAGE_BYTES + C::A_BYTES; };
+    auto b_slot = [&](int t) {
+        return PAIRB ? A_REGION + ((t >> 1) & 1) * (2 * C::B_BYTES)
+                     : (PAIRED ? A_REGION + (t % S) * C::B_BYTES : (t % S) * C::STAGE_BYTES + C::A_BYTES);
+    };
     // loads of A for K-step t (PAIRED: for K-steps t and t + 1, t even).  A K-step (pair) that reaches past K: a lane whose
     // chunk lies past K stores zeros at its LDS position instead of fetching.
     // PAIRED: `part` 0 / 1 issues the first / second half of the wave's loads of the pair, so that every K-step issues the
@@ -1236,21 +1247,24 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
         for (int i = 0; i < L; ++i)
             if (i >= i0 && i < i1) dl_load16(offa[i], sa, lds0 + (uint32_t)(slot + (wave * L + i) * 1024));
     };
+    // B of K-step t (PAIRB: of the pair t, t + 1, t even)
     auto issue_b = [&](int t) {
+        constexpr int L = PAIRB ? LBP : LB, SPAN = PAIRB ? 2 : 1;
         const int slot = b_slot(t);
         const unsigned char *sb = gb + (int64_t)rotated(t) * stepb;
-        if (RAGGED && (kbeg + t + 1) * BK > p.K) {
+        if (RAGGED && (kbeg + t + SPAN) * BK > p.K) {
             const int k_left = p.K - (kbeg + t) * BK;
 #pragma unroll
-            for (int i = 0; i < LB; ++i) {
-                const int wl = wave * LB + i;
-                if (dl_chunk_k<BN, BKC>(wl, lane) < k_left) dl_load16(offb[i], sb, lds0 + (uint32_t)(slot + wl * 1024));
+            for (int i = 0; i < L; ++i) {
+                const int wl = wave * L + i;
+                const int ck = PAIRB ? dl_chunk_k_pair(wl, lane) : dl_chunk_k<BN, BKC>(wl, lane);
+                if (ck < k_left) dl_load16(offb[i], sb, lds0 + (uint32_t)(slot + wl * 1024));
                 else *reinterpret_cast<u32x4 *>(smem + slot + wl * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
             }
             return;
         }
 #pragma unroll
-        for (int i = 0; i < LB; ++i) dl_load16(offb[i], sb, lds0 + (uint32_t)(slot + (wave * LB + i) * 1024));
+        for (int i = 0; i < L; ++i) dl_load16(offb[i], sb, lds0 + (uint32_t)(slot + (wave * L + i) * 1024));
     };
     bf16x8 fal[HM], fah[HM], fb0[NJ], fb1[NJ];
     auto read_a = [&](bf16x8(&fa)[HM], int t, int half) {
@@ -1264,7 +1278,10 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     auto read_b = [&](bf16x8(&fb)[NJ], int t) {
         const unsigned char *sb = smem + b_slot(t);
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) fb[j] = dl_frag16<BN, BKC>(sb, wn * C::WTN + j * 16, lane);
+        for (int j = 0; j < NJ; ++j) {
+            const int col = wn * C::WTN + j * 16;
+            fb[j] = PAIRB ? dl_frag16_pair(sb, col, lane, t & 1) : dl_frag16<BN, BKC>(sb, col, lane);
+        }
     };
     auto mma = [&](const bf16x8(&fa)[HM], const bf16x8(&fb)[NJ], int half) {
 #pragma unroll
@@ -1282,7 +1299,14 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     auto step = [&](int kt, const bf16x8(&fbc)[NJ], bf16x8(&fbn)[NJ], bool last, bool steady, bool even) {
         const bool refill = steady || kt + S - 1 < KT;
         bool exact;
-        if (PAIRED) {
+        if (PAIRB) {
+            // B's pair kt+3, kt+4 is issued in odd steps only, behind the barrier (part D): its slot held the pair that
+            // ended with K-step kt, read for the last time in part D of step kt-1.  Two loads per step before the waits;
+            // even steps need no wait at all (both operands of kt+1 are in the pairs already in use)
+            const int tp = (kt & ~1) + S;
+            if (steady || tp + 1 < KT) issue_a(tp, even ? 0 : 1);         // A
+            exact = steady && (!RAGGED || (kbeg + (kt | 1) + S + 1) * BK <= p.K);
+        } else if (PAIRED) {
             const int tp = (kt & ~1) + S;                                 // first K-step of the pair being fetched
             if (steady || tp + 1 < KT) issue_a(tp, even ? 0 : 1);         // A
             if (refill) issue_b(kt + S - 1);
@@ -1298,12 +1322,21 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
         mma(fal, fbc, 0);
         if (!last) {
             // C: K-step kt+1 must have landed, the loads of kt+2 and kt+3 may be in flight
-            if (exact) {
+            if (PAIRB) {
+                if (!even) {
+                    if (exact) {
+                        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LA) : "memory");   // the two halves of A's newest pair
+                    } else {
+                        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    }
+                }
+            } else if (exact) {
                 asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
             } else {
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             }
             __syncthreads();
+            if (PAIRB && !even && (steady || kt + S < KT)) issue_b(kt + S - 1);
             read_a(fal, kt + 1, 0);                                      // D
             read_b(fbn, kt + 1);
         }
@@ -1313,7 +1346,13 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     if (KT > 0) {
         // prologue: fill the ring; only K-step 0 has to have landed (loads retire in order)
         bool exact;
-        if (PAIRED) {
+        if (PAIRB) {
+            issue_a(0, -1);
+            issue_b(0);
+            if (2 < KT) issue_a(2, -1);
+            if (2 < KT) issue_b(2);
+            exact = KT >= S && (!RAGGED || (kbeg + S) * BK <= p.K);      // A 2-3 and B 2-3 issued in full: (S-2)*(LA+LB) loads
+        } else if (PAIRED) {
             issue_a(0, -1);
             issue_b(0);
             if (1 < KT) issue_b(1);
