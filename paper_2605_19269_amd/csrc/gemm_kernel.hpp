@@ -1402,40 +1402,24 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 // ---------------------------------------------------------------------------------
 // 8-bit operands (OCP E4M3), both stored with the contraction index contiguous: A [M x K], B [N x K] bytes.
 // One K-step is 64 elements = 64 bytes per row, so operand tiles, LDS slots and the direct-to-LDS fill have the byte
-// geometry of the bf16 kernel's 32-element step with a K-contiguous A: A in pair slots (128-byte rows), B in single-step
-// slots (whose chunk swizzle is its own: row bits 2..3 folded into the chunk index, which is bank-conflict-free for the
-// 32-row fragment read).  v_mfma_f32_32x32x64_f8f6f4 takes 32 bytes
+// geometry of the bf16 A*B^T kernel's 32-element step: both operands in pair slots (128-byte rows).
+// v_mfma_f32_32x32x64_f8f6f4 takes 32 bytes
 // per lane and operand: lane (row = lane % 32, half = lane / 32) holds bytes 32*half .. 32*half+31 of its row's 64;
 // both operands are loaded with the same rule, so every product pairs bytes of equal k.  The accumulator layout is
 // that of v_mfma_f32_32x32x16_bf16 (Acc32), and the epilogues are shared.
 // Per K-step (one MFMA per 32x32 block) the work is split in two halves of the wave's rows, so that the
 // fragment reads of one half run under the MFMAs of the other, with the workgroup barrier between them:
-//   A  issue loads: B of tile kt+S-1, half of A's loads of the pair kt+S, kt+S+1 (kt even) / the other half (kt odd)
+//   A  issue half of A's loads of the pair kt+S, kt+S+1 (kt even) / the other half (kt odd); B's pair kt+3, kt+4 follows
+//      behind the barrier of odd steps
 //   B  read the row fragments of the upper half of tile kt; MFMAs of the lower half
 //   C  wait for this wave's loads of tile kt+1; barrier
 //   D  read the lower-half row fragments and the column fragments of tile kt+1; MFMAs of the upper half
 // ---------------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 
-// `valid`: rows of the operand tile that exist; positions past it fetch the last existing row again (see dl_goffset).
-template <class C>
-__device__ __forceinline__ uint32_t dl_goffset_f8(int j, int lane, int64_t ld, int valid)
-{
-    const int r = j * 16 + (lane >> 2);
-    const int c = (lane & 3) ^ ((r >> 2) & 3);
-    const int rg = r < valid ? r : valid - 1;
-    return (uint32_t)((int64_t)rg * ld + c * 16);
-}
-
-// First contraction index, within the 64-wide operand tile, of the 16-byte chunk that lane `lane` of wave-load `j` fetches.
-__device__ __forceinline__ int dl_chunk_k_f8(int j, int lane)
-{
-    const int r = j * 16 + (lane >> 2);
-    return ((lane & 3) ^ ((r >> 2) & 3)) * 16;
-}
-
-// A fetched for two K-steps at a time, as in the bf16 kernel: [256][128 B] tiles, chunk c (of 8) of row r at position
-// c ^ ((r >> 1) & 7), which is conflict-free for the 32-row fragment read (timed; c ^ (r & 7) costs a 2-way conflict here).
+// Both operands are fetched for two K-steps at a time, as in the bf16 A*B^T kernel: [256][128 B] tiles, chunk c (of 8) of
+// row r at position c ^ ((r >> 1) & 7), which is conflict-free for the 32-row fragment read (timed; c ^ (r & 7) costs a
+// 2-way conflict here).  `valid`: rows of the operand tile that exist; positions past it fetch the last existing row again.
 __device__ __forceinline__ uint32_t dl_goffset_pair_f8(int j, int lane, int64_t ld, int valid)
 {
     const int r = j * 8 + (lane >> 3);
@@ -1443,6 +1427,7 @@ __device__ __forceinline__ uint32_t dl_goffset_pair_f8(int j, int lane, int64_t 
     const int rg = r < valid ? r : valid - 1;
     return (uint32_t)((int64_t)rg * ld + c * 16);
 }
+// first contraction index, within the 128-wide pair, of the 16-byte chunk that lane `lane` of wave-load `j` fetches
 __device__ __forceinline__ int dl_chunk_k_pair_f8(int j, int lane)
 {
     const int r = j * 8 + (lane >> 3);
@@ -1457,24 +1442,16 @@ __device__ __forceinline__ i32x8 dl_frag_pair_f8(const unsigned char *tile, int 
     return i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
 }
 
-__device__ __forceinline__ i32x8 dl_frag_f8(const unsigned char *tile, int row_base, int lane)
-{
-    const int r = row_base + (lane & 31), h = lane >> 5, sw = (r >> 2) & 3;
-    const u32x4 lo = *reinterpret_cast<const u32x4 *>(tile + r * 64 + (((2 * h) ^ sw) << 4));
-    const u32x4 hi = *reinterpret_cast<const u32x4 *>(tile + r * 64 + (((2 * h + 1) ^ sw) << 4));
-    return i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
-}
-
 // RAGGED as in the bf16 kernel: clamped fetches and the bounds-checked epilogue on the edges of M and N; K (a multiple of
 // 16) is rounded up to whole pairs of K-steps, with zeros stored at the positions past it.
 template <class C, int EPI, bool RAGGED>
 __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE))) void gemm_kernel_dl_f8(const GemmParams p)
 {
     constexpr int BM = C::BM, BN = C::BN, BKB = 64, FM = C::FM, FN = C::FN, S = C::STAGES, HM = FM / 2;
-    constexpr int LA = C::LA, LB = C::LB, LAP = 2 * LA;
+    constexpr int LA = C::LA, LB = C::LB, LAP = 2 * LA, LBP = 2 * LB;
     static_assert(FM % 2 == 0, "two row halves");
-    // LDS plan of the bf16 kernel with a K-contiguous A: three pair slots of A, four single-step slots of B, 160 KB; the
-    // epilogue stages through the first EPI_RING bytes and `red` follows them (inside B slots that are free by then).
+    // LDS plan of the bf16 A*B^T kernel: three pair slots of A, two pair slots of B, 160 KB; the epilogue stages through
+    // the first EPI_RING bytes and `red` follows them (inside B slots that are free by then).
     constexpr int EPI_RING = S * C::STAGE_BYTES, RED_BYTES = 2 * C::WGN * C::BM * 4;
     constexpr int A_REGION = 3 * 2 * C::A_BYTES, LDS_BYTES = A_REGION + S * C::B_BYTES;
     static_assert(S == 4 && LDS_BYTES >= EPI_RING + RED_BYTES && LDS_BYTES <= 160 * 1024, "LDS plan");
@@ -1501,17 +1478,17 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 
     const int valid_m = RAGGED ? (p.M - m0 < BM ? p.M - m0 : BM) : BM;
     const int valid_n = RAGGED ? (p.N - n0 < BN ? p.N - n0 : BN) : BN;
-    uint32_t offa[LAP], offb[LB];
+    uint32_t offa[LAP], offb[LBP];
 #pragma unroll
     for (int i = 0; i < LAP; ++i) offa[i] = dl_goffset_pair_f8(wave * LAP + i, lane, p.lda, valid_m);
 #pragma unroll
-    for (int i = 0; i < LB; ++i) offb[i] = dl_goffset_f8<C>(wave * LB + i, lane, p.ldb, valid_n);
+    for (int i = 0; i < LBP; ++i) offb[i] = dl_goffset_pair_f8(wave * LBP + i, lane, p.ldb, valid_n);
     const unsigned char *ga = reinterpret_cast<const unsigned char *>(p.A) + (int64_t)m0 * p.lda + (int64_t)kbeg * BKB;
     const unsigned char *gb = reinterpret_cast<const unsigned char *>(p.B) + (int64_t)n0 * p.ldb + (int64_t)kbeg * BKB;
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
 
     auto a_slot = [&](int t) { return ((t >> 1) % 3) * (2 * C::A_BYTES); };      // the pair that contains K-step t
-    auto b_slot = [&](int t) { return A_REGION + (t % S) * C::B_BYTES; };
+    auto b_slot = [&](int t) { return A_REGION + ((t >> 1) & 1) * (2 * C::B_BYTES); };   // the pair that contains K-step t
     // loads of A for the pair of K-steps t, t + 1 (t even): `part` 0 / 1 = first / second half of the wave's loads, -1 = all
     auto issue_a = [&](int t, int part) {
         const int slot = a_slot(t);
@@ -1533,21 +1510,22 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
         for (int i = 0; i < LAP; ++i)
             if (i >= i0 && i < i1) dl_load16(offa[i], sa, lds0 + (uint32_t)(slot + (wave * LAP + i) * 1024));
     };
+    // loads of B for the pair of K-steps t, t + 1 (t even)
     auto issue_b = [&](int t) {
         const int slot = b_slot(t);
         const unsigned char *sb = gb + (int64_t)t * BKB;
-        if (RAGGED && (kbeg + t + 1) * BKB > p.K) {
+        if (RAGGED && (kbeg + t + 2) * BKB > p.K) {
             const int k_left = p.K - (kbeg + t) * BKB;
 #pragma unroll
-            for (int i = 0; i < LB; ++i) {
-                const int wl = wave * LB + i;
-                if (dl_chunk_k_f8(wl, lane) < k_left) dl_load16(offb[i], sb, lds0 + (uint32_t)(slot + wl * 1024));
+            for (int i = 0; i < LBP; ++i) {
+                const int wl = wave * LBP + i;
+                if (dl_chunk_k_pair_f8(wl, lane) < k_left) dl_load16(offb[i], sb, lds0 + (uint32_t)(slot + wl * 1024));
                 else *reinterpret_cast<u32x4 *>(smem + slot + wl * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
             }
             return;
         }
 #pragma unroll
-        for (int i = 0; i < LB; ++i) dl_load16(offb[i], sb, lds0 + (uint32_t)(slot + (wave * LB + i) * 1024));
+        for (int i = 0; i < LBP; ++i) dl_load16(offb[i], sb, lds0 + (uint32_t)(slot + (wave * LBP + i) * 1024));
     };
     i32x8 fal[HM], fah[HM], fb0[FN], fb1[FN];
     auto read_a = [&](i32x8(&fa)[HM], int t, int half) {
@@ -1558,7 +1536,7 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     auto read_b = [&](i32x8(&fb)[FN], int t) {
         const unsigned char *sb = smem + b_slot(t);
 #pragma unroll
-        for (int j = 0; j < FN; ++j) fb[j] = dl_frag_f8(sb, wn * C::WTN + j * 32, lane);
+        for (int j = 0; j < FN; ++j) fb[j] = dl_frag_pair_f8(sb, wn * C::WTN + j * 32, lane, t & 1);
     };
     auto mma = [&](const i32x8(&fa)[HM], const i32x8(&fb)[FN], int half) {
 #pragma unroll
@@ -1568,21 +1546,24 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
                 acc.a[half * HM + i][j] =
                     __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j], fa[i], acc.a[half * HM + i][j], 0, 0, 0, 0, 0, 0);
     };
-    // refills and waits as in the bf16 kernel with a paired A: every step issues LA + LB loads per wave, A first
+    // refills and waits as in the bf16 A*B^T kernel: half of A's pair kt+S, kt+S+1 before the waits of every step, B's whole
+    // pair kt+3, kt+4 behind the barrier of every odd step; only odd steps wait, for all but A's newest pair
     auto step = [&](int kt, const i32x8(&fbc)[FN], i32x8(&fbn)[FN], bool last, bool steady, bool even) {
         const int tp = (kt & ~1) + S;                                    // first K-step of the pair being fetched
         if (steady || tp + 1 < KT) issue_a(tp, even ? 0 : 1);            // A
-        if (steady || kt + S - 1 < KT) issue_b(kt + S - 1);
         const bool exact = steady && (!RAGGED || (kbeg + (kt | 1) + S + 1) * BKB <= p.K);
         read_a(fah, kt, 1);                                              // B
         mma(fal, fbc, 0);
         if (!last) {
-            if (exact) {                                                 // C
-                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
-            } else {
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (!even) {                                                 // C
+                if (exact) {
+                    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LA) : "memory");
+                } else {
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                }
             }
             __syncthreads();
+            if (!even && (steady || kt + S < KT)) issue_b(kt + S - 1);
             read_a(fal, kt + 1, 0);                                      // D
             read_b(fbn, kt + 1);
         }
@@ -1592,7 +1573,6 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     if (KT > 0) {
         issue_a(0, -1);
         issue_b(0);
-        if (1 < KT) issue_b(1);
         if (2 < KT) issue_a(2, -1);
         if (2 < KT) issue_b(2);
         if (KT >= S && (!RAGGED || (kbeg + S) * BKB <= p.K)) {
