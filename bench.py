@@ -29,7 +29,7 @@ PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 FLO
 # Bytes per launch of the dominant kernel (up-projection) crossing the L2 -> fabric boundary, measured with
 # rocprofv3 --pmc: FETCH_SIZE 393614 KiB x 2.0 (calibration factor from a plain copy) + WRITE_SIZE 131076 KiB x 1.0;
 # see profiles/gemm_epilogue_llama1b_mlp_block_hbm_traffic.md.  Algorithmic bytes are 234.9e6.
-MEASURED_TRAFFIC_BYTES = int(393591 * 1024 * 2.0 + 131163 * 1024)
+MEASURED_TRAFFIC_BYTES = int(393597 * 1024 * 2.0 + 131330 * 1024)
 
 
 def main():
