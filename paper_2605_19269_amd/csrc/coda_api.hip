@@ -377,8 +377,10 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
 
 size_t coda_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, const coda_epi_op *, int32_t)
 {
-    if (M < 0 || N < 0 || K < 0 || M > INT32_MAX - 256 || N > INT32_MAX / 2 || K > INT32_MAX - 64) return 0;
-    return splitk_bytes(plan_splitk(M, N, K));
+    if (M < 0 || N < 0 || K < 0 || M > INT32_MAX - 256 || N > INT32_MAX / 2 || K > INT32_MAX - 128) return 0;
+    // the plan depends on the operand width (an 8-bit K-step covers twice the elements): report what covers both
+    const size_t b16 = splitk_bytes(plan_splitk(M, N, K, false)), b8 = splitk_bytes(plan_splitk(M, N, K, true));
+    return b16 > b8 ? b16 : b8;
 }
 
 int64_t coda_row_partial_blocks(int64_t N)

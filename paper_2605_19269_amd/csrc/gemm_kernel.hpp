@@ -113,7 +113,7 @@ __device__ __forceinline__ float fast_sigmoid(float g)
 // range in column-major order inside groups of GROUP_M tile rows, so the tiles
 // resident on one XCD at a time form a compact patch that re-uses A and B panels.
 // ---------------------------------------------------------------------------------
-__device__ __forceinline__ void tile_coords(int bid, int nb, int tiles_m, int tiles_n, int &tm, int &tn)
+__device__ __host__ __forceinline__ void tile_coords(int bid, int nb, int tiles_m, int tiles_n, int &tm, int &tn)
 {
     constexpr int XCDS = 8, GROUP_M = 8;
     const int x = bid % XCDS, q = bid / XCDS;
@@ -1028,26 +1028,34 @@ __device__ __forceinline__ bf16x8 dl_frag16_pair(const unsigned char *tile, int 
 
 __device__ __forceinline__ void dl_load16(uint32_t voff, const void *sbase, uint32_t lds_addr)
 {
-    // M0 carries the wave-uniform LDS destination; one wait state between the M0 write and its use.
+    // M0 carries the wave-uniform LDS destination; one wait state between the M0 write and its use.  M0 is declared
+    // clobbered, so the compiler never assumes that a value of its own survives this statement.
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
                  : "v"(voff), "s"(sbase), "s"(lds_addr)
-                 : "memory");
+                 : "memory", "m0");
 }
 
-// Virtual workgroup -> (tile, part of K, parts of this tile): tiles below split_from are whole, the others are shared
-// by `splitk` workgroups each.  The grid has split_from + (tiles - split_from) * splitk workgroups.
-__device__ __forceinline__ void locate_workgroup(const GemmParams &p, int bid, int &tile_id, int &split, int &nsplit)
+// Virtual workgroup -> its work item: an output tile, a contiguous range of that tile's K-steps, and -- when the tile is
+// shared -- which of its `nsplit` parts this is and the tile's slot in the exchange workspace.  Tiles below split_from
+// are whole, the others are shared by `splitk` workgroups each (equal parts of K); the grid has
+// split_from + (tiles - split_from) * splitk workgroups.
+struct WorkItem {
+    int tile, slot, split, nsplit, kbeg, kcnt;
+};
+__device__ __host__ __forceinline__ WorkItem locate_workgroup(int splitk, int split_from, int bid, int KT_all)
 {
-    nsplit = 1;
-    tile_id = bid;
-    split = 0;
-    if (p.splitk > 1 && bid >= p.split_from) {
-        const int w = bid - p.split_from;
-        nsplit = p.splitk;
-        tile_id = p.split_from + w / nsplit;
-        split = w % nsplit;
+    WorkItem w = {bid, 0, 0, 1, 0, KT_all};
+    if (splitk > 1 && bid >= split_from) {
+        const int v = bid - split_from;
+        w.nsplit = splitk;
+        w.slot = v / w.nsplit;
+        w.tile = split_from + w.slot;
+        w.split = v % w.nsplit;
+        w.kbeg = (int)((int64_t)KT_all * w.split / w.nsplit);
+        w.kcnt = (int)((int64_t)KT_all * (w.split + 1) / w.nsplit) - w.kbeg;
     }
+    return w;
 }
 
 // ---------------------------------------------------------------------------------
@@ -1162,20 +1170,17 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % C::WGM, wn = wave / C::WGM;
-    int tile_id, split, nsplit;
-    locate_workgroup(p, (int)blockIdx.x, tile_id, split, nsplit);
+    // this workgroup's part of the contraction: K-steps [kbeg, kbeg + KT); a ragged K is rounded up to whole pairs of
+    // K-steps, the positions past K are zero-filled by the tile fill
+    const int KT_all = RAGGED ? ((p.K + 2 * BK - 1) / (2 * BK)) * 2 : p.K / BK;
+    const WorkItem wi = locate_workgroup(p.splitk, p.split_from, (int)blockIdx.x, KT_all);
+    const int nsplit = wi.nsplit, kbeg = wi.kbeg, KT = wi.kcnt;
     int tm, tn;
-    tile_coords(tile_id, p.tiles_m * p.tiles_n, p.tiles_m, p.tiles_n, tm, tn);
+    tile_coords(wi.tile, p.tiles_m * p.tiles_n, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
     ACC acc;
     acc_zero(acc);
-
-    // this workgroup's part of the contraction: K-steps [kbeg, kbeg + KT); a ragged K is rounded up to whole pairs of
-    // K-steps, the positions past K are zero-filled by the tile fill
-    const int KT_all = RAGGED ? ((p.K + 2 * BK - 1) / (2 * BK)) * 2 : p.K / BK;
-    const int kbeg = (int)((int64_t)KT_all * split / nsplit);
-    const int KT = (int)((int64_t)KT_all * (split + 1) / nsplit) - kbeg;
 
     // loop-invariant per-lane byte offsets of this wave's chunks; wave w issues wave-loads w*L .. w*L+L-1
     const int valid_m = RAGGED ? (p.M - m0 < BM ? p.M - m0 : BM) : BM;
@@ -1390,7 +1395,7 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     }
     __syncthreads();  // every wave is done with the operand ring before the epilogue reuses it
 
-    if (nsplit > 1 && !splitk_exchange<C>(acc, p, tile_id - p.split_from, split, nsplit, red, tid)) return;
+    if (nsplit > 1 && !splitk_exchange<C>(acc, p, wi.slot, wi.split, nsplit, red, tid)) return;
 
     // a tile that lies wholly inside the matrix takes the epilogue without bounds checks
     if (RAGGED && (m0 + BM > p.M || n0 + BN > p.N))
@@ -1461,20 +1466,17 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % C::WGM, wn = wave / C::WGM;
-    int tile_id, split, nsplit;
-    locate_workgroup(p, (int)blockIdx.x, tile_id, split, nsplit);
+    // this workgroup's K-steps [kbeg, kbeg + KT); the host guarantees an even, positive count
+    const int KT_all = RAGGED ? ((p.K + 2 * BKB - 1) / (2 * BKB)) * 2 : p.K / BKB;
+    const WorkItem wi = locate_workgroup(p.splitk, p.split_from, (int)blockIdx.x, KT_all);
+    const int nsplit = wi.nsplit, kbeg = wi.kbeg, KT = wi.kcnt;
     int tm, tn;
-    tile_coords(tile_id, p.tiles_m * p.tiles_n, p.tiles_m, p.tiles_n, tm, tn);
+    tile_coords(wi.tile, p.tiles_m * p.tiles_n, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
     using ACC = Acc32<C>;
     ACC acc;
     acc_zero(acc);
-
-    // this workgroup's K-steps [kbeg, kbeg + KT); the host guarantees an even, positive count
-    const int KT_all = RAGGED ? ((p.K + 2 * BKB - 1) / (2 * BKB)) * 2 : p.K / BKB;
-    const int kbeg = (int)((int64_t)KT_all * split / nsplit);
-    const int KT = (int)((int64_t)KT_all * (split + 1) / nsplit) - kbeg;
 
     const int valid_m = RAGGED ? (p.M - m0 < BM ? p.M - m0 : BM) : BM;
     const int valid_n = RAGGED ? (p.N - n0 < BN ? p.N - n0 : BN) : BN;
@@ -1598,7 +1600,7 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     }
     __syncthreads();  // every wave is done with the operand ring before the epilogue reuses it
 
-    if (nsplit > 1 && !splitk_exchange<C>(acc, p, tile_id - p.split_from, split, nsplit, red, tid)) return;
+    if (nsplit > 1 && !splitk_exchange<C>(acc, p, wi.slot, wi.split, nsplit, red, tid)) return;
 
     run_epilogue<C, ACC, EPI, RAGGED, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
 }
