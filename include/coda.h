@@ -202,6 +202,24 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
                       const coda_mat *B, const coda_epi_op *prog /* host */, int32_t n_ops,
                       void *workspace, size_t workspace_bytes);
 
+/*
+ * coda_gemm for callers that cannot allocate device memory or hand in a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Identical to coda_gemm -- same arguments, same programs, same
+ * results bit for bit -- except that the split-K workspace is a static device array inside the library
+ * (CODA_STATIC_WS_BYTES = 32 MiB + 1 KiB per GPU, part of the code object's data, held from library load until the
+ * process ends) instead of a caller buffer.  The call allocates nothing and frees nothing.  Shapes that are not planned
+ * for split-K do not touch the array.  A shape whose split-K plan needs more than the array holds
+ * (coda_gemm_workspace_bytes(...) > CODA_STATIC_WS_BYTES, e.g. 2048 x 2048 x 8192: 64 tiles in 4 parts) is refused with
+ * CODA_ERR_WORKSPACE and nothing is enqueued: run it through coda_gemm with a workspace of the caller's, or with NULL.
+ * The array keeps whatever the previous call left in it; the ticket counters are cleared by a small kernel ahead of
+ * every split launch (no memset node, so the call can be captured into a HIP graph).  All calls on one GPU share that
+ * GPU's array: two calls that overlap in time on one GPU (different streams) race.  The first call on a GPU looks the
+ * array's device address up (one symbol query, error code CODA_ERR_LAUNCH if that fails).
+ */
+#define CODA_STATIC_WS_BYTES ((size_t)32 * 1024 * 1024 + 1024)
+coda_status coda_gemm_static_ws(void *stream, int64_t M, int64_t N, int64_t K, const coda_mat *A,
+                                const coda_mat *B, const coda_epi_op *prog /* host */, int32_t n_ops);
+
 /* Bytes of workspace that enable split-K for this shape; 0 when the shape is not split (the program does not matter;
    the figure is sufficient for bf16 and for 8-bit operands alike). */
 size_t coda_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, const coda_epi_op *prog /* host */,

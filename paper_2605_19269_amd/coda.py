@@ -26,7 +26,7 @@ CODA_BF16, CODA_F32, CODA_F8E4M3 = 0, 1, 2
  CODA_EPI_ROW_SUMSQ, CODA_EPI_STORE, CODA_EPI_ACCUM_F32, CODA_EPI_ROPE, CODA_EPI_RMSNORM_BWD, CODA_EPI_LSE_PARTIAL) = range(11)
 CODA_REDUCE_PARTIALS, CODA_REDUCE_ATOMIC, CODA_STORE_F32 = 0, 1, 2
 
-EXPORTS = ["coda_gemm", "coda_gemm_workspace_bytes", "coda_row_partial_blocks", "coda_row_finalize",
+EXPORTS = ["coda_gemm", "coda_gemm_static_ws", "coda_gemm_workspace_bytes", "coda_row_partial_blocks", "coda_row_finalize",
            "coda_col_partial_blocks", "coda_col_finalize", "coda_lse_finalize",
            "coda_row_sumsq", "coda_fold_gamma", "coda_interleave_pairs", "coda_status_string",
            "coda_last_hip_error"]
@@ -51,6 +51,9 @@ _vp, _i64, _i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
 _lib.coda_gemm.restype = ctypes.c_int
 _lib.coda_gemm.argtypes = [_vp, _i64, _i64, _i64, ctypes.POINTER(coda_mat), ctypes.POINTER(coda_mat),
                            ctypes.POINTER(coda_epi_op), _i32, _vp, ctypes.c_size_t]
+_lib.coda_gemm_static_ws.restype = ctypes.c_int
+_lib.coda_gemm_static_ws.argtypes = [_vp, _i64, _i64, _i64, ctypes.POINTER(coda_mat), ctypes.POINTER(coda_mat),
+                                     ctypes.POINTER(coda_epi_op), _i32]
 _lib.coda_gemm_workspace_bytes.restype = ctypes.c_size_t
 _lib.coda_gemm_workspace_bytes.argtypes = [_i64, _i64, _i64, ctypes.POINTER(coda_epi_op), _i32]
 _lib.coda_row_partial_blocks.restype = _i64
@@ -212,6 +215,23 @@ def coda_gemm(A, B, ops, transA=False, transB=False, stream=None, workspace=None
     ws_ptr = None if workspace is None else workspace.data_ptr()
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(coda_gemm_raw(_stream(stream), M, N, K, a, b, list(ops), ws_ptr, ws_bytes))
+
+
+def coda_gemm_static_ws_raw(stream, M, N, K, A, B, ops):
+    arr, n = _prog(ops)
+    return _lib.coda_gemm_static_ws(stream, M, N, K, ctypes.byref(A) if A is not None else None,
+                                    ctypes.byref(B) if B is not None else None, arr if ops is not None else None, n)
+
+
+def coda_gemm_static_ws(A, B, ops, transA=False, transB=False, stream=None):
+    """coda_gemm with the library's static split-K scratch instead of a caller workspace (allocates nothing)."""
+    a, b = mat(A, transA), mat(B, transB)
+    M, K = (A.shape[1], A.shape[0]) if transA else (A.shape[0], A.shape[1])
+    N = B.shape[0] if transB else B.shape[1]
+    _check(coda_gemm_static_ws_raw(_stream(stream), M, N, K, a, b, list(ops)))
+
+
+CODA_STATIC_WS_BYTES = 32 * 1024 * 1024 + 1024
 
 
 def coda_gemm_workspace_bytes(M, N, K, ops):

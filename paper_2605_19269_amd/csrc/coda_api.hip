@@ -6,6 +6,8 @@
 #include "aux_kernels.hpp"
 #include "gemm_launch.hpp"
 
+#include <mutex>
+
 namespace {
 
 thread_local int g_last_hip_error = 0;
@@ -311,11 +313,8 @@ hipError_t dispatch_mode_f8(int mode, int kind, const coda::GemmParams &p, hipSt
     }
 }
 
-}  // namespace
-
-extern "C" {
-
-coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_mat *A, const coda_mat *B,
+// coda_gemm proper (shared by the entry points that differ only in where the split-K workspace comes from).
+coda_status gemm_impl(void *stream, int64_t M, int64_t N, int64_t K, const coda_mat *A, const coda_mat *B,
                       const coda_epi_op *prog, int32_t n_ops, void *workspace, size_t workspace_bytes)
 {
     // the kernels index in 32 bits; K is rounded up to whole pairs of K-steps (64 bf16 or 128 8-bit elements) there
@@ -373,6 +372,56 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
     else
         e = dispatch_mode<false, true>(ps.mode, kind, p, s);
     return launch_status(e);
+}
+
+// ---- static scratch of coda_gemm_static_ws: one array per GPU, in the code object's own data, held until the process ends
+constexpr size_t STATIC_WS_BYTES = SPLITK_CNT_BYTES + (size_t)32 * 1024 * 1024;
+static __device__ __align__(256) unsigned char scratch[STATIC_WS_BYTES];
+constexpr int STATIC_WS_MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[STATIC_WS_MAX_DEVICES] = {};   // device address of `scratch` on each GPU, looked up once per GPU
+
+// Device address of the current GPU's copy of `scratch` (the array's name is only a host-side handle).
+hipError_t static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= STATIC_WS_MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" {
+
+coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_mat *A, const coda_mat *B,
+                      const coda_epi_op *prog, int32_t n_ops, void *workspace, size_t workspace_bytes)
+{
+    return gemm_impl(stream, M, N, K, A, B, prog, n_ops, workspace, workspace_bytes);
+}
+
+coda_status coda_gemm_static_ws(void *stream, int64_t M, int64_t N, int64_t K, const coda_mat *A, const coda_mat *B,
+                                const coda_epi_op *prog, int32_t n_ops)
+{
+    // the size check comes first and needs no GPU: a plan beyond the static array is an error, not a silent unsplit run
+    if (M < 0 || N < 0 || K < 0 || M > INT32_MAX - 256 || N > INT32_MAX / 2 || K > INT32_MAX - 128) return CODA_ERR_SHAPE;
+    if (!A || !B) return CODA_ERR_NULL;
+    const bool f8 = A->dtype == CODA_F8E4M3 || B->dtype == CODA_F8E4M3;
+    if (splitk_bytes(plan_splitk(M, N, K, f8)) > STATIC_WS_BYTES) return CODA_ERR_WORKSPACE;
+    void *ws = nullptr;
+    const hipError_t e = static_scratch(&ws);
+    if (e != hipSuccess) return launch_status(e);
+    return gemm_impl(stream, M, N, K, A, B, prog, n_ops, ws, STATIC_WS_BYTES);
 }
 
 size_t coda_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, const coda_epi_op *, int32_t)

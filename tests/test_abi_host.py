@@ -190,3 +190,17 @@ def test_epilogue_op_keeps_its_tensors_alive():
     assert ref() is not None and op.in_ == ref().data_ptr()
     del op
     assert ref() is None
+
+
+def test_static_scratch_entry_refuses_oversized_plans_before_touching_the_gpu(coda):
+    # 2048 x 2048 x 8192: 64 tiles in 4 parts = 64 MiB of partials, beyond the 32 MiB static array; the size check needs no GPU
+    M = N = 2048
+    K = 8192
+    assert coda.coda_gemm_workspace_bytes(M, N, K, []) > coda.CODA_STATIC_WS_BYTES
+    A, B = _mat(coda, P, M, K), _mat(coda, P, K, N)
+    store = _op(coda, coda.CODA_EPI_STORE, out=P, ld_out=N)
+    assert coda.coda_gemm_static_ws_raw(None, M, N, K, A, B, [store]) == coda.CODA_ERR_WORKSPACE
+    assert coda.coda_gemm_static_ws_raw(None, M, N, K, None, B, [store]) == coda.CODA_ERR_NULL
+    text = open(os.path.join(ROOT, "include", "coda.h")).read()
+    m = re.search(r"#define CODA_STATIC_WS_BYTES \(\(size_t\)(\d+) \* 1024 \* 1024 \+ (\d+)\)", text)
+    assert m and int(m.group(1)) * 1024 * 1024 + int(m.group(2)) == coda.CODA_STATIC_WS_BYTES
