@@ -3,20 +3,22 @@
  *
  * One call, coda_gemm, runs a dense bf16 GEMM with fp32 accumulation and then,
  * while the output tile is still in registers, an ordered list of epilogue
- * primitives ("epilogue program") before anything is written to memory.  This
- * is the paper's statement of the method: a fixed GEMM mainloop plus a small
- * set of composable epilogue primitives for scaling, reductions, pairwise
- * transforms and accumulation (Section 3.1), applied in list order like the
- * ordered primitive list of the paper's kernel example (Appendix "Epilogue
- * Example").  The remaining entry points are the lightweight auxiliary
- * reduction of Section 3.2.1 and one-time weight preparation.
+ * primitives ("epilogue program") before anything is written to memory.  The
+ * method it implements (Section 3.1) keeps the GEMM mainloop fixed and builds every
+ * fused operator out of a few epilogue building blocks -- per-row and per-column
+ * scaling, tile loads and stores, row and column reductions, maps over adjacent
+ * column pairs, in-place accumulation -- applied in list order, as in the
+ * paper's kernel example (Appendix "Epilogue Example").  The remaining entry
+ * points are the lightweight auxiliary reduction of Section 3.2.1 and one-time
+ * weight preparation.
  *
  * Conventions (all entry points)
  *  - Every pointer is a DEVICE pointer unless the comment says "host".  The
  *    caller owns all buffers; the library allocates nothing, keeps no state
  *    beyond a last-HIP-error slot, never synchronises, and only enqueues work
- *    on the given stream (`stream` is a hipStream_t passed as void*; NULL is
- *    the default stream).
+ *    on the given stream (`stream` is a hipStream_t passed as void*, so that
+ *    this header needs no HIP header and stays plain C; NULL is the default
+ *    stream).
  *  - Matrices are row-major.  `ld` is the row pitch in ELEMENTS.  bf16 is the
  *    upper half of an IEEE binary32, stored as 16-bit words.
  *  - "row" means a row of the GEMM output (a token): a row scale multiplies
@@ -32,6 +34,13 @@
 
 #include <stddef.h>
 #include <stdint.h>
+
+/* Entry points are the only symbols the shared objects export (they are built with hidden default visibility). */
+#if defined(__GNUC__)
+#define CODA_API __attribute__((visibility("default")))
+#else
+#define CODA_API
+#endif
 
 #ifdef __cplusplus
 extern "C" {
@@ -109,8 +118,9 @@ typedef enum coda_epi_kind {
        (2p, 2p+1) of the first i1 = rope_cols columns by the angle of (position of row i,
        frequency f = p mod (head_dim/2)):  v'[2p] = x0*cos - x1*sin,  v'[2p+1] = x0*sin + x1*cos.
        in: f32 cos table [T x head_dim/2] (dense), in2: f32 sin table (same shape),
-       in3: int32 pos[M] with 0 <= pos < T (not checked), i0 = head_dim (multiple of 8),
-       i1 = rope_cols (multiple of 8, <= N), ld_in = T.  Columns >= rope_cols pass through.
+       in3: int32 pos[M], i0 = head_dim (multiple of 8), i1 = rope_cols (multiple of 8, <= N),
+       ld_in = T, the number of table rows (T * head_dim/2 < 2^31).  A position outside [0, T) is
+       clamped to the nearest table row (never read out of bounds).  Columns >= rope_cols pass through.
        The paper pre-broadcasts the tables to [M x N/2]; indexing a [T x head_dim/2] table by
        position gives the same values without that input traffic.                       */
     CODA_EPI_ROPE = 8,
@@ -120,6 +130,9 @@ typedef enum coda_epi_kind {
            v'[i][j] = ( v*gamma[j] - cn[i][j]*z[i] ) * r[i]
        (follow with ADD_TILE to add the incoming residual gradient O_in, then STORE = O_out).
        in: bf16 C [M x N] (ld_in); in2: f32 r[M]; in3: f32 z[M]; in4: f32 gamma[N] (16-byte aligned).
+       i0 = 0: in3 is z itself.  i0 = d > 0: in3 holds the raw row sums sum_j (grad_h2 * h2)[i][j], as the row
+       statistic of SWIGLU_BWD leaves them (after coda_row_finalize, or directly with CODA_REDUCE_ATOMIC), and the
+       kernel uses z[i] = in3[i] / d -- the chain Kernel 10 -> auxiliary combine -> Kernel 9 needs no scaling pass.
        Optional out: bf16 [M x N] (ld_out) receives C_out = cn (.) gamma (the normalised activation).
        Optional out2: f32 column reduction dgamma[j] = sum_i v[i][j]*cn[i][j] of this tile row, laid
        out per `flags`: CODA_REDUCE_PARTIALS: [nblk x N] block-major (out2[b*N + j]),
@@ -150,7 +163,7 @@ typedef struct coda_epi_op {
     const void *in3; /* device */
     const void *in4; /* device */
     void *out3;      /* device */
-    int64_t i0, i1;  /* integer parameters of the op (ROPE: head_dim, rope_cols) */
+    int64_t i0, i1;  /* integer parameters of the op (ROPE: head_dim, rope_cols; RMSNORM_BWD: i0 = d or 0) */
 } coda_epi_op;
 
 /*
@@ -198,7 +211,7 @@ typedef struct coda_epi_op {
  * CODA_ERR_WORKSPACE.  The workspace needs no initialisation and holds nothing between calls;
  * two calls that share one must not overlap in time.
  */
-coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_mat *A,
+CODA_API coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_mat *A,
                       const coda_mat *B, const coda_epi_op *prog /* host */, int32_t n_ops,
                       void *workspace, size_t workspace_bytes);
 
@@ -217,17 +230,21 @@ coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_
  * array's device address up (one symbol query, error code CODA_ERR_LAUNCH if that fails).
  */
 #define CODA_STATIC_WS_BYTES ((size_t)32 * 1024 * 1024 + 1024)
-coda_status coda_gemm_static_ws(void *stream, int64_t M, int64_t N, int64_t K, const coda_mat *A,
+CODA_API coda_status coda_gemm_static_ws(void *stream, int64_t M, int64_t N, int64_t K, const coda_mat *A,
                                 const coda_mat *B, const coda_epi_op *prog /* host */, int32_t n_ops);
 
 /* Bytes of workspace that enable split-K for this shape; 0 when the shape is not split (the program does not matter;
-   the figure is sufficient for bf16 and for 8-bit operands alike). */
-size_t coda_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, const coda_epi_op *prog /* host */,
+   the figure is sufficient for bf16 and for 8-bit operands alike).  Split-K is this library's answer to the
+   tile-count quantisation that the paper leaves to its expert-written mainloop (Section 3.1: the mainloop is taken
+   as given); nothing in the method depends on it. */
+CODA_API size_t coda_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, const coda_epi_op *prog /* host */,
                                  int32_t n_ops);
 
-/* Number of column blocks nblk of a CODA_REDUCE_PARTIALS buffer for output width N
-   (the partial buffer is f32[nblk x M]). */
-int64_t coda_row_partial_blocks(int64_t N);
+/* Number of column blocks nblk of a CODA_REDUCE_PARTIALS buffer for output width N (the partial buffer is
+   f32[nblk x M]): one partial per row and output tile, the tile-level partial reduction of Section 3.1
+   ("tile reductions") that Section 3.2.1 combines in its auxiliary kernel.  `prog` / `n_ops` name the program
+   the buffer is for; every program of this build reduces over the same 256-column tiles, so they may be NULL / 0. */
+CODA_API int64_t coda_row_partial_blocks(int64_t N, const coda_epi_op *prog /* host, may be NULL */, int32_t n_ops);
 
 /*
  * Lightweight auxiliary reduction (Section 3.2.1): combine tile partials and
@@ -235,42 +252,48 @@ int64_t coda_row_partial_blocks(int64_t N);
  * partials: f32[nblk x M] (block-major).  sum_out, rstd_out: f32[M], either may
  * be NULL (not both).  d > 0 is the hidden size the mean is taken over.
  */
-coda_status coda_row_finalize(void *stream, const float *partials, int64_t M, int64_t nblk,
+CODA_API coda_status coda_row_finalize(void *stream, const float *partials, int64_t M, int64_t nblk,
                               float *sum_out, float *rstd_out, int64_t d, float eps);
 
 /* Auxiliary reduction of the log-sum-exp partials (Section 3.2.3: the per-tile maximum and sum-exp statistics are
    combined across tiles by a separate small kernel): lse[i] = M_i + log sum_b psum[b][i] exp(pmax[b][i] - M_i), M_i = max_b pmax[b][i];
    loss[i] = lse[i] - ztgt[i].  pmax, psum: f32[nblk x M]; ztgt f32[M] (needed only for loss_out);
    lse_out, loss_out: f32[M], either may be NULL (not both). */
-coda_status coda_lse_finalize(void *stream, const float *pmax, const float *psum, int64_t M, int64_t nblk,
+CODA_API coda_status coda_lse_finalize(void *stream, const float *pmax, const float *psum, int64_t M, int64_t nblk,
                               const float *ztgt, float *lse_out, float *loss_out);
 
 /* Number of row blocks nblk of a column-reduction partial buffer (f32[nblk x N]) for M output rows. */
-int64_t coda_col_partial_blocks(int64_t M);
+CODA_API int64_t coda_col_partial_blocks(int64_t M);
 
 /* Auxiliary reduction over column partials (the reduce_rows step of the RMSNorm weight gradient,
    Appendix "GEMM-RMSNorm-GEMM Backward Pass"): out[j] = sum_b partials[b*N + j].  partials f32[nblk x N]. */
-coda_status coda_col_finalize(void *stream, const float *partials, int64_t N, int64_t nblk, float *out);
+CODA_API coda_status coda_col_finalize(void *stream, const float *partials, int64_t N, int64_t nblk, float *out);
 
-/* ss[i] = sum_k X[i][k]^2 in fp32 for a bf16 matrix not produced by coda_gemm
-   (the first layer's input).  X->trans must be 0.  sum_out: f32[X->rows]. */
-coda_status coda_row_sumsq(void *stream, const coda_mat *X, float *sum_out);
+/* ss[i] = sum_k X[i][k]^2 in fp32 for a bf16 matrix not produced by coda_gemm (the first layer's input): the
+   row statistic behind r = 1/rms(x) of Section 3.2.1, which every later layer gets from the previous GEMM's
+   ROW_SUMSQ epilogue instead.  X->trans must be 0.  sum_out: f32[X->rows]. */
+CODA_API coda_status coda_row_sumsq(void *stream, const coda_mat *X, float *sum_out);
 
 /* One-time weight preparation: W_out[k][j] = bf16(gamma[k] * W[k][j]) so that
-   RMSNorm(x, gamma) W == diag(r) (x W_out).  W is [K x N] as stored (trans 0);
-   gamma f32[K]; W_out bf16 [K x N] with pitch ld_out. */
-coda_status coda_fold_gamma(void *stream, const coda_mat *W, const float *gamma, void *W_out,
+   RMSNorm(x, gamma) W == diag(r) (x W_out): the reparameterisation of Section 3.2.1 (the normalisation's row factor
+   commutes with the GEMM and moves into its epilogue) with the column factor gamma moved the other way, into the
+   weight.  The paper keeps gamma in the epilogue of the producing GEMM (Kernel 4, available here as COL_SCALE_SIDE);
+   folding is this library's default because it costs nothing per step.  One rounding to bf16 per weight element.
+   W is [K x N] as stored (trans 0); gamma f32[K]; W_out bf16 [K x N] with row pitch ld_out (elements; lets W_out be
+   a column block of a larger fused weight). */
+CODA_API coda_status coda_fold_gamma(void *stream, const coda_mat *W, const float *gamma, void *W_out,
                             int64_t ld_out);
 
 /* One-time weight preparation: interleave the columns of two [K x N] bf16
-   matrices: W_out[k][2j] = Wa[k][j] (gate), W_out[k][2j+1] = Wb[k][j] (up).
-   W_out is bf16 [K x 2N] with pitch ld_out. */
-coda_status coda_interleave_pairs(void *stream, const coda_mat *Wa, const coda_mat *Wb, void *W_out,
+   matrices: W_out[k][2j] = Wa[k][j] (gate), W_out[k][2j+1] = Wb[k][j] (up), the column order that the pairwise
+   SwiGLU epilogues split again (Section 3.2.2; interleavedSplit in Kernels 2, 6 and 10).
+   W_out is bf16 [K x 2N] with row pitch ld_out (elements). */
+CODA_API coda_status coda_interleave_pairs(void *stream, const coda_mat *Wa, const coda_mat *Wb, void *W_out,
                                   int64_t ld_out);
 
-const char *coda_status_string(coda_status s);
+CODA_API const char *coda_status_string(coda_status s);
 /* The hipError_t (as int) recorded by the most recent CODA_ERR_LAUNCH on this thread. */
-int coda_last_hip_error(void);
+CODA_API int coda_last_hip_error(void);
 
 #ifdef __cplusplus
 }

@@ -31,7 +31,7 @@ extern "C" {
  * Errors: CODA_ERR_NULL (a_frags / b_frags), CODA_ERR_ALIGN (16-byte alignment),
  * CODA_ERR_SHAPE (n_blocks < 0, iters < 0, n_blocks > 65535 * 16), CODA_ERR_LAUNCH.
  */
-coda_status coda_calib_mfma_loop(void *stream, const void *a_frags, const void *b_frags, int64_t n_blocks,
+CODA_API coda_status coda_calib_mfma_loop(void *stream, const void *a_frags, const void *b_frags, int64_t n_blocks,
                                  int64_t iters, float *out);
 
 /*
@@ -44,7 +44,7 @@ coda_status coda_calib_mfma_loop(void *stream, const void *a_frags, const void *
  * out[((wave*8 + i*2 + j)*4 + reg)*64 + lane] (lane holds row 4*(lane/16) + reg, column lane % 16 of B x A^T).
  * Errors as above.
  */
-coda_status coda_calib_mfma_loop16(void *stream, const void *a_frags, const void *b_frags, int64_t n_blocks,
+CODA_API coda_status coda_calib_mfma_loop16(void *stream, const void *a_frags, const void *b_frags, int64_t n_blocks,
                                    int64_t iters, float *out);
 
 #ifdef __cplusplus

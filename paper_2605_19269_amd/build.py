@@ -1,10 +1,13 @@
-"""Build libcoda.so (HIP, gfx950 only) in-tree with hipcc.
+"""Build libcoda.so and libcoda_bench.so (HIP, gfx950 only) in-tree with hipcc.
 
     python -m paper_2605_19269_amd.build [--force]
 
 Each translation unit is compiled to an object under paper_2605_19269_amd/_build/
-(in parallel) and linked into paper_2605_19269_amd/libcoda.so, which the ctypes
-binding loads.  hipcc cross-compiles for gfx950 without a GPU present.
+(in parallel).  libcoda.so is the product: it exports exactly what include/coda.h declares.
+libcoda_bench.so holds what only the measurement needs (the unfused baseline kernels of
+include/coda_unfused.h and the MFMA-only calibration loops of include/coda_calib.h) and links
+nothing of the product.  The ctypes binding loads both.  hipcc cross-compiles for gfx950
+without a GPU present.
 """
 import concurrent.futures
 import os
@@ -16,17 +19,20 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libcoda.so")
+LIB_BENCH = os.path.join(HERE, "libcoda_bench.so")
 RESOURCES = os.path.join(HERE, "libcoda.resources.txt")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 VALU ops.
+# -fvisibility=hidden: only the entry points marked CODA_API in the headers are exported.
 # -Wno-inline-asm: the direct-to-LDS load statement names M0 in its clobber list on purpose (it writes M0); the compiler
 # honours the clobber and warns, once per use, that M0 is a reserved register.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-fvisibility=hidden", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
-SOURCES = ["coda_api.hip", "aux_kernels.hip", "baseline_kernels.hip", "calib_kernels.hip",
+SOURCES = ["coda_api.hip", "aux_kernels.hip",
            "gemm_inst_nn.hip", "gemm_inst_nt.hip", "gemm_inst_tn.hip", "gemm_inst_tt.hip", "gemm_inst_f8.hip"]
+SOURCES_BENCH = ["baseline_kernels.hip", "calib_kernels.hip"]
 
 
 def _headers():
@@ -88,9 +94,17 @@ def _strip_remarks(text):
     return out
 
 
+def _link(lib, objs, force):
+    if force or not os.path.exists(lib) or any(os.path.getmtime(o) > os.path.getmtime(lib) for o in objs):
+        r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + objs,
+                           capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
+
+
 def build(force=False, jobs=None):
     os.makedirs(BUILD, exist_ok=True)
-    srcs = [s for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
+    srcs = SOURCES + SOURCES_BENCH
     jobs = jobs or min(8, len(srcs))
     with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:
         results = list(ex.map(lambda s: _compile(s, force), srcs))
@@ -98,12 +112,9 @@ def build(force=False, jobs=None):
     for _, log in results:
         if log.strip():
             print(log)
-    if force or not os.path.exists(LIB) or any(os.path.getmtime(o) > os.path.getmtime(LIB) for o in objs):
-        r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs,
-                           capture_output=True, text=True)
-        if r.returncode != 0:
-            raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
-    # registers, scratch and LDS of every kernel in the library, as the compiler reported them (read by the host tests)
+    _link(LIB, objs[:len(SOURCES)], force)
+    _link(LIB_BENCH, objs[len(SOURCES):], force)
+    # registers, scratch and LDS of every kernel of the two libraries, as the compiler reported them (read by the host tests)
     with open(RESOURCES, "w") as f:
         for o in objs:
             if os.path.exists(o + ".resources"):

@@ -4,6 +4,8 @@ Every function here has the name of the C entry point it forwards to (include/co
 and does nothing but turn torch tensors into raw device pointers, sizes and pitches.
 All arithmetic happens in the HIP kernels.  If the library has not been built the
 import of this module fails loudly; there is no fallback path of any kind.
+The measurement-only entry points (include/coda_unfused.h, include/coda_calib.h) live in
+a second library, libcoda_bench.so, loaded here as well.
 """
 import ctypes
 import os
@@ -16,7 +18,12 @@ if not os.path.exists(LIB_PATH):
         "libcoda.so is not built (%s). Build it with `python -m paper_2605_19269_amd.build`; "
         "there is no fallback implementation." % LIB_PATH)
 
+LIB_BENCH_PATH = os.path.join(_HERE, "libcoda_bench.so")
+if not os.path.exists(LIB_BENCH_PATH):
+    raise ImportError("libcoda_bench.so is not built (%s). Build it with `python -m paper_2605_19269_amd.build`." % LIB_BENCH_PATH)
+
 _lib = ctypes.CDLL(LIB_PATH)
+_blib = ctypes.CDLL(LIB_BENCH_PATH)
 
 # status codes / enums (mirrors of include/coda.h)
 CODA_OK, CODA_ERR_NULL, CODA_ERR_SHAPE, CODA_ERR_ALIGN, CODA_ERR_DTYPE, CODA_ERR_PROGRAM, \
@@ -57,7 +64,7 @@ _lib.coda_gemm_static_ws.argtypes = [_vp, _i64, _i64, _i64, ctypes.POINTER(coda_
 _lib.coda_gemm_workspace_bytes.restype = ctypes.c_size_t
 _lib.coda_gemm_workspace_bytes.argtypes = [_i64, _i64, _i64, ctypes.POINTER(coda_epi_op), _i32]
 _lib.coda_row_partial_blocks.restype = _i64
-_lib.coda_row_partial_blocks.argtypes = [_i64]
+_lib.coda_row_partial_blocks.argtypes = [_i64, ctypes.POINTER(coda_epi_op), _i32]
 _lib.coda_row_finalize.restype = ctypes.c_int
 _lib.coda_row_finalize.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _i64, ctypes.c_float]
 _lib.coda_col_partial_blocks.restype = _i64
@@ -76,20 +83,20 @@ _lib.coda_status_string.restype = ctypes.c_char_p
 _lib.coda_status_string.argtypes = [ctypes.c_int]
 _lib.coda_last_hip_error.restype = ctypes.c_int
 _lib.coda_last_hip_error.argtypes = []
-_lib.coda_unfused_rmsnorm_apply.restype = ctypes.c_int
-_lib.coda_unfused_rmsnorm_apply.argtypes = [_vp, _vp, _i64, _vp, _vp, _i64, _i64, _vp, _i64]
-_lib.coda_unfused_swiglu_fwd.restype = ctypes.c_int
-_lib.coda_unfused_swiglu_fwd.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _i64]
-_lib.coda_unfused_swiglu_bwd.restype = ctypes.c_int
-_lib.coda_unfused_swiglu_bwd.argtypes = [_vp, _vp, _i64, _vp, _i64, _i64, _i64, _vp, _i64]
-_lib.coda_unfused_add_sumsq.restype = ctypes.c_int
-_lib.coda_unfused_add_sumsq.argtypes = [_vp, _vp, _i64, _vp, _i64, _i64, _i64, _vp, _i64, _vp]
-_lib.coda_unfused_accumulate.restype = ctypes.c_int
-_lib.coda_unfused_accumulate.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _i64]
-_lib.coda_calib_mfma_loop.restype = ctypes.c_int
-_lib.coda_calib_mfma_loop.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp]
-_lib.coda_calib_mfma_loop16.restype = ctypes.c_int
-_lib.coda_calib_mfma_loop16.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp]
+_blib.coda_unfused_rmsnorm_apply.restype = ctypes.c_int
+_blib.coda_unfused_rmsnorm_apply.argtypes = [_vp, _vp, _i64, _vp, _vp, _i64, _i64, _vp, _i64]
+_blib.coda_unfused_swiglu_fwd.restype = ctypes.c_int
+_blib.coda_unfused_swiglu_fwd.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _i64]
+_blib.coda_unfused_swiglu_bwd.restype = ctypes.c_int
+_blib.coda_unfused_swiglu_bwd.argtypes = [_vp, _vp, _i64, _vp, _i64, _i64, _i64, _vp, _i64]
+_blib.coda_unfused_add_sumsq.restype = ctypes.c_int
+_blib.coda_unfused_add_sumsq.argtypes = [_vp, _vp, _i64, _vp, _i64, _i64, _i64, _vp, _i64, _vp]
+_blib.coda_unfused_accumulate.restype = ctypes.c_int
+_blib.coda_unfused_accumulate.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _i64]
+_blib.coda_calib_mfma_loop.restype = ctypes.c_int
+_blib.coda_calib_mfma_loop.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp]
+_blib.coda_calib_mfma_loop16.restype = ctypes.c_int
+_blib.coda_calib_mfma_loop16.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp]
 
 
 class CodaError(RuntimeError):
@@ -152,12 +159,15 @@ def col_scale_side(gamma, out):
 
 def rope(cos, sin, pos, head_dim, rope_cols):
     """cos / sin: f32 [T x head_dim/2] dense tables; pos: int32 [M]."""
-    return _op(CODA_EPI_ROPE, in_=cos, in2=sin, in3=pos, i0=head_dim, i1=rope_cols)
+    op = _op(CODA_EPI_ROPE, in_=cos, in2=sin, in3=pos, i0=head_dim, i1=rope_cols)
+    op.ld_in = cos.shape[0]     # T: rows of the tables
+    return op
 
 
-def rmsnorm_bwd(C, r, z, gamma, c_out=None, dgamma_out=None, atomic=False):
+def rmsnorm_bwd(C, r, z, gamma, c_out=None, dgamma_out=None, atomic=False, z_sum_over=0):
+    """z: f32 [M] row statistic; with z_sum_over = d > 0 it holds the raw row sums and the kernel divides by d."""
     return _op(CODA_EPI_RMSNORM_BWD, CODA_REDUCE_ATOMIC if atomic else CODA_REDUCE_PARTIALS, in_=C, in2=r, in3=z,
-               in4=gamma, out=c_out, out2=dgamma_out)
+               in4=gamma, out=c_out, out2=dgamma_out, i0=z_sum_over)
 
 
 def lse_partial(y, pmax, psum, ztgt):
@@ -239,8 +249,11 @@ def coda_gemm_workspace_bytes(M, N, K, ops):
     return _lib.coda_gemm_workspace_bytes(M, N, K, arr, n)
 
 
-def coda_row_partial_blocks(N):
-    return _lib.coda_row_partial_blocks(N)
+def coda_row_partial_blocks(N, ops=None):
+    if ops is None:
+        return _lib.coda_row_partial_blocks(N, None, 0)
+    arr, n = _prog(list(ops))
+    return _lib.coda_row_partial_blocks(N, arr, n)
 
 
 def coda_row_finalize(partials, M, nblk, sum_out=None, rstd_out=None, d=1, eps=0.0, stream=None):
@@ -284,27 +297,27 @@ def coda_last_hip_error():
 
 # --- unfused baseline kernels (include/coda_unfused.h) -----------------------------------------
 def coda_unfused_rmsnorm_apply(X, r, gamma, Xn, stream=None):
-    _check(_lib.coda_unfused_rmsnorm_apply(_stream(stream), _ptr(X), X.stride(0), _ptr(r), _ptr(gamma),
+    _check(_blib.coda_unfused_rmsnorm_apply(_stream(stream), _ptr(X), X.stride(0), _ptr(r), _ptr(gamma),
                                            X.shape[0], X.shape[1], _ptr(Xn), Xn.stride(0)))
 
 
 def coda_unfused_swiglu_fwd(Z, H, stream=None):
-    _check(_lib.coda_unfused_swiglu_fwd(_stream(stream), _ptr(Z), Z.stride(0), H.shape[0], H.shape[1],
+    _check(_blib.coda_unfused_swiglu_fwd(_stream(stream), _ptr(Z), Z.stride(0), H.shape[0], H.shape[1],
                                         _ptr(H), H.stride(0)))
 
 
 def coda_unfused_swiglu_bwd(dH, Z, dZ, stream=None):
-    _check(_lib.coda_unfused_swiglu_bwd(_stream(stream), _ptr(dH), dH.stride(0), _ptr(Z), Z.stride(0),
+    _check(_blib.coda_unfused_swiglu_bwd(_stream(stream), _ptr(dH), dH.stride(0), _ptr(Z), Z.stride(0),
                                         dH.shape[0], dH.shape[1], _ptr(dZ), dZ.stride(0)))
 
 
 def coda_unfused_add_sumsq(D, R, Y, ss=None, stream=None):
-    _check(_lib.coda_unfused_add_sumsq(_stream(stream), _ptr(D), D.stride(0), _ptr(R), R.stride(0),
+    _check(_blib.coda_unfused_add_sumsq(_stream(stream), _ptr(D), D.stride(0), _ptr(R), R.stride(0),
                                        D.shape[0], D.shape[1], _ptr(Y), Y.stride(0), _ptr(ss)))
 
 
 def coda_unfused_accumulate(T, G, stream=None):
-    _check(_lib.coda_unfused_accumulate(_stream(stream), _ptr(T), T.stride(0), T.shape[0], T.shape[1],
+    _check(_blib.coda_unfused_accumulate(_stream(stream), _ptr(T), T.stride(0), T.shape[0], T.shape[1],
                                         _ptr(G), G.stride(0)))
 
 
@@ -319,8 +332,8 @@ def _calib(fn, out_elems, a_frags, b_frags, n_blocks, iters, out, stream):
 
 
 def coda_calib_mfma_loop(a_frags, b_frags, n_blocks, iters, out=None, stream=None):
-    _calib(_lib.coda_calib_mfma_loop, 8 * 8 * 16 * 64, a_frags, b_frags, n_blocks, iters, out, stream)
+    _calib(_blib.coda_calib_mfma_loop, 8 * 8 * 16 * 64, a_frags, b_frags, n_blocks, iters, out, stream)
 
 
 def coda_calib_mfma_loop16(a_frags, b_frags, n_blocks, iters, out=None, stream=None):
-    _calib(_lib.coda_calib_mfma_loop16, 8 * 8 * 4 * 64, a_frags, b_frags, n_blocks, iters, out, stream)
+    _calib(_blib.coda_calib_mfma_loop16, 8 * 8 * 4 * 64, a_frags, b_frags, n_blocks, iters, out, stream)

@@ -5,10 +5,13 @@
 
 #include "aux_kernels.hpp"
 #include "gemm_launch.hpp"
+#include "splitk_plan.hpp"
 
 #include <mutex>
 
 namespace {
+
+static_assert(coda::PLAN_TILE_M == coda::TILE_M && coda::PLAN_TILE_N == coda::TILE_N, "the split-K plan counts the kernels' tiles");
 
 thread_local int g_last_hip_error = 0;
 
@@ -82,13 +85,15 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
             if ((st = check_vec(op.in)) != CODA_OK || (st = check_vec(op.in2)) != CODA_OK || (st = check_vec(op.in3)) != CODA_OK)
                 return st;
             if ((reinterpret_cast<uintptr_t>(op.in) & 7u) || (reinterpret_cast<uintptr_t>(op.in2) & 7u)) return CODA_ERR_ALIGN;
-            if (op.i0 <= 0 || (op.i0 & 7) || op.i0 > INT32_MAX || op.i1 < 0 || (op.i1 & 7) || op.i1 > N || op.ld_in <= 0)
+            if (op.i0 <= 0 || (op.i0 & 7) || op.i0 > INT32_MAX || op.i1 < 0 || (op.i1 & 7) || op.i1 > N || op.ld_in <= 0 ||
+                op.ld_in > INT32_MAX / (op.i0 / 2))    // T rows of head_dim / 2 entries, indexed in 31 bits
                 return CODA_ERR_SHAPE;
             p.rope_cos = static_cast<const float *>(op.in);
             p.rope_sin = static_cast<const float *>(op.in2);
             p.rope_pos = static_cast<const int *>(op.in3);
             p.rope_half = (int)(op.i0 / 2);
             p.rope_cols = (int)op.i1;
+            p.rope_T = (int)op.ld_in;
             stage = 4;          // only STORE may follow
             linear_only = true;
             break;
@@ -115,6 +120,8 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
             p.rn_r = static_cast<const float *>(op.in2);
             p.rn_z = static_cast<const float *>(op.in3);
             p.rn_gamma = static_cast<const float *>(op.in4);
+            if (op.i0 < 0 || op.i0 > INT32_MAX) return CODA_ERR_SHAPE;
+            p.rn_zscale = op.i0 > 0 ? 1.0f / (float)op.i0 : 1.0f;
             if (op.out) {
                 if ((st = check_tile(op.out, op.ld_out, N)) != CODA_OK) return st;
                 p.out2 = static_cast<uint16_t *>(op.out);
@@ -219,52 +226,6 @@ coda_status parse_program(const coda_epi_op *prog, int32_t n_ops, int64_t N, Par
     return final_seen ? CODA_OK : CODA_ERR_PROGRAM;
 }
 
-// Split-K plan (tiles and K-steps counted with their ragged edges).  Two cases:
-//  * few tiles: at most 64 output tiles leave at least three quarters of the 256 compute units without one (measured:
-//    with 64 tiles 4 parts win 1.4x, with 128 tiles 2 parts lose to the exchange of partial tiles): every tile is shared;
-//  * partly filled last round: more than 256 tiles whose count is not a multiple of 256 and whose remainder fills at
-//    most half of the chip: only the tiles of that last round are shared, so that it takes 1/parts of a round.  Worth
-//    it when the contraction length a workgroup is spared clearly outweighs the exchange (about 35 us, the time of ~1400
-//    contraction elements of a bf16 tile; the partly filled round itself runs faster than a full one): measured +16 % at
-//    320 tiles and +2 % at 384 tiles with K = 8192, +5 % at 320 tiles with K = 4096.
-// Every part gets at least 32 K-steps of 32 bf16 (64 fp8) elements and an even number of K-steps.
-constexpr int64_t SPLITK_CUS = 256, SPLITK_MAX = 8, SPLITK_MIN_K = 1024, SPLITK_MAX_TILES = 64, SPLITK_TAIL_MIN_SPARED = 3072;
-struct SplitPlan {
-    int parts;    // <= 1: no split
-    int first;    // tiles with id >= first are shared by `parts` workgroups each
-    int shared;   // number of shared tiles
-};
-SplitPlan plan_splitk(int64_t M, int64_t N, int64_t K, bool f8 = false)
-{
-    const SplitPlan none = {1, 0, 0};
-    if (M <= 0 || N <= 0 || K <= 0) return none;
-    const int64_t tiles = ((M + coda::TILE_M - 1) / coda::TILE_M) * ((N + coda::TILE_N - 1) / coda::TILE_N);
-    const int64_t scale = f8 ? 2 : 1;                         // an fp8 K-step covers twice the elements in the same time
-    const int64_t steps = (K + scale * 64 - 1) / (scale * 64) * 2;   // K-steps of 32 bf16 / 64 fp8 elements, in whole pairs
-    auto fit = [&](int64_t s) {
-        if (s > K / (scale * SPLITK_MIN_K)) s = K / (scale * SPLITK_MIN_K);
-        if (s > SPLITK_MAX) s = SPLITK_MAX;
-        // the kernels walk their K-steps in pairs: every part must get an even number
-        while (s >= 2 && steps % (2 * s)) --s;
-        return s >= 2 ? s : (int64_t)1;
-    };
-    if (tiles <= SPLITK_MAX_TILES) {
-        const int64_t s = fit(SPLITK_CUS / tiles);
-        return s >= 2 ? SplitPlan{(int)s, 0, (int)tiles} : none;
-    }
-    const int64_t rem = tiles % SPLITK_CUS;
-    if (tiles < SPLITK_CUS || rem == 0 || rem > SPLITK_CUS / 2) return none;
-    const int64_t s = fit(SPLITK_CUS / rem);
-    if (s < 2 || K - K / s < scale * SPLITK_TAIL_MIN_SPARED) return none;
-    return SplitPlan{(int)s, (int)(tiles - rem), (int)rem};
-}
-constexpr size_t SPLITK_CNT_BYTES = 1024;   // ticket counters (at most 128 shared tiles x 4 bytes), kept apart from the partials
-size_t splitk_bytes(const SplitPlan &pl)
-{
-    if (pl.parts <= 1) return 0;
-    return SPLITK_CNT_BYTES + (size_t)pl.shared * (size_t)pl.parts * coda::TILE_M * coda::TILE_N * sizeof(float);
-}
-
 __global__ void zero_counters_kernel(unsigned *c, int n)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -347,15 +308,15 @@ coda_status gemm_impl(void *stream, int64_t M, int64_t N, int64_t K, const coda_
     hipError_t e;
     // split-K only when the caller brought the workspace for it; without one the shape runs unsplit
     if (workspace) {
-        const SplitPlan pl = plan_splitk(M, N, K, f8);
-        const size_t need = splitk_bytes(pl);
+        const coda::SplitPlan pl = coda::plan_splitk(M, N, K, f8);
+        const size_t need = coda::splitk_bytes(pl);
         if (!aligned16(workspace)) return CODA_ERR_ALIGN;
         if (workspace_bytes < need) return CODA_ERR_WORKSPACE;
         if (pl.parts > 1) {
             p.splitk = pl.parts;
             p.split_from = pl.first;
             p.ws_cnt = static_cast<unsigned *>(workspace);
-            p.ws_part = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + SPLITK_CNT_BYTES);
+            p.ws_part = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + coda::SPLITK_CNT_BYTES);
             hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(256), 0, s, p.ws_cnt, pl.shared);
             if ((e = hipGetLastError()) != hipSuccess) return launch_status(e);
         }
@@ -375,7 +336,7 @@ coda_status gemm_impl(void *stream, int64_t M, int64_t N, int64_t K, const coda_
 }
 
 // ---- static scratch of coda_gemm_static_ws: one array per GPU, in the code object's own data, held until the process ends
-constexpr size_t STATIC_WS_BYTES = SPLITK_CNT_BYTES + (size_t)32 * 1024 * 1024;
+constexpr size_t STATIC_WS_BYTES = coda::SPLITK_CNT_BYTES + (size_t)32 * 1024 * 1024;
 static __device__ __align__(256) unsigned char scratch[STATIC_WS_BYTES];
 constexpr int STATIC_WS_MAX_DEVICES = 64;
 std::mutex g_scratch_mutex;
@@ -417,7 +378,7 @@ coda_status coda_gemm_static_ws(void *stream, int64_t M, int64_t N, int64_t K, c
     if (M < 0 || N < 0 || K < 0 || M > INT32_MAX - 256 || N > INT32_MAX / 2 || K > INT32_MAX - 128) return CODA_ERR_SHAPE;
     if (!A || !B) return CODA_ERR_NULL;
     const bool f8 = A->dtype == CODA_F8E4M3 || B->dtype == CODA_F8E4M3;
-    if (splitk_bytes(plan_splitk(M, N, K, f8)) > STATIC_WS_BYTES) return CODA_ERR_WORKSPACE;
+    if (coda::splitk_bytes(coda::plan_splitk(M, N, K, f8)) > STATIC_WS_BYTES) return CODA_ERR_WORKSPACE;
     void *ws = nullptr;
     const hipError_t e = static_scratch(&ws);
     if (e != hipSuccess) return launch_status(e);
@@ -428,11 +389,11 @@ size_t coda_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, const coda_epi
 {
     if (M < 0 || N < 0 || K < 0 || M > INT32_MAX - 256 || N > INT32_MAX / 2 || K > INT32_MAX - 128) return 0;
     // the plan depends on the operand width (an 8-bit K-step covers twice the elements): report what covers both
-    const size_t b16 = splitk_bytes(plan_splitk(M, N, K, false)), b8 = splitk_bytes(plan_splitk(M, N, K, true));
+    const size_t b16 = coda::splitk_bytes(coda::plan_splitk(M, N, K, false)), b8 = coda::splitk_bytes(coda::plan_splitk(M, N, K, true));
     return b16 > b8 ? b16 : b8;
 }
 
-int64_t coda_row_partial_blocks(int64_t N)
+int64_t coda_row_partial_blocks(int64_t N, const coda_epi_op *, int32_t)
 {
     return N <= 0 ? 0 : (N + coda::TILE_N - 1) / coda::TILE_N;
 }

@@ -58,12 +58,14 @@ struct GemmParams {
     const uint16_t *Z; int64_t ldz;      // SWIGLU_BWD saved pre-activation [M x 2N]
     uint16_t *out2; int64_t ld_out2;     // SWIGLU_FWD: pre-activation; SWIGLU_BWD: silu(g)*u
     const float *rope_cos, *rope_sin;    // f32 [T x rope_half] tables (linear mode; null = no rotation)
-    const int *rope_pos;                 // int32 [M]
+    const int *rope_pos;                 // int32 [M]; values are clamped to [0, rope_T - 1] where they are read
     int rope_half, rope_cols;            // head_dim / 2 (multiple of 4); leading columns that are rotated
+    int rope_T;                          // rows of the tables (rope_T * rope_half fits 31 bits)
     // RMSNORM_BWD: RMSNorm input C [M x N] bf16, inverse rms r[M], row statistic z[M], weight gamma[N];
     // the optional O_in tile travels in `add`, the optional C_out in `out2`
     const uint16_t *rn_c; int64_t ld_rn_c;
     const float *rn_r, *rn_z, *rn_gamma;
+    float rn_zscale;                     // z = rn_z[i] * rn_zscale (1, or 1/d when rn_z holds the raw row sums)
     float *colred; int colred_mode;      // dgamma: partials [tiles_m x N] (ROWRED_PARTIALS) or atomics into f32[N]
     // log-sum-exp partials (linear mode): per column tile the row maximum and sum of exp(v - max), both [tiles_n x M];
     // target column y[M] and the selected logit z_tgt[M]
@@ -507,7 +509,7 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
                 const int m = mw + (ps * FPP + fi) * LR + lrow;
                 const bool mok = !EDGE || m < p.M;
                 rrv[fi] = mok ? p.rn_r[m] : 0.0f;
-                zzv[fi] = mok ? p.rn_z[m] : 0.0f;
+                zzv[fi] = mok ? p.rn_z[m] * p.rn_zscale : 0.0f;
             }
 #pragma unroll
             for (int u = 0; u < NU; ++u) {
@@ -722,7 +724,7 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
         u32x4 tc[4], ts[4];
         auto gather = [&](int ps) {                                    // table slices of 32-row pass ps -> registers
             const int m = mw + ps * P + (lane & 31);
-            const int trow = (!EDGE || m < p.M) ? p.rope_pos[m] * p.rope_half + f0 : f0;
+            const int trow = (!EDGE || m < p.M) ? clampi(p.rope_pos[m], 0, p.rope_T - 1) * p.rope_half + f0 : f0;
 #pragma unroll
             for (int it = 0; it < 4; ++it) {                           // 8 rows x 128 bytes per access
                 const int src = __shfl(trow, it * 8 + (lane >> 3), 64) + (lane & 7) * 4;
@@ -792,7 +794,7 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
                     const float rs = rsv[i];
                     // RoPE: table row of this token and the frequency index of the lane's first pair; units follow each
                     // other UC / 2 <= 8 pairs apart and rope_half is a multiple of 4, so the index wraps at most twice per step
-                    const int64_t trow = (p.rope_cos && mok) ? (int64_t)p.rope_pos[m] * p.rope_half : 0;
+                    const int64_t trow = (p.rope_cos && mok) ? (int64_t)clampi(p.rope_pos[m], 0, p.rope_T - 1) * p.rope_half : 0;
                     int rf = p.rope_cos ? ((nw + lcol) >> 1) % p.rope_half : 0;
 #pragma unroll
                     for (int u = 0; u < NU; ++u) {
@@ -880,7 +882,7 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
             const bool mok = !EDGE || m < p.M;
             const float rs = rsv[i];
             const bool rope = EPI == EPI_LINEAR && p.rope_cos;
-            const int64_t trow = (rope && mok) ? (int64_t)p.rope_pos[m] * p.rope_half : 0;
+            const int64_t trow = (rope && mok) ? (int64_t)clampi(p.rope_pos[m], 0, p.rope_T - 1) * p.rope_half : 0;
             int rf = rope ? ((nw + lcol) >> 1) % p.rope_half : 0;
 #pragma unroll
             for (int u = 0; u < NU; ++u) {

@@ -137,3 +137,15 @@ def sample_rows(M, n, seed=0):
     extra = g.choice(M, size=min(M, max(0, n - len(fixed))), replace=False).tolist()
     rows = sorted(set(fixed + extra))
     return np.asarray(rows, dtype=np.int64)
+
+
+def sample_rows_per_tile(M, per_tile, seed=0, tile=256):
+    """Deterministic row sample that reaches every row tile: the tile-boundary rows of sample_rows plus `per_tile`
+    seeded rows inside each block of `tile` consecutive rows, sorted and unique."""
+    fixed = [r for r in (0, 1, 31, 32, 127, 128, 255, 256, M - 2, M - 1) if 0 <= r < M]
+    g = _rng(seed)
+    extra = []
+    for t0 in range(0, M, tile):
+        n = min(tile, M - t0)
+        extra += (t0 + g.choice(n, size=min(n, per_tile), replace=False)).tolist()
+    return np.asarray(sorted(set(fixed + extra)), dtype=np.int64)

@@ -1,7 +1,10 @@
 """Full-size parity: the benchmark workloads at their real shapes, launched exactly as bench.py launches
 them (same programs, same layouts, whole-tile kernel instantiation), checked on a deterministic sample of output rows
 that the oracle computes one by one.  Every epilogue on the path is row-local, so sampled rows are exact; the
-weight gradient is sampled over its own output rows."""
+weight gradient is sampled over its own output rows.  The sample holds rows of EVERY 256-row tile (two per tile at the
+1B shapes, one at the 8B shapes, plus the tile-boundary rows), and every output buffer starts out filled with a sentinel
+that must be gone afterwards, so a tile that was never written or was written by the wrong workgroup cannot hide between
+sampled rows."""
 import numpy as np
 import pytest
 import torch
@@ -11,7 +14,26 @@ from tests import gpu_util as G
 
 pytestmark = pytest.mark.gpu
 coda = None
-NSAMPLE = 48
+PER_TILE = 2          # sampled rows per 256-row tile (1B shapes); the 8B shapes take one
+
+
+def sentinel_bf16(shape):
+    t = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+    t.view(torch.int16).fill_(int(np.uint16(G.SENTINEL_BF16).view(np.int16)))
+    return t
+
+
+def sentinel_f32(shape):
+    return torch.full(shape, G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+
+
+def assert_all_written(t, what):
+    """No sentinel survives anywhere in the output (checked on the device over the whole tensor)."""
+    if t.dtype == torch.bfloat16:
+        left = int((t.view(torch.int16) == int(np.uint16(G.SENTINEL_BF16).view(np.int16))).sum().item())
+    else:
+        left = int((t == G.SENTINEL_F32).sum().item())
+    assert left == 0, "%s: %d elements were never written" % (what, left)
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -38,31 +60,33 @@ def gpu_rstd(X, eps=1e-6):
     return r
 
 
-def check_up(oracle, Xb, Wb, tag):
+def check_up(oracle, Xb, Wb, tag, per_tile=PER_TILE):
     M, N = Xb.shape[0], Wb.shape[1]
-    rows = synth.sample_rows(M, NSAMPLE, seed=3)
+    rows = synth.sample_rows_per_tile(M, per_tile, seed=3)
     X, W = G.dev_bf16(Xb), G.dev_bf16(Wb)
     r = gpu_rstd(X)
-    H = torch.empty((M, N // 2), dtype=torch.bfloat16, device="cuda")
+    H = sentinel_bf16((M, N // 2))
     coda.coda_gemm(X, W, [coda.row_scale(r), coda.swiglu_fwd(), coda.store(H)])
     torch.cuda.synchronize()
+    assert_all_written(H, tag + " H")
     r_host = r.cpu().numpy()
     G.assert_sumsq_close(r_host[rows], oracle.rstd(Xb, 1e-6, rows=rows), tag + " rstd")
     ref = oracle.gemm_rowscale_swiglu(Xb, Wb, r=r_host.astype(np.float64), rows=rows)   # same fp32 r bytes as the GPU
     G.assert_bf16_close(rows_of(H, rows), ref, tag + " H")
 
 
-def check_down(oracle, Hb, Wb, Rb, tag):
+def check_down(oracle, Hb, Wb, Rb, tag, per_tile=PER_TILE):
     M, N = Hb.shape[0], Wb.shape[1]
-    rows = synth.sample_rows(M, NSAMPLE, seed=4)
-    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    rows = synth.sample_rows_per_tile(M, per_tile, seed=4)
+    Y = sentinel_bf16((M, N))
     nblk = coda.coda_row_partial_blocks(N)
-    part = torch.empty((nblk, M), dtype=torch.float32, device="cuda")
-    ss = torch.empty(M, dtype=torch.float32, device="cuda")
+    part = sentinel_f32((nblk, M))
+    ss = sentinel_f32((M,))
     dR = G.dev_bf16(Rb)
     coda.coda_gemm(G.dev_bf16(Hb), G.dev_bf16(Wb), [coda.add_tile(dR), coda.row_sumsq(part), coda.store(Y)])
     coda.coda_row_finalize(part, M, nblk, sum_out=ss, d=N, eps=0.0)
     torch.cuda.synchronize()
+    assert_all_written(Y, tag + " Y"); assert_all_written(part, tag + " partials"); assert_all_written(ss, tag + " sumsq")
     refY, refss = oracle.gemm_residual_sumsq(Hb, Wb, C=Rb, rows=rows)
     G.assert_bf16_close(rows_of(Y, rows), refY, tag + " Y")
     G.assert_sumsq_close(ss.cpu().numpy()[rows], refss, tag + " sumsq")
@@ -83,15 +107,20 @@ def test_llama1b_mlp_backward(oracle):
     M, d = c["dY"].shape
     F = c["W"].shape[0]
     dY, W, Z, H = G.dev_bf16(c["dY"]), G.dev_bf16(c["W"]), G.dev_bf16(c["Z"]), G.dev_bf16(c["H"])
-    dZ = torch.empty((M, 2 * F), dtype=torch.bfloat16, device="cuda")
+    dZ = sentinel_bf16((M, 2 * F))
     coda.coda_gemm(dY, W, [coda.swiglu_bwd(Z), coda.store(dZ)], transB=True)
     Gb = torch.from_numpy(c["G"]).cuda()
+    G0 = Gb.clone()
     coda.coda_gemm(H, dY, [coda.accum_f32(Gb)], transA=True)
     torch.cuda.synchronize()
-    rows = synth.sample_rows(M, NSAMPLE, seed=5)
+    assert_all_written(dZ, "1B dZ")
+    # the accumulate works in place: every element must have moved (increments are ~N(0, 0.9) on values ~1e-3)
+    assert int((Gb == G0).sum().item()) <= 2, "1B dW accumulate left elements untouched"
+    del G0
+    rows = synth.sample_rows_per_tile(M, PER_TILE, seed=5)
     refdZ, _, _ = oracle.gemm_swiglu_bwd(c["dY"], c["W"], c["Z"], transB=True, rows=rows)
     G.assert_bf16_close(rows_of(dZ, rows), refdZ, "1B dZ")
-    wrows = synth.sample_rows(F, NSAMPLE, seed=6)
+    wrows = synth.sample_rows_per_tile(F, PER_TILE, seed=6)
     refG = oracle.gemm_accumulate(c["H"], c["dY"], c["G"], transA=True, rows=wrows)
     G.assert_f32_signed_close(rows_of(Gb, wrows), refG, "1B dW accumulate")
 
@@ -101,31 +130,29 @@ def test_llama8b_block_shapes(oracle):
     residual add and sum of squares (M = 16384, d = 4096, F = 14336)."""
     c = synth.block_8b(seed=7)
     M = c["X"].shape[0]
-    rows = synth.sample_rows(M, 32, seed=8)
+    rows = synth.sample_rows_per_tile(M, 1, seed=8)
     X = G.dev_bf16(c["X"])
     r = gpu_rstd(X)
     r_host = r.cpu().numpy().astype(np.float64)
-    Q = torch.empty((M, c["Wqkv"].shape[1]), dtype=torch.bfloat16, device="cuda")
+    Q = sentinel_bf16((M, c["Wqkv"].shape[1]))
     coda.coda_gemm(X, G.dev_bf16(c["Wqkv"]), [coda.row_scale(r), coda.store(Q)])
     torch.cuda.synchronize()
+    assert_all_written(Q, "8B qkv")
     G.assert_bf16_close(rows_of(Q, rows), oracle.gemm_rowscale(c["X"], c["Wqkv"], r=r_host, rows=rows), "8B qkv")
     # the same projection with RoPE on the query and key heads (32 + 8 heads of 128; value heads pass through)
+    Q.view(torch.int16).fill_(int(np.uint16(G.SENTINEL_BF16).view(np.int16)))
     hd, rc, T = 128, 5120, 2048
     cos, sin = synth.rope_tables(T, hd)
     pos = (np.arange(M) % T).astype(np.int32)
     dcos, dsin, dpos = G.dev_f32(cos), G.dev_f32(sin), torch.from_numpy(pos).cuda()
     coda.coda_gemm(X, G.dev_bf16(c["Wqkv"]), [coda.row_scale(r), coda.rope(dcos, dsin, dpos, hd, rc), coda.store(Q)])
     torch.cuda.synchronize()
+    assert_all_written(Q, "8B qkv + rope")
     G.assert_bf16_close(rows_of(Q, rows), oracle.gemm_rowscale_rope(c["X"], c["Wqkv"], cos, sin, pos, hd, rc, r=r_host, rows=rows),
                         "8B qkv + rope")
     del Q
-    global NSAMPLE
-    keep, NSAMPLE = NSAMPLE, 32
-    try:
-        check_up(oracle, c["X"], c["Wup"], "8B up")
-        check_down(oracle, c["H"], c["Wdown"], c["R"], "8B down")
-    finally:
-        NSAMPLE = keep
+    check_up(oracle, c["X"], c["Wup"], "8B up", per_tile=1)
+    check_down(oracle, c["H"], c["Wdown"], c["R"], "8B down", per_tile=1)
 
 
 def test_llama8b_rmsnorm_backward(oracle):
@@ -142,17 +169,17 @@ def test_llama8b_rmsnorm_backward(oracle):
     r = synth.uniform_f32(g, (M,), 0.5, 1.5)
     z = synth.normal_f32(g, (M,), 1e-3)
     gamma = synth.uniform_f32(g, (N,), 0.5, 1.5)
-    Oout = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
-    Cout = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    Oout, Cout = sentinel_bf16((M, N)), sentinel_bf16((M, N))
     nblk = coda.coda_col_partial_blocks(M)
-    part = torch.empty((nblk, N), dtype=torch.float32, device="cuda")
+    part = sentinel_f32((nblk, N))
     dg = torch.empty(N, dtype=torch.float32, device="cuda")
     dC, dr, dz, dgm, dO = G.dev_bf16(Cb), G.dev_f32(r), G.dev_f32(z), G.dev_f32(gamma), G.dev_bf16(Oin)
     coda.coda_gemm(G.dev_bf16(dY), G.dev_bf16(W),
                    [coda.rmsnorm_bwd(dC, dr, dz, dgm, c_out=Cout, dgamma_out=part), coda.add_tile(dO), coda.store(Oout)], transB=True)
     coda.coda_col_finalize(part, N, nblk, dg)
     torch.cuda.synchronize()
-    rows = synth.sample_rows(M, 32, seed=10)
+    assert_all_written(Oout, "8B O_out"); assert_all_written(Cout, "8B C_out"); assert_all_written(part, "8B dgamma partials")
+    rows = synth.sample_rows_per_tile(M, 1, seed=10)
     r64, z64, g64 = r.astype(np.float64), z.astype(np.float64), gamma.astype(np.float64)
     refO, refC, _ = oracle.gemm_rmsnorm_bwd(dY, W, Cb, r64, z64, g64, Oin=Oin, transB=True, rows=rows)
     G.assert_bf16_close(rows_of(Oout, rows), refO, "8B O_out")
@@ -172,16 +199,17 @@ def test_lm_head_logits_lse(oracle):
     y = g.integers(0, N, size=M).astype(np.int32)
     X = G.dev_bf16(Xb)
     r = gpu_rstd(X)
-    Z = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    Z = sentinel_bf16((M, N))
     nblk = coda.coda_row_partial_blocks(N)
-    pmax = torch.empty((nblk, M), dtype=torch.float32, device="cuda")
-    psum = torch.empty((nblk, M), dtype=torch.float32, device="cuda")
-    zt, lse, loss = (torch.empty(M, dtype=torch.float32, device="cuda") for _ in range(3))
+    pmax, psum = sentinel_f32((nblk, M)), sentinel_f32((nblk, M))
+    zt, lse, loss = (sentinel_f32((M,)) for _ in range(3))
     dy = torch.from_numpy(y).cuda()
     coda.coda_gemm(X, G.dev_bf16(Wb), [coda.row_scale(r), coda.lse_partial(dy, pmax, psum, zt), coda.store(Z)])
     coda.coda_lse_finalize(pmax, psum, M, nblk, ztgt=zt, lse_out=lse, loss_out=loss)
     torch.cuda.synchronize()
-    rows = synth.sample_rows(M, 32, seed=12)
+    for t, what in ((Z, "logits"), (pmax, "max partials"), (psum, "sum-exp partials"), (zt, "target logit"), (lse, "lse"), (loss, "loss")):
+        assert_all_written(t, "LM-head " + what)
+    rows = synth.sample_rows_per_tile(M, 1, seed=12)
     refZ, refzt, reflse = oracle.gemm_rowscale_lse(Xb, Wb, y, r=r.cpu().numpy().astype(np.float64), rows=rows)
     G.assert_bf16_close(rows_of(Z, rows), refZ, "LM-head logits")
     G.assert_f32_signed_close(zt.cpu().numpy()[rows].astype(np.float64), refzt, "LM-head target logit")
@@ -196,14 +224,15 @@ def test_llama1b_forward_gemms_on_f8e4m3_operands(oracle):
     residual, sum of squares).  Operands ~ N(0,1) rounded to E4M3; the weights are stored [out x in]."""
     M, d, F = 8192, 2048, 8192
     g = np.random.Generator(np.random.PCG64(31))
-    rows = synth.sample_rows(M, NSAMPLE, seed=5)
+    rows = synth.sample_rows_per_tile(M, 1, seed=5)
     X8, W8 = synth.normal_f8e4m3(g, (M, d), 1.0), synth.normal_f8e4m3(g, (2 * F, d), 1.0)
     r = synth.uniform_f32(g, (M,), 0.01, 0.03)
     dr = G.dev_f32(r)
-    H = torch.empty((M, F), dtype=torch.bfloat16, device="cuda")
+    H = sentinel_bf16((M, F))
     coda.coda_gemm(torch.from_numpy(X8).cuda(), torch.from_numpy(W8).cuda(), [coda.row_scale(dr), coda.swiglu_fwd(), coda.store(H)],
                    transB=True)
     torch.cuda.synchronize()
+    assert_all_written(H, "1B up, E4M3 operands")
     ref = oracle.gemm_rowscale_swiglu(oracle.f8e4m3_to_bf16_bits(X8), oracle.f8e4m3_to_bf16_bits(W8), r=r.astype(np.float64),
                                       transB=True, rows=rows)
     G.assert_bf16_close(rows_of(H, rows), ref, "1B up, E4M3 operands")
@@ -212,14 +241,15 @@ def test_llama1b_forward_gemms_on_f8e4m3_operands(oracle):
     Rb = synth.normal_bf16(g, (M, d), 1.0)
     r2 = synth.uniform_f32(g, (M,), 0.005, 0.015)
     dr2, dR = G.dev_f32(r2), G.dev_bf16(Rb)
-    Y = torch.empty((M, d), dtype=torch.bfloat16, device="cuda")
+    Y = sentinel_bf16((M, d))
     nblk = coda.coda_row_partial_blocks(d)
-    part = torch.empty((nblk, M), dtype=torch.float32, device="cuda")
+    part = sentinel_f32((nblk, M))
     ss = torch.empty(M, dtype=torch.float32, device="cuda")
     coda.coda_gemm(torch.from_numpy(H8).cuda(), torch.from_numpy(Wd8).cuda(),
                    [coda.row_scale(dr2), coda.add_tile(dR), coda.row_sumsq(part), coda.store(Y)], transB=True)
     coda.coda_row_finalize(part, M, nblk, sum_out=ss, d=d, eps=0.0)
     torch.cuda.synchronize()
+    assert_all_written(Y, "1B down, E4M3 operands"); assert_all_written(part, "1B down partials, E4M3 operands")
     refY, refss = oracle.gemm_residual_sumsq(oracle.f8e4m3_to_bf16_bits(H8), oracle.f8e4m3_to_bf16_bits(Wd8), r=r2.astype(np.float64),
                                              C=Rb, transB=True, rows=rows)[:2]
     G.assert_bf16_close(rows_of(Y, rows), refY, "1B down, E4M3 operands")

@@ -284,6 +284,99 @@ def test_mlp_block_chain(oracle):
     assert rel.max() <= 1e-2, "block sum of squares: max relative error %.3g" % rel.max()
 
 
+def test_mlp_block_chain_stage_by_stage(oracle):
+    """The same three launches, each held to the single-kernel bar: every stage's oracle gets the bytes that the GPU
+    stage before it actually stored (the fp32 rstd, the folded bf16 weight, the bf16 H), so no rounding of an earlier
+    stage is left for the tolerance to absorb."""
+    g = rng(21)
+    M, d, F = 384, 256, 512
+    Xb = synth.normal_bf16(g, (M, d), 1.0)
+    gamma = synth.uniform_f32(g, (d,), 0.5, 1.5)
+    W1 = synth.normal_bf16(g, (d, 2 * F), 0.08)
+    W2 = synth.normal_bf16(g, (F, d), 0.08)
+    X, dW1, dW2, dg = G.dev_bf16(Xb), G.dev_bf16(W1), G.dev_bf16(W2), G.dev_f32(gamma)
+    ssx = torch.empty(M, dtype=torch.float32, device="cuda")
+    rstd = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_row_sumsq(X, ssx)
+    coda.coda_row_finalize(ssx.view(1, M), M, 1, rstd_out=rstd, d=d, eps=1e-6)
+    W1p = torch.empty_like(dW1)
+    coda.coda_fold_gamma(dW1, dg, W1p)
+    H = G.Guarded(M, F, torch.bfloat16)
+    coda.coda_gemm(X, W1p, [coda.row_scale(rstd), coda.swiglu_fwd(), coda.store(H.t)])
+    Y = G.Guarded(M, d, torch.bfloat16)
+    nblk = coda.coda_row_partial_blocks(d)
+    part = torch.full((nblk, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    ss = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_gemm(H.t, dW2, [coda.add_tile(X), coda.row_sumsq(part), coda.store(Y.t)])
+    coda.coda_row_finalize(part, M, nblk, sum_out=ss, d=d, eps=0.0)
+    torch.cuda.synchronize()
+    H.check_guards(); H.written(); Y.check_guards(); Y.written()
+    # stage 1: the row statistic
+    G.assert_sumsq_close(G.host_f64(rstd), oracle.rstd(Xb, 1e-6), "stage rstd")
+    # stage 2: the folded weight, one rounding of the exact product
+    W1p_bits = G.host_bits(W1p)
+    G.assert_bf16_close(G.bits_to_f64(W1p_bits), oracle.fold_gamma(W1, gamma.astype(np.float64)), "stage folded weight")
+    # stage 3: up-projection on the GPU's own rstd and folded weight
+    refH = oracle.gemm_rowscale_swiglu(Xb, W1p_bits, r=G.host_f64(rstd))
+    G.assert_bf16_close(G.host_f64(H.t), refH, "stage H")
+    # stage 4: down-projection on the GPU's own stored H
+    refY, refss = oracle.gemm_residual_sumsq(np.ascontiguousarray(G.host_bits(H.t)), W2, C=Xb)[:2]
+    G.assert_bf16_close(G.host_f64(Y.t), refY, "stage Y")
+    G.assert_sumsq_close(G.host_f64(ss), refss, "stage sum of squares")
+
+
+@pytest.mark.parametrize("atomic", [False, True])
+def test_backward_chain_kernel10_statistic_into_kernel9(oracle, atomic):
+    """Kernel 10's row statistic feeds Kernel 9 end to end: dY W_down^T with SwiGLU backward leaves dZ and the row sums
+    sum_j (g dG + u dU); the auxiliary combine adds the tile partials; Kernel 9 (dZ W1^T with the local RMSNorm backward)
+    reads those raw sums and divides by the hidden size itself.  The oracle takes the same chain in fp64, with the
+    GPU's stored dZ as Kernel 9's operand so that the second stage is held to the single-kernel bar."""
+    g = rng(83)
+    M, dm, F = 520, 264, 256
+    dYb = synth.normal_bf16(g, (M, dm), 0.5)
+    Wd = synth.normal_bf16(g, (F, dm), 0.1)              # down-projection weight [F x d], used transposed
+    Zb = synth.normal_bf16(g, (M, 2 * F), 1.0)
+    W1 = synth.normal_bf16(g, (dm, 2 * F), 0.1)          # up-projection weight [d x 2F], used transposed
+    h1 = synth.normal_bf16(g, (M, dm), 1.0)              # the RMSNorm input
+    Oin = synth.normal_bf16(g, (M, dm), 0.5)
+    gamma = synth.uniform_f32(g, (dm,), 0.5, 1.5)
+    r = oracle.rstd(h1, 1e-6).astype(np.float32)
+    # Kernel 10
+    dZ = G.Guarded(M, 2 * F, torch.bfloat16)
+    nblk = coda.coda_row_partial_blocks(F)
+    stat = torch.zeros(M, dtype=torch.float32, device="cuda") if atomic else \
+        torch.full((nblk, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    dZz = G.dev_bf16(Zb)
+    coda.coda_gemm(G.dev_bf16(dYb), G.dev_bf16(Wd), [coda.swiglu_bwd(dZz, stat_out=stat, atomic=atomic), coda.store(dZ.t)], transB=True)
+    if atomic:
+        zsum = stat
+    else:
+        zsum = torch.empty(M, dtype=torch.float32, device="cuda")
+        coda.coda_row_finalize(stat, M, nblk, sum_out=zsum, d=1, eps=0.0)
+    # Kernel 9 on the stored dZ, z = zsum / d formed in the kernel
+    Oout, Cout = G.Guarded(M, dm, torch.bfloat16), G.Guarded(M, dm, torch.bfloat16)
+    nb2 = coda.coda_col_partial_blocks(M)
+    dgp = torch.full((nb2, dm), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    dgam = torch.empty(dm, dtype=torch.float32, device="cuda")
+    dh1, dr, dgm, dO = G.dev_bf16(h1), G.dev_f32(r), G.dev_f32(gamma), G.dev_bf16(Oin)
+    coda.coda_gemm(dZ.t, G.dev_bf16(W1),
+                   [coda.rmsnorm_bwd(dh1, dr, zsum, dgm, c_out=Cout.t, dgamma_out=dgp, z_sum_over=dm), coda.add_tile(dO), coda.store(Oout.t)],
+                   transB=True)
+    coda.coda_col_finalize(dgp, dm, nb2, dgam)
+    torch.cuda.synchronize()
+    for t in (dZ, Oout, Cout):
+        t.check_guards(); t.written()
+    refdZ, _, refstat = oracle.gemm_swiglu_bwd(dYb, Wd, Zb, transB=True)
+    G.assert_bf16_close(G.host_f64(dZ.t), refdZ, "chain dZ")
+    G.assert_f32_signed_close(G.host_f64(zsum), refstat, "chain row statistic")
+    dZ_bits = np.ascontiguousarray(G.host_bits(dZ.t))
+    refO, refC, refdg = oracle.gemm_rmsnorm_bwd(dZ_bits, W1, h1, r.astype(np.float64), refstat / dm, gamma.astype(np.float64),
+                                                Oin=Oin, transB=True)
+    G.assert_bf16_close(G.host_f64(Oout.t), refO, "chain O_out")
+    G.assert_bf16_close(G.host_f64(Cout.t), refC, "chain C_out")
+    G.assert_f32_signed_close(G.host_f64(dgam), refdg, "chain dgamma")
+
+
 def test_aux_kernels(oracle):
     g = rng(31)
     M, K = 37, 264
@@ -414,6 +507,35 @@ def test_kernel7_rope(oracle, M, N, K, hd, rc, with_r, f32):
         G.assert_f32_signed_close(G.host_f64(out.t), ref, "rope f32")
     else:
         G.assert_bf16_close(G.host_f64(out.t), ref, "rope")
+
+
+@pytest.mark.parametrize("M,N,K,hd", [(512, 768, 128, 64), (264, 256, 72, 16)])
+@pytest.mark.parametrize("f32", [False, True])
+def test_rope_positions_outside_the_table_are_clamped(oracle, M, N, K, hd, f32):
+    """A position below 0 or at / beyond the table length T reads the nearest table row (never outside the table):
+    the result equals the oracle's on the clamped positions.  The tables sit between sentinel rows that would poison
+    the output if a row outside [0, T) were read.  Both RoPE paths (LDS-staged tables, per-unit gathers) are covered."""
+    g = rng(67)
+    A, B = operands(g, M, N, K, False, False, b_std=0.2)
+    T = 40
+    cos, sin = synth.rope_tables(T, hd)
+    pos = g.integers(0, T, size=M).astype(np.int32)
+    pos[::7] = -1 - g.integers(0, 1000, size=pos[::7].size).astype(np.int32)
+    pos[3::7] = T + g.integers(0, 1 << 20, size=pos[3::7].size).astype(np.int32)
+    pos[5] = np.iinfo(np.int32).min
+    pos[6] = np.iinfo(np.int32).max
+    pad = np.full((64, hd // 2), 1e30, np.float32)
+    dcos = G.dev_f32(np.concatenate([pad, cos, pad]))[64:64 + T]
+    dsin = G.dev_f32(np.concatenate([pad, sin, pad]))[64:64 + T]
+    out = G.Guarded(M, N, torch.float32 if f32 else torch.bfloat16)
+    coda.coda_gemm(G.dev_bf16(A), G.dev_bf16(B), [coda.rope(dcos, dsin, torch.from_numpy(pos).cuda(), hd, N), coda.store(out.t, f32=f32)])
+    torch.cuda.synchronize()
+    out.check_guards(); out.written()
+    ref = oracle.gemm_rowscale_rope(A, B, cos, sin, np.clip(pos, 0, T - 1).astype(np.int32), hd, N)
+    if f32:
+        G.assert_f32_signed_close(G.host_f64(out.t), ref, "rope clamp f32")
+    else:
+        G.assert_bf16_close(G.host_f64(out.t), ref, "rope clamp")
 
 
 @pytest.mark.parametrize("M,N,K", [(512, 512, 128), (520, 264, 200)])

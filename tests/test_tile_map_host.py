@@ -1,0 +1,95 @@
+"""Host-side check of the launch geometry: the map from workgroup id to (output tile, part of K) -- the split-K work-item
+lookup composed with the XCD-aware tile order -- compiled for the host from the kernels' own header, must reach every
+(tile, part) of a launch exactly once, and the parts of a shared tile must cut its K-steps into contiguous, even,
+non-empty ranges.  Covers the grids of every benchmark configuration, the split-K shapes and ragged tile counts."""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+
+@pytest.fixture(scope="module")
+def hostlib(tmp_path_factory):
+    so = str(tmp_path_factory.mktemp("tile_map") / "tile_map_host.so")
+    subprocess.run([HIPCC, "--offload-host-only", "-O1", "-std=c++17", "-fPIC", "-shared", "-Wno-inline-asm", "-o", so,
+                    os.path.join(ROOT, "tests", "tile_map_host.hip")], check=True, capture_output=True)
+    lib = ctypes.CDLL(so)
+    lib.host_plan.restype = ctypes.c_size_t
+    lib.host_plan.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
+    lib.host_tile_map.restype = None
+    lib.host_tile_map.argtypes = [ctypes.c_int] * 6 + [ctypes.POINTER(ctypes.c_int)]
+    return lib
+
+
+def launch_map(lib, M, N, K, f8=False, use_plan=True):
+    tiles_m, tiles_n = -(-M // 256), -(-N // 256)
+    step = 64 if f8 else 32
+    kt_all = -(-K // (2 * step)) * 2                 # K-steps, in whole pairs
+    plan = (ctypes.c_int * 3)()
+    need = lib.host_plan(M, N, K, int(f8), plan)
+    parts, first, shared = (plan[0], plan[1], plan[2]) if use_plan else (1, 0, 0)
+    tiles = tiles_m * tiles_n
+    nwg = tiles if parts <= 1 else first + (tiles - first) * parts
+    out = (ctypes.c_int * (7 * nwg))()
+    lib.host_tile_map(tiles_m, tiles_n, parts, first, kt_all, nwg, out)
+    return np.array(out, dtype=np.int64).reshape(nwg, 7), (tiles_m, tiles_n, kt_all, parts, first, shared, need)
+
+
+# (M, N, K): the benchmark step, the 8B chain, the LM head, the 70B-style sweep point, split-K shapes (few tiles; a
+# partly filled last round: 320 and 384 tiles), ragged tile counts, a single tile
+SHAPES = [(8192, 16384, 2048), (8192, 2048, 8192), (8192, 8192, 2048), (16384, 6144, 4096), (16384, 28672, 4096),
+          (16384, 4096, 14336), (8192, 32768, 4096), (8192, 57344, 8192), (512, 512, 8192), (1024, 1024, 8192),
+          (2048, 2048, 8192), (5120, 4096, 8192), (6144, 4096, 8192), (256, 256, 6272), (504, 264, 4168), (8200, 8192, 8192),
+          (8448, 2304, 200), (4000, 4000, 4000), (256, 256, 64), (8, 8, 8), (69632, 256, 8192)]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+@pytest.mark.parametrize("f8", [False, True])
+def test_every_tile_and_part_is_reached_exactly_once(hostlib, M, N, K, f8):
+    m, (tiles_m, tiles_n, kt_all, parts, first, shared, need) = launch_map(hostlib, M, N, K, f8)
+    tiles = tiles_m * tiles_n
+    assert ((m[:, 0] >= 0) & (m[:, 0] < tiles_m) & (m[:, 1] >= 0) & (m[:, 1] < tiles_n)).all()
+    keys = [(int(r[0]), int(r[1]), int(r[2])) for r in m]
+    assert len(set(keys)) == len(keys), "two workgroups share a (tile, part)"
+    per_tile = {}
+    for r in m:
+        per_tile.setdefault((int(r[0]), int(r[1])), []).append(r)
+    assert len(per_tile) == tiles, "some tile has no workgroup"
+    n_shared = 0
+    for rows in per_tile.values():
+        rows = sorted(rows, key=lambda r: r[2])
+        nsplit = int(rows[0][3])
+        assert len(rows) == nsplit and [int(r[2]) for r in rows] == list(range(nsplit))
+        assert all(int(r[3]) == nsplit for r in rows)
+        k = 0
+        for r in rows:                                # contiguous, even, non-empty ranges that cover all K-steps
+            assert int(r[4]) == k and int(r[5]) > 0 and int(r[5]) % 2 == 0
+            k += int(r[5])
+        assert k == kt_all
+        if nsplit > 1:
+            n_shared += 1
+            assert len({int(r[6]) for r in rows}) == 1 and 0 <= int(rows[0][6]) < shared   # one exchange slot per shared tile
+    assert n_shared == (shared if parts > 1 else 0)
+    if parts > 1:
+        slots = {int(r[6]) for r in m if r[3] > 1}
+        assert slots == set(range(shared)), "exchange slots are not a permutation"
+        assert need == 1024 + shared * parts * 256 * 256 * 4
+        assert shared <= 256, "ticket counters live in the first 1024 bytes of the workspace"
+    else:
+        assert need == 0
+
+
+def test_each_xcd_walks_a_compact_patch(hostlib):
+    """Workgroups are dealt round-robin to the 8 XCDs; the 32 tiles an XCD runs at a time (one round of 256) form an
+    8 x 4 patch, so that they share 8 + 4 operand panels in that XCD's L2."""
+    m, (tiles_m, tiles_n, *_rest) = launch_map(hostlib, 8192, 16384, 2048, use_plan=False)
+    for rnd in range(0, m.shape[0], 256):
+        for x in range(8):
+            t = m[rnd + x:rnd + 256:8]
+            assert len(t) == 32
+            assert len(set(t[:, 0].tolist())) + len(set(t[:, 1].tolist())) <= 12 + 2, "patch of XCD %d in round %d is not compact" % (x, rnd // 256)
