@@ -429,15 +429,35 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
             const bool mok = !EDGE || m < p.M;
             const float rs = rsv[i];
             const int yy = yv[i];
-            float mx = NEG_INF;
+            // row maximum of v = a * rs without scaling every element: the extreme of the raw accumulators in the direction of
+            // rs's sign, scaled once (a monotone map of the same fp32 products, so it is the maximum of the rounded v exactly)
+            float hi = NEG_INF, lo = -NEG_INF;
 #pragma unroll
             for (int u = 0; u < NU; ++u) {
                 const int n = nw + u * UC + lcol;
                 if (mok && (!EDGE || n < p.N)) {
-                    const f32x4 a = acc.get(i, u) * rs;
-                    mx = fmaxf(fmaxf(mx, fmaxf(a[0], a[1])), fmaxf(a[2], a[3]));
-                    const unsigned e = (unsigned)(yy - n);          // the target column falls into this unit iff e < 4
-                    if (e < 4u) p.lse_tgt[m] = e == 0 ? a[0] : (e == 1 ? a[1] : (e == 2 ? a[2] : a[3]));
+                    const f32x4 a = acc.get(i, u);
+                    hi = fmaxf(fmaxf(hi, fmaxf(a[0], a[1])), fmaxf(a[2], a[3]));
+                    lo = fminf(fminf(lo, fminf(a[0], a[1])), fminf(a[2], a[3]));
+                }
+            }
+            float mx = rs >= 0.0f ? hi * rs : lo * rs;
+            if (hi == NEG_INF) mx = NEG_INF;                          // no valid column in this lane's part of the row
+            // maximum over the wave's 64 columns of the row first (the lanes that share the row exchange it), so that all
+            // of them take their exponentials against the same reference and the sums simply add up
+#pragma unroll
+            for (int off = LR; off < 64; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+            // the target logit: at most one unit of the wave's 64 columns holds column y[i]
+            {
+                const unsigned e0 = (unsigned)(yy - (nw + lcol));      // distance from the lane's first column
+                if (mok && e0 < (unsigned)WTN && (e0 & (UC - 1)) < 4u && (!EDGE || yy < p.N)) {
+#pragma unroll
+                    for (int u = 0; u < NU; ++u)
+                        if ((int)(e0 / UC) == u) {
+                            const f32x4 a = acc.get(i, u) * rs;
+                            const unsigned e = e0 & 3u;
+                            p.lse_tgt[m] = e == 0 ? a[0] : (e == 1 ? a[1] : (e == 2 ? a[2] : a[3]));
+                        }
                 }
             }
             // exp(a * rs - mx) as one multiply-add and one base-2 exponential per element
@@ -453,13 +473,7 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
                     for (int e = 0; e < 4; ++e) sm += __builtin_amdgcn_exp2f(__builtin_fmaf(a[e], c2, d2));
                 }
             }
-#pragma unroll
-            for (int off = LR; off < 64; off <<= 1) {
-                const float mo = __shfl_xor(mx, off, 64), so = __shfl_xor(sm, off, 64);
-                const float mm = fmaxf(mx, mo);
-                sm = (mx == NEG_INF ? 0.0f : sm * __expf(mx - mm)) + (mo == NEG_INF ? 0.0f : so * __expf(mo - mm));
-                mx = mm;
-            }
+            sm = row_lanes_sum<LR>(sm);
             if (lane < LR) {
                 red[wn * BM + wm * WTM + i * LR + lane] = mx;
                 red[C::WGN * BM + wn * BM + wm * WTM + i * LR + lane] = sm;
@@ -490,6 +504,7 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
         // Per 64-row pass the region holds the C rows and the O_in rows side by side; results overwrite them in place.
         constexpr int RB = WTN * 2, P = 64, FPP = P / LR;
         static_assert(WTN == 64 && WTM % P == 0 && 2 * P * RB <= REG, "staging pass");
+        static_assert((C::WGM * C::BN + C::WGM * C::WGN * WTN) * 4 <= 2 * C::WGN * C::BM * 4, "gamma strips fit behind the column sums in `red`");
         using St = Stage<RB>;
         const uint32_t ulane = St::template unit_lane<8, LR>(lane);
         unsigned char *rego = reg + P * RB;
@@ -497,25 +512,25 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
         f32x4 dg[NU];
 #pragma unroll
         for (int u = 0; u < NU; ++u) dg[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // the wave's 64 gamma values wait in LDS (a private 256-byte strip of `red` behind the part the column reduction
+        // uses) instead of in 16 registers that would have to live across both passes
+        float *gstrip = red + C::WGM * C::BN + wave * WTN;
+        {
+            const int n = nw + lane;
+            gstrip[lane] = (!EDGE || n < p.N) ? p.rn_gamma[n] : 0.0f;
+        }
 #pragma unroll
         for (int ps = 0; ps < WTM / P; ++ps) {
             const int r0 = ps * P;
-            // the pass's row factors and the wave's gamma values first, so that they travel with the tile loads instead of
-            // waiting, block by block, behind the previous pass's stores
+            // the pass's row factors first, so that they travel with the tile loads instead of waiting, block by block,
+            // behind the previous pass's stores
             float rrv[FPP], zzv[FPP];
-            f32x4 gmv[NU];
 #pragma unroll
             for (int fi = 0; fi < FPP; ++fi) {
                 const int m = mw + (ps * FPP + fi) * LR + lrow;
                 const bool mok = !EDGE || m < p.M;
                 rrv[fi] = mok ? p.rn_r[m] : 0.0f;
                 zzv[fi] = mok ? p.rn_z[m] * p.rn_zscale : 0.0f;
-            }
-#pragma unroll
-            for (int u = 0; u < NU; ++u) {
-                const int nl = u * UC + lcol;
-                gmv[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (!EDGE || nw + nl < p.N) gmv[u] = *reinterpret_cast<const f32x4 *>(p.rn_gamma + nw + nl);
             }
             stage_load<RB, P, EDGE, true>(reg, reinterpret_cast<const unsigned char *>(p.rn_c + (int64_t)(mw + r0) * p.ld_rn_c + nw),
                                     p.ld_rn_c * 2, rows_ok - r0, cols_ok * 2, lane);
@@ -533,7 +548,7 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
                     const int nl = u * UC + lcol;
                     const bool ok = mok && (!EDGE || nw + nl < p.N);
                     const uint32_t ua = St::template unit_addr<LR>(ulane, fi, u * UC * 2);
-                    const f32x4 gm = gmv[u];
+                    const f32x4 gm = *reinterpret_cast<const f32x4 *>(gstrip + nl);
                     const u32x2 cw = *reinterpret_cast<const u32x2 *>(reg + ua);
                     const f32x4 d = acc.get(i, u);
                     const f32x4 cn = f32x4{bf16_lo(cw[0]), bf16_hi(cw[0]), bf16_lo(cw[1]), bf16_hi(cw[1])} * rr;
@@ -543,6 +558,9 @@ __device__ __forceinline__ void run_epilogue(ACC &acc, const GemmParams &p, int 
                         o += f32x4{bf16_lo(ow[0]), bf16_hi(ow[0]), bf16_lo(ow[1]), bf16_hi(ow[1])};
                     }
                     if (ok) dg[u] += d * cn;
+                    // pin the column sums here: otherwise their multiply-add chains are sunk to the point of use behind the
+                    // last pass and every cn of the tile has to stay live (spilled) until then
+                    asm volatile("" : "+v"(dg[u]));
                     const f32x4 co = cn * gm;
                     *reinterpret_cast<u32x2 *>(rego + ua) = u32x2{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
                     *reinterpret_cast<u32x2 *>(reg + ua) = u32x2{pack_bf16x2(co[0], co[1]), pack_bf16x2(co[2], co[3])};

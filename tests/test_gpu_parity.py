@@ -621,6 +621,37 @@ def _extreme_pairs(g, rows, pairs):
     return synth.f32_to_bf16_bits(Z)
 
 
+def test_logits_lse_with_row_scales_of_either_sign(oracle):
+    """The log-sum-exp partials take the row maximum from the raw accumulators in the direction of the row scale's sign:
+    negative, zero and positive row scales, and targets on the last valid column of a ragged tile."""
+    g = rng(97)
+    M, N, K = 300, 520, 136
+    A, B = operands(g, M, N, K, False, False, b_std=0.3)
+    r = synth.uniform_f32(g, (M,), -2.0, 2.0)
+    r[::5] = 0.0
+    r[1::5] = -np.abs(r[1::5])
+    y = g.integers(0, N, size=M).astype(np.int32)
+    y[:8] = N - 1
+    y[8:16] = [0, 3, 4, 15, 16, 63, 64, 255]
+    Z = G.Guarded(M, N, torch.bfloat16)
+    nblk = coda.coda_row_partial_blocks(N)
+    pmax = torch.full((nblk, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    psum = torch.full((nblk, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    zt = torch.full((M,), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    lse = torch.empty(M, dtype=torch.float32, device="cuda")
+    dy, dr = torch.from_numpy(y).cuda(), G.dev_f32(r)
+    coda.coda_gemm(G.dev_bf16(A), G.dev_bf16(B), [coda.row_scale(dr), coda.lse_partial(dy, pmax, psum, zt), coda.store(Z.t)])
+    coda.coda_lse_finalize(pmax, psum, M, nblk, lse_out=lse)
+    torch.cuda.synchronize()
+    Z.check_guards(); Z.written()
+    assert int((pmax == G.SENTINEL_F32).sum().item()) == 0 and int((zt == G.SENTINEL_F32).sum().item()) == 0
+    refZ, refzt, reflse = oracle.gemm_rowscale_lse(A, B, y, r=r.astype(np.float64))
+    G.assert_bf16_close(G.host_f64(Z.t), refZ, "logits, signed row scales")
+    G.assert_f32_signed_close(G.host_f64(zt), refzt, "target logit, signed row scales")
+    d = np.abs(G.host_f64(lse) - reflse)
+    assert (d <= 1e-3 * np.maximum(np.abs(reflse), 1.0)).all(), "lse max delta %.3g" % d.max()
+
+
 def test_swiglu_forward_saturated_gates(oracle):
     M, N, K = 256, 512, 64
     g = rng(31)
