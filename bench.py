@@ -26,10 +26,28 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 FLOP/clk x 2.4 GHz
 
-# Bytes per launch of the dominant kernel (up-projection) crossing the L2 -> fabric boundary, measured with
-# rocprofv3 --pmc: FETCH_SIZE 393614 KiB x 2.0 (calibration factor from a plain copy) + WRITE_SIZE 131076 KiB x 1.0;
-# see profiles/gemm_epilogue_llama1b_mlp_block_hbm_traffic.md.  Algorithmic bytes are 234.9e6.
-MEASURED_TRAFFIC_BYTES = int(393597 * 1024 * 2.0 + 131330 * 1024)
+PEAK_HBM_TBS = 8.0          # MI355X HBM3E
+
+# Bytes per launch of the dominant kernel (up-projection) crossing the L2 -> fabric boundary.  A STORED figure, not measured
+# by this run: rocprofv3 --pmc counters of profiles/gemm_epilogue_llama1b_mlp_block_hbm_traffic.md (FETCH_SIZE and
+# WRITE_SIZE in KiB per dispatch, each scaled by the factor that the same counter shows for a plain 256 MiB copy in the
+# same profiling run).  Algorithmic bytes are 234.9e6.
+TRAFFIC_FETCH_KIB, TRAFFIC_FETCH_FACTOR = 393597, 2.0
+TRAFFIC_WRITE_KIB, TRAFFIC_WRITE_FACTOR = 131330, 1.0
+MEASURED_TRAFFIC_BYTES = int(TRAFFIC_FETCH_KIB * 1024 * TRAFFIC_FETCH_FACTOR + TRAFFIC_WRITE_KIB * 1024 * TRAFFIC_WRITE_FACTOR)
+TRAFFIC_SOURCE = ("stored figure from profiles/gemm_epilogue_llama1b_mlp_block_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE x %.1f + "
+                  "WRITE_SIZE x %.1f, factors from a plain 256 MiB copy in the same profiling run; counted at the L2 -> fabric "
+                  "boundary, in front of the 256 MB Infinity Cache); not measured by this run" % (TRAFFIC_FETCH_FACTOR, TRAFFIC_WRITE_FACTOR))
+
+
+def roof_entry(kernel, shape, flop, alg_bytes, ms):
+    """Roofline record of one GEMM+epilogue launch: bf16 MFMA peak is the bound of every kernel here (arithmetic intensity
+    455 ... 4587 FLOP/B against a ridge of 315); the HBM floor is the algorithmic bytes at 8 TB/s."""
+    tf = flop / (ms * 1e-3) * 1e-12
+    return {"kernel": kernel, "shape": shape, "bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS,
+            "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "ms": round(ms, 4),
+            "algorithmic_bytes": int(alg_bytes), "hbm_floor_us": round(alg_bytes / (PEAK_HBM_TBS * 1e12) * 1e6, 1),
+            "mfma_floor_us": round(flop / (PEAK_BF16_TFLOPS * 1e12) * 1e6, 1)}
 
 
 def main():
@@ -37,6 +55,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--settle-steps", type=int, default=200,
+                    help="untimed steps of the same work run before the warm-up, so that the clocks have ramped and the result "
+                         "does not depend on how small --warmup is (reported in the JSON line)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unfused", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
@@ -129,6 +150,12 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # Settle phase (untimed, stated in the JSON): the chip needs a few tenths of a second of this load before its clocks
+    # and the power controller have settled; a run with a handful of warm-up steps otherwise measures the ramp.
+    for _ in range(max(0, args.settle_steps)):
+        fused_step(None)
+    torch.cuda.synchronize()
+
     # Timed region: HIP events bracket only the dominant kernel (each event pair costs the step about 6 us of launch gaps);
     # the other three kernels get their events in a second, untimed pass of the same step.
     rec = {"up": []}
@@ -136,6 +163,14 @@ def main():
     rec_rest = {k: [] for k in kernels if k != "up"}
     run(fused_step, args.steps, 2, rec_rest)
     rec.update(rec_rest)
+    # spread of the step itself: every step of one more pass between its own pair of events (the events cost a few us each)
+    step_ev = []
+    for _ in range(args.steps):
+        a, b = ev(), ev()
+        a.record(); fused_step(None); b.record()
+        step_ev.append((a, b))
+    torch.cuda.synchronize()
+    step_ms = np.array([a.elapsed_time(b) for a, b in step_ev])
     kern_all = {k: np.array([a.elapsed_time(b) for a, b in rec[k]]) for k in kernels}
     kern_ms = {k: float(kern_all[k].mean()) for k in kernels}
     kern_tflops = {k: flops[k] / (kern_ms[k] * 1e-3) * 1e-12 for k in kernels}
@@ -150,6 +185,10 @@ def main():
                                "dY*Wdown^T+SwiGLU-bwd, H^T*dY fp32-accumulate) + aux reductions",
                    "tokens": M, "hidden": d, "intermediate": F, "flop_per_step": total_flops},
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "settle": {"steps": args.settle_steps, "what": "untimed steps of the same work ahead of the warm-up (clock ramp)"},
+        "step_ms_spread": {"median": round(float(np.median(step_ms)), 4), "min": round(float(step_ms.min()), 4),
+                           "max": round(float(step_ms.max()), 4), "std": round(float(step_ms.std()), 4),
+                           "what": "each step of one further pass between its own pair of HIP events"},
         "kernels": {k: {"ms": round(kern_ms[k], 4), "ms_std": round(float(kern_all[k].std()), 4),
                         "ms_min": round(float(kern_all[k].min()), 4), "tflops": round(kern_tflops[k], 1),
                         "pct_peak": round(100.0 * kern_tflops[k] / PEAK_BF16_TFLOPS, 2)} for k in kernels},
@@ -157,8 +196,18 @@ def main():
                         "step right after it (every event pair adds about 6 us of launch gap to a step)",
         "roofline": {"kernel": "gemm_kernel<EPI_SWIGLU_FWD> (up-projection: row scale + SwiGLU)", "bound": "mfma",
                      "achieved": round(kern_tflops["up"], 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(kern_tflops["up"] / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES},
+                     "frac": round(kern_tflops["up"] / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES,
+                     "traffic_source": TRAFFIC_SOURCE, "algorithmic_bytes": int(2 * (M * d + d * 2 * F + M * F) + 4 * M)},
     }
+    # one roofline record per GEMM+epilogue kernel (algorithmic bytes: every operand and output once)
+    alg = {"up": 2 * (M * d + d * 2 * F + M * F) + 4 * M,
+           "down": 2 * (M * F + F * d + 2 * M * d) + 4 * nblk * M,
+           "bwd_act": 2 * (M * d + F * d + 2 * M * 2 * F),
+           "bwd_wgt": 2 * (M * F + M * d) + 8 * F * d}
+    names = {"up": "up-projection: row scale + SwiGLU", "down": "down-projection: residual + row sum of squares",
+             "bwd_act": "dY W_down^T + SwiGLU backward", "bwd_wgt": "H^T dY + fp32 accumulate"}
+    shapes = {"up": [M, 2 * F, d], "down": [M, d, F], "bwd_act": [M, F, d], "bwd_wgt": [F, d, M]}
+    out["rooflines"] = {"llama1b_" + k: roof_entry(names[k], shapes[k], flops[k], alg[k], kern_ms[k]) for k in kernels}
 
     def time_kernel(fn, reps=10, warm=3):
         for _ in range(warm):
@@ -229,6 +278,9 @@ def main():
         out["extra_kernels"] = {
             "qkv_8b_rowscale_rope": {"shape": [Mq, Nq, Kq], "ms": round(ms_rope, 4), "tflops": round(fl / ms_rope * 1e-9, 1)},
             "qkv_8b_plain_store": {"shape": [Mq, Nq, Kq], "ms": round(ms_plain, 4), "tflops": round(fl / ms_plain * 1e-9, 1)}}
+        out["rooflines"]["llama8b_qkv_rowscale_rope"] = roof_entry(
+            "QKV projection: row scale + RoPE (Kernels 1/7)", [Mq, Nq, Kq], fl,
+            2 * (Mq * Kq + Kq * Nq + Mq * Nq) + 8 * Mq + 2 * 4 * 2048 * 64, ms_rope)
         del Xq, Wq, Q
         # Kernel 9 at the backward shape of the same projection: dY[M x 6144] Wqkv^T with RMSNorm backward,
         # residual-gradient accumulation, recomputed normalised activation and dgamma partials
@@ -250,6 +302,9 @@ def main():
             ms_k9 = min(ms_k9, time_kernel(f_k9))
         out["extra_kernels"]["qkv_bwd_8b_rmsnorm_backward"] = {"shape": [Mb, Nb, Kb], "ms": round(ms_k9, 4), "tflops": round(flb / ms_k9 * 1e-9, 1)}
         out["extra_kernels"]["qkv_bwd_8b_plain_store"] = {"shape": [Mb, Nb, Kb], "ms": round(ms_pl, 4), "tflops": round(flb / ms_pl * 1e-9, 1)}
+        out["rooflines"]["llama8b_qkv_bwd_rmsnorm_backward"] = roof_entry(
+            "dY Wqkv^T + RMSNorm backward, O_in, C_out, dgamma partials (Kernel 9)", [Mb, Nb, Kb], flb,
+            2 * (Mb * Kb + Nb * Kb + 4 * Mb * Nb) + 4 * pb.numel() + 4 * (2 * Mb + Nb), ms_k9)
         del dYq, Wt, Cq, Oi, Oo, Co, pb
         # Kernel 8 at an LM-head shape: logits + log-sum-exp partials + target logit, then the aux combine
         Ml, Kl, Nl = 8192, 4096, 32768
@@ -273,6 +328,11 @@ def main():
             ms_l = min(ms_l, time_kernel(f_lse, reps=5))
         out["extra_kernels"]["lm_head_logits_lse_loss"] = {"shape": [Ml, Nl, Kl], "ms": round(ms_l, 4), "tflops": round(fll / ms_l * 1e-9, 1)}
         out["extra_kernels"]["lm_head_plain_store"] = {"shape": [Ml, Nl, Kl], "ms": round(ms_p, 4), "tflops": round(fll / ms_p * 1e-9, 1)}
+        ms_lg = min(time_kernel(lambda: coda.coda_gemm(Xl, Wl, [coda.row_scale(rl), coda.lse_partial(yl, pm, psm, ztl), coda.store(Zl)]), reps=5)
+                    for _ in range(2))
+        out["rooflines"]["lm_head_logits_lse_partials"] = roof_entry(
+            "LM head: row scale + log-sum-exp partials + logits store (Kernels 3/8), without the aux combine", [Ml, Nl, Kl], fll,
+            2 * (Ml * Kl + Kl * Nl + Ml * Nl) + 4 * (2 * nb * Ml + 3 * Ml), ms_lg)
         del Xl, Wl, Zl, pm, psm
 
         def rnd(shape, std=1.0):
@@ -296,6 +356,22 @@ def main():
         ms_c = min(time_kernel(f_chain, reps=5, warm=2) for _ in range(2))
         out["extra_kernels"]["block_8b_chain_qkv_up_down"] = {"tokens": Mc, "hidden": dc, "intermediate": Fc, "ms": round(ms_c, 4),
                                                               "tflops": round(flc / ms_c * 1e-9, 1)}
+        # the chain's three GEMMs one by one (events around a loop of each), for their roofline records
+        ms_q = min(time_kernel(lambda: coda.coda_gemm(Xc, Wq8, [coda.row_scale(rc), coda.store(Qc)]), reps=5, warm=2) for _ in range(2))
+        ms_u = min(time_kernel(lambda: coda.coda_gemm(Xc, Wu8, [coda.row_scale(rc), coda.swiglu_fwd(), coda.store(Hc)]), reps=5, warm=2)
+                   for _ in range(2))
+        ms_d = min(time_kernel(lambda: coda.coda_gemm(Hc, Wd8, [coda.add_tile(Rc), coda.row_sumsq(pc), coda.store(Yc)]), reps=5, warm=2)
+                   for _ in range(2))
+        out["rooflines"]["llama8b_qkv_rowscale"] = roof_entry("QKV projection: row scale (Kernel 5)", [Mc, Nq8, dc], 2.0 * Mc * Nq8 * dc,
+                                                              2 * (Mc * dc + dc * Nq8 + Mc * Nq8) + 4 * Mc, ms_q)
+        out["rooflines"]["llama8b_up_rowscale_swiglu"] = roof_entry("up-projection: row scale + SwiGLU (Kernel 6)", [Mc, 2 * Fc, dc],
+                                                                    2.0 * Mc * 2 * Fc * dc, 2 * (Mc * dc + dc * 2 * Fc + Mc * Fc) + 4 * Mc, ms_u)
+        out["rooflines"]["llama8b_down_residual_sumsq"] = roof_entry("down-projection: residual + row sum of squares (Kernel 4)", [Mc, dc, Fc],
+                                                                     2.0 * Mc * dc * Fc, 2 * (Mc * Fc + Fc * dc + 2 * Mc * dc) + 4 * nbc * Mc, ms_d)
+        out["rooflines"]["llama8b_chain_qkv_up_down"] = roof_entry(
+            "QKV -> up -> down + aux combine, end to end", [Mc, dc, Fc], flc,
+            sum(out["rooflines"][k]["algorithmic_bytes"] for k in ("llama8b_qkv_rowscale", "llama8b_up_rowscale_swiglu", "llama8b_down_residual_sumsq")),
+            ms_c)
         del Xc, Wq8, Wu8, Wd8, Rc, Qc, Hc, Yc
 
         # the dominant kernel with cold caches: rotate over enough operand sets to exceed the 256 MB Infinity Cache
