@@ -50,6 +50,103 @@ def roof_entry(kernel, shape, flop, alg_bytes, ms):
             "mfma_floor_us": round(flop / (PEAK_BF16_TFLOPS * 1e12) * 1e6, 1)}
 
 
+SINGLE_KERNELS = ["llama1b_up", "llama1b_down", "llama1b_bwd_act", "llama1b_bwd_wgt", "llama8b_qkv_rowscale",
+                  "llama8b_qkv_rowscale_rope", "llama8b_up_rowscale_swiglu", "llama8b_down_residual_sumsq",
+                  "llama8b_qkv_bwd_rmsnorm_backward", "lm_head_logits_lse_partials", "copy256"]
+
+
+def single_kernel(name, steps, warmup):
+    """One named kernel launched `steps` times between a pair of HIP events: the launches a profiler run should see."""
+    import torch
+    from paper_2605_19269_amd import coda
+    dev = "cuda"
+    f32, b16 = dict(dtype=torch.float32, device=dev), dict(dtype=torch.bfloat16, device=dev)
+    g = torch.Generator(device=dev).manual_seed(17)
+
+    def rnd(shape, std=1.0):
+        return (torch.randn(shape, device=dev, generator=g) * std).to(torch.bfloat16)
+
+    def vec(n, lo=0.5, hi=1.5):
+        return torch.rand(n, device=dev, generator=g) * (hi - lo) + lo
+
+    if name == "copy256":
+        src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        fn, shape, flop, nbytes, what = (lambda: dst.copy_(src)), [256 * 1024 * 1024], 0.0, 2 * 256 * 1024 * 1024, "plain device copy"
+    elif name in ("llama1b_up", "llama8b_up_rowscale_swiglu"):
+        M, K, N = (8192, 2048, 16384) if name == "llama1b_up" else (16384, 4096, 28672)
+        X, W, r, H = rnd((M, K)), rnd((K, N), 0.02), vec(M), torch.empty((M, N // 2), **b16)
+        fn = lambda: coda.coda_gemm(X, W, [coda.row_scale(r), coda.swiglu_fwd(), coda.store(H)])
+        shape, flop, nbytes, what = [M, N, K], 2.0 * M * N * K, 2 * (M * K + K * N + M * N // 2) + 4 * M, "row scale + SwiGLU (Kernel 6)"
+    elif name in ("llama1b_down", "llama8b_down_residual_sumsq"):
+        M, K, N = (8192, 8192, 2048) if name == "llama1b_down" else (16384, 14336, 4096)
+        Hh, W, R, Y = rnd((M, K)), rnd((K, N), 0.02), rnd((M, N)), torch.empty((M, N), **b16)
+        nb = coda.coda_row_partial_blocks(N)
+        part = torch.empty((nb, M), **f32)
+        fn = lambda: coda.coda_gemm(Hh, W, [coda.add_tile(R), coda.row_sumsq(part), coda.store(Y)])
+        shape, flop, nbytes, what = [M, N, K], 2.0 * M * N * K, 2 * (M * K + K * N + 2 * M * N) + 4 * nb * M, "residual + row sum of squares (Kernel 4)"
+    elif name == "llama1b_bwd_act":
+        M, K, N = 8192, 2048, 8192
+        dY, W, Z, dZ = rnd((M, K), 1e-2), rnd((N, K), 0.02), rnd((M, 2 * N)), torch.empty((M, 2 * N), **b16)
+        fn = lambda: coda.coda_gemm(dY, W, [coda.swiglu_bwd(Z), coda.store(dZ)], transB=True)
+        shape, flop, nbytes, what = [M, N, K], 2.0 * M * N * K, 2 * (M * K + N * K + 4 * M * N), "A B^T + SwiGLU backward (Kernel 10)"
+    elif name == "llama1b_bwd_wgt":
+        Kt, M, N = 8192, 8192, 2048
+        Hh, dY, Gb = rnd((Kt, M)), rnd((Kt, N), 1e-2), torch.randn((M, N), device=dev, generator=g) * 1e-3
+        fn = lambda: coda.coda_gemm(Hh, dY, [coda.accum_f32(Gb)], transA=True)
+        shape, flop, nbytes, what = [M, N, Kt], 2.0 * M * N * Kt, 2 * (Kt * M + Kt * N) + 8 * M * N, "A^T B + fp32 accumulate (Theorem 1)"
+    elif name in ("llama8b_qkv_rowscale", "llama8b_qkv_rowscale_rope"):
+        from paper_2605_19269_amd import synth
+        M, K, N = 16384, 4096, 6144
+        X, W, r, Q = rnd((M, K)), rnd((K, N), 0.02), vec(M), torch.empty((M, N), **b16)
+        nbytes = 2 * (M * K + K * N + M * N) + 4 * M
+        if name.endswith("rope"):
+            cos_h, sin_h = synth.rope_tables(2048, 128)
+            cos_d, sin_d = torch.from_numpy(cos_h).to(dev), torch.from_numpy(sin_h).to(dev)
+            pos = (torch.arange(M, device=dev) % 2048).to(torch.int32)
+            fn = lambda: coda.coda_gemm(X, W, [coda.row_scale(r), coda.rope(cos_d, sin_d, pos, 128, 5120), coda.store(Q)])
+            nbytes += 4 * M + 2 * 4 * 2048 * 64
+            what = "row scale + RoPE (Kernels 1/7)"
+        else:
+            fn = lambda: coda.coda_gemm(X, W, [coda.row_scale(r), coda.store(Q)])
+            what = "row scale (Kernel 5)"
+        shape, flop = [M, N, K], 2.0 * M * N * K
+    elif name == "llama8b_qkv_bwd_rmsnorm_backward":
+        M, N, K = 16384, 4096, 6144
+        dY, W, C, Oi = rnd((M, K), 1e-2), rnd((N, K), 0.02), rnd((M, N)), rnd((M, N))
+        rr, zz, gg = vec(M), torch.randn(M, device=dev, generator=g) * 1e-3, vec(N)
+        Oo, Co = torch.empty((M, N), **b16), torch.empty((M, N), **b16)
+        pb = torch.empty((coda.coda_col_partial_blocks(M), N), **f32)
+        fn = lambda: coda.coda_gemm(dY, W, [coda.rmsnorm_bwd(C, rr, zz, gg, c_out=Co, dgamma_out=pb), coda.add_tile(Oi), coda.store(Oo)], transB=True)
+        shape, flop, nbytes = [M, N, K], 2.0 * M * N * K, 2 * (M * K + N * K + 4 * M * N) + 4 * pb.numel() + 4 * (2 * M + N)
+        what = "A B^T + RMSNorm backward, O_in, C_out, dgamma partials (Kernel 9)"
+    elif name == "lm_head_logits_lse_partials":
+        M, K, N = 8192, 4096, 32768
+        X, W, r, Z = rnd((M, K)), rnd((K, N), 0.02), vec(M), torch.empty((M, N), **b16)
+        y = torch.randint(0, N, (M,), device=dev, dtype=torch.int32, generator=g)
+        nb = coda.coda_row_partial_blocks(N)
+        pm, ps, zt = torch.empty((nb, M), **f32), torch.empty((nb, M), **f32), torch.empty(M, **f32)
+        fn = lambda: coda.coda_gemm(X, W, [coda.row_scale(r), coda.lse_partial(y, pm, ps, zt), coda.store(Z)])
+        shape, flop, nbytes = [M, N, K], 2.0 * M * N * K, 2 * (M * K + K * N + M * N) + 4 * (2 * nb * M + 3 * M)
+        what = "row scale + log-sum-exp partials + logits store (Kernels 3/8)"
+    else:
+        sys.exit("bench.py: unknown --kernel %r; one of %s" % (name, ", ".join(SINGLE_KERNELS)))
+    for _ in range(warmup):
+        fn()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(steps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / steps
+    rec = roof_entry(what, shape, flop, nbytes, ms) if flop else {"kernel": what, "ms": round(ms, 4), "bytes": nbytes,
+                                                                 "GBps": round(nbytes / ms * 1e-6, 1)}
+    rec.update({"name": name, "launches": steps, "warmup": warmup, "data": "synthetic"})
+    print(json.dumps(rec))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -67,6 +164,10 @@ def main():
                          "operand-bit toggling -- shows how far the power-limited clock, rather than the kernel, sets the rate. "
                          "Not the benchmark; the JSON line says so in `data`.")
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
+    ap.add_argument("--kernel", default=None,
+                    help="profiling aid: launch ONE named GEMM+epilogue kernel --steps times (after --warmup launches) and print "
+                         "its roofline record; names: " + ", ".join(SINGLE_KERNELS) + "; 'copy256' is a plain 256 MiB device "
+                         "copy of known traffic for scaling rocprofv3 --pmc byte counters")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (known traffic) so that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -81,6 +182,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
+    if args.kernel:
+        return single_kernel(args.kernel, args.steps, args.warmup)
     dev = "cuda"
     M, d, F = 8192, 2048, 8192
 
