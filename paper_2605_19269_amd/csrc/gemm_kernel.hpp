@@ -1082,42 +1082,78 @@ __device__ __host__ __forceinline__ WorkItem locate_workgroup(int splitk, int sp
 // Split-K exchange.  Every workgroup of a tile leaves its fp32 partial in the workspace and takes a
 // ticket; all but the last one to arrive return false (and must exit); the last one gets the sum of all partials,
 // added in split order so that it does not depend on who arrived last, and returns true.
+//
+// Coherence without cache-wide operations.  The workgroups of a tile may run on different XCDs, whose L2 caches are not
+// coherent with each other.  A device-scope release / acquire fence pair would write back and invalidate the WHOLE L2 of
+// the XCD (every dirty output line of every other tile on it, every operand panel its neighbours are re-using): that
+// cost the exchange about 35 us and slowed the tiles that run beside it.  Instead every access to the partials is a
+// device-scope (agent) relaxed atomic, which the hardware performs at the device's point of coherence (sc1: stores
+// write through, loads do not hit in a non-coherent cache), so only these lines travel:
+//   writer: sc1 stores of the partial (16 bytes per lane, inline asm: the compiler offers the scope bit only through
+//           atomics of at most 8 bytes); wait until they are acknowledged (vmcnt 0); workgroup barrier; one thread
+//           takes the ticket with a device-scope atomic add, issued after the barrier, hence after every store of the
+//           workgroup has been performed;
+//   reader: the ticket it drew says that all other workgroups' tickets, and therefore their stores, were performed;
+//           its sc1 loads, issued after the ticket returned, then read those values.
 // ---------------------------------------------------------------------------------
+// 16-byte device-scope (sc1) store / load.  The loads are issued from inline asm, invisible to the compiler's waitcnt
+// insertion: the caller waits with coherent_wait8 before it touches the values.
+__device__ __forceinline__ void coherent_store16(f32x4 *dst, f32x4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(v) : "memory");
+}
+__device__ __forceinline__ void coherent_load16(f32x4 &v, const f32x4 *src)
+{
+    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(src) : "memory");
+}
+// wait for all outstanding loads; the eight values are operands so that no use of them can be scheduled ahead of the wait
+__device__ __forceinline__ void coherent_wait8(f32x4 (&b)[8])
+{
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(b[4]), "+v"(b[5]), "+v"(b[6]), "+v"(b[7])
+                 :
+                 : "memory");
+}
+
 template <class C, class ACC>
-__device__ __forceinline__ bool splitk_exchange(ACC &acc, const GemmParams &p, int tile_id, int split, int nsplit, float *red, int tid)   // tile_id: counted from split_from
+__device__ __forceinline__ bool splitk_exchange(ACC &acc, const GemmParams &p, int slot, int split, int nsplit, float *red, int tid)   // slot: the tile's index among the shared tiles
 {
     // Partial tile -> workspace in register order: float4 q of thread t at [q][t], fully coalesced.  The layout is
     // private to this exchange.
     constexpr int NQ = ACC::NB * ACC::NU;
-    static_assert(NQ * 4 * C::NT == C::BM * C::BN, "one float per output element");
-    f32x4 *part = reinterpret_cast<f32x4 *>(p.ws_part) + (size_t)tile_id * nsplit * NQ * C::NT;
+    static_assert(NQ * 4 * C::NT == C::BM * C::BN && NQ % 8 == 0, "one float per output element, whole batches of loads");
+    f32x4 *part = reinterpret_cast<f32x4 *>(p.ws_part) + (size_t)slot * nsplit * NQ * C::NT;
     f32x4 *mine = part + (size_t)split * NQ * C::NT + tid;
 #pragma unroll
     for (int i = 0; i < ACC::NB; ++i)
 #pragma unroll
-        for (int u = 0; u < ACC::NU; ++u) mine[(i * ACC::NU + u) * C::NT] = acc.get(i, u);
-    // Completed stores sit in this XCD's L2 (the vector L1 writes through).  One thread then does the device-scope
-    // release (L2 write-back) for the whole workgroup, takes the ticket, and -- if it is the last -- the acquire
-    // (L2 / L1 invalidate) on behalf of all waves of this compute unit.
+        for (int u = 0; u < ACC::NU; ++u) coherent_store16(mine + (i * ACC::NU + u) * C::NT, acc.get(i, u));
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     int *last = reinterpret_cast<int *>(red);
     if (tid == 0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        const unsigned ticket = __hip_atomic_fetch_add(p.ws_cnt + tile_id, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int is_last = ticket == (unsigned)(nsplit - 1);
-        if (is_last) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        *last = is_last;
+        const unsigned ticket = __hip_atomic_fetch_add(p.ws_cnt + slot, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *last = ticket == (unsigned)(nsplit - 1);
     }
     __syncthreads();
     if (!*last) return false;        // uniform: the whole workgroup leaves; nobody waits for anybody
+    // fixed order: part 0 + part 1 + ... (this workgroup's own part is read back like the others: a copy of the
+    // accumulators kept aside for it would not fit the register file); eight loads in flight per thread
     acc_zero(acc);
-    for (int sp = 0; sp < nsplit; ++sp) {          // fixed order
+    for (int sp = 0; sp < nsplit; ++sp) {
         const f32x4 *src = part + (size_t)sp * NQ * C::NT + tid;
 #pragma unroll
-        for (int i = 0; i < ACC::NB; ++i)
+        for (int q0 = 0; q0 < NQ; q0 += 8) {
+            f32x4 b[8];
 #pragma unroll
-            for (int u = 0; u < ACC::NU; ++u) acc.set(i, u, acc.get(i, u) + src[(i * ACC::NU + u) * C::NT]);
+            for (int k = 0; k < 8; ++k) coherent_load16(b[k], src + (q0 + k) * C::NT);
+            coherent_wait8(b);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int q = q0 + k;
+                acc.set(q / ACC::NU, q % ACC::NU, acc.get(q / ACC::NU, q % ACC::NU) + b[k]);
+            }
+        }
     }
     __syncthreads();                 // `red` (the flag) is reused by the epilogue
     return true;
