@@ -197,19 +197,17 @@ typedef struct coda_epi_op {
  * multiple of 8, M is free (edge tiles are predicated as for bf16).  Anything else is CODA_ERR_DTYPE (layout,
  * mixed dtypes) or CODA_ERR_SHAPE (sizes).
  *
- * workspace / workspace_bytes (device memory, 16-byte aligned; may be NULL): scratch for split-K.
- * Shapes with at most 64 output tiles (256 x 256, counted with a ragged edge) and K >= 2048 leave
- * most of the chip idle, and shapes with more than 256 tiles whose count modulo 256 is between 1 and
- * 128 end with a round of tiles that fills at most half of it (long contractions only: K >= 4096).  For them
- * coda_gemm_workspace_bytes returns a non-zero size, and a call
- * that brings that much workspace lets 2 to 8 workgroups share every output tile (first case) or every
- * tile of the last round (second case), each
- * contracting a contiguous part of K: partial tiles go to the workspace in fp32, the workgroup
- * that finishes last adds them up in a fixed order (the result does not depend on arrival
- * order) and runs the epilogue program on the sum.  Without a workspace (NULL) the same shape
- * runs unsplit.  A non-NULL workspace smaller than coda_gemm_workspace_bytes(...) is
- * CODA_ERR_WORKSPACE.  The workspace needs no initialisation and holds nothing between calls;
- * two calls that share one must not overlap in time.
+ * workspace / workspace_bytes (device memory, 16-byte aligned; may be NULL): scratch for sharing output tiles
+ * among workgroups (split-K / stream-K).  A shape with fewer than 256 output tiles (256 x 256, counted with a ragged
+ * edge) leaves compute units idle, and a shape with more ends with a partly filled round of tiles.  When those
+ * tiles (the "tail") number at most 144 and the contraction is long enough (K >= 2048, and every workgroup must be
+ * spared at least 64 K-steps of 32 elements), coda_gemm_workspace_bytes returns a non-zero size, and a call that brings
+ * that much workspace cuts the K-steps of the tail, laid end to end, into up to 256 equal contiguous ranges, one or two
+ * workgroups each (a range may end in one tile and begin in the next): partial tiles go to the workspace in fp32, and
+ * the workgroup that reaches a tile last adds its parts up in a fixed order (the result does not depend on arrival
+ * order) and runs the epilogue program on the sum.  Without a workspace (NULL) the same shape runs unsplit.  A non-NULL
+ * workspace smaller than coda_gemm_workspace_bytes(...) is CODA_ERR_WORKSPACE.  The workspace needs no initialisation
+ * and holds nothing between calls; two calls that share one must not overlap in time.
  */
 CODA_API coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, const coda_mat *A,
                       const coda_mat *B, const coda_epi_op *prog /* host */, int32_t n_ops,
@@ -222,7 +220,7 @@ CODA_API coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, co
  * (CODA_STATIC_WS_BYTES = 32 MiB + 1 KiB per GPU, part of the code object's data, held from library load until the
  * process ends) instead of a caller buffer.  The call allocates nothing and frees nothing.  Shapes that are not planned
  * for split-K do not touch the array.  A shape whose split-K plan needs more than the array holds
- * (coda_gemm_workspace_bytes(...) > CODA_STATIC_WS_BYTES, e.g. 2048 x 2048 x 8192: 64 tiles in 4 parts) is refused with
+ * (coda_gemm_workspace_bytes(...) > CODA_STATIC_WS_BYTES, e.g. 2048 x 2048 x 8192: 64 tiles in 4 parts each) is refused with
  * CODA_ERR_WORKSPACE and nothing is enqueued: run it through coda_gemm with a workspace of the caller's, or with NULL.
  * The array keeps whatever the previous call left in it; the ticket counters are cleared by a small kernel ahead of
  * every split launch (no memset node, so the call can be captured into a HIP graph).  All calls on one GPU share that
@@ -233,8 +231,8 @@ CODA_API coda_status coda_gemm(void *stream, int64_t M, int64_t N, int64_t K, co
 CODA_API coda_status coda_gemm_static_ws(void *stream, int64_t M, int64_t N, int64_t K, const coda_mat *A,
                                 const coda_mat *B, const coda_epi_op *prog /* host */, int32_t n_ops);
 
-/* Bytes of workspace that enable split-K for this shape; 0 when the shape is not split (the program does not matter;
-   the figure is sufficient for bf16 and for 8-bit operands alike).  Split-K is this library's answer to the
+/* Bytes of workspace that enable tile sharing for this shape; 0 when the shape runs unsplit (the program does not matter;
+   the figure is sufficient for bf16 and for 8-bit operands alike).  Sharing tiles is this library's answer to the
    tile-count quantisation that the paper leaves to its expert-written mainloop (Section 3.1: the mainloop is taken
    as given); nothing in the method depends on it. */
 CODA_API size_t coda_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, const coda_epi_op *prog /* host */,

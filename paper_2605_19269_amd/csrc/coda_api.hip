@@ -312,12 +312,15 @@ coda_status gemm_impl(void *stream, int64_t M, int64_t N, int64_t K, const coda_
         const size_t need = coda::splitk_bytes(pl);
         if (!aligned16(workspace)) return CODA_ERR_ALIGN;
         if (workspace_bytes < need) return CODA_ERR_WORKSPACE;
-        if (pl.parts > 1) {
-            p.splitk = pl.parts;
+        if (pl.chunks > 0) {
             p.split_from = pl.first;
+            p.tail_tiles = pl.tail;
+            p.tail_chunks = pl.chunks;
+            p.tail_pieces = pl.pieces;
+            p.ws_stride = pl.stride;
             p.ws_cnt = static_cast<unsigned *>(workspace);
             p.ws_part = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + coda::SPLITK_CNT_BYTES);
-            hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(256), 0, s, p.ws_cnt, pl.shared);
+            hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(256), 0, s, p.ws_cnt, pl.tail);
             if ((e = hipGetLastError()) != hipSuccess) return launch_status(e);
         }
     }

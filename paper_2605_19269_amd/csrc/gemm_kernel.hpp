@@ -71,13 +71,13 @@ struct GemmParams {
     // target column y[M] and the selected logit z_tgt[M]
     float *lse_max, *lse_sum, *lse_tgt;
     const int *lse_y;
-    // split-K (splitk <= 1 = off): tiles with id >= split_from are shared by `splitk` workgroups
-    // each, every one contracting a contiguous part of K (split_from = 0: all tiles; split_from = a whole number of
-    // 256-workgroup rounds: only the tiles of the last, partly filled round).  With t = tile - split_from, a workgroup
-    // leaves its fp32 partial tile in ws_part[t * splitk + split] and takes a
-    // ticket from ws_cnt[t] (zeroed before the launch); the last one to arrive adds the partials up in split order
-    // and runs the epilogue.
-    int splitk, split_from;
+    // Shared tiles (tail_chunks = 0: none).  Tiles below split_from run whole, one workgroup each.  The K-steps of the
+    // tail_tiles tiles from split_from on, laid end to end, are cut into tail_chunks equal contiguous ranges (see
+    // locate_workgroup; tail_pieces = 2 when ranges straddle tile boundaries: then two workgroups per range): a tile is then contracted by up to ws_stride workgroups, each of which
+    // leaves its fp32 partial in ws_part[(tile - split_from) * ws_stride + part] and takes a ticket from
+    // ws_cnt[tile - split_from] (zeroed before the launch); the last one to arrive adds the partials up in part order and
+    // runs the epilogue.
+    int split_from, tail_tiles, tail_chunks, tail_pieces, ws_stride;
     float *ws_part;
     unsigned *ws_cnt;
 };
@@ -1056,26 +1056,58 @@ __device__ __forceinline__ void dl_load16(uint32_t voff, const void *sbase, uint
                  : "memory", "m0");
 }
 
-// Virtual workgroup -> its work item: an output tile, a contiguous range of that tile's K-steps, and -- when the tile is
-// shared -- which of its `nsplit` parts this is and the tile's slot in the exchange workspace.  Tiles below split_from
-// are whole, the others are shared by `splitk` workgroups each (equal parts of K); the grid has
-// split_from + (tiles - split_from) * splitk workgroups.
+// Virtual workgroup -> its work items.  A work item is an output tile, a contiguous range of that tile's K-steps, and --
+// when the tile is shared -- which of its `nsplit` parts this is.
+//  * Workgroups below split_from (all of them when nothing is shared) own one whole tile each.
+//  * The others share the tail: the K-steps of the tail's tiles, laid end to end in units of K-step pairs, are cut into
+//    tail_chunks equal contiguous ranges ("stream-K" on the last, partly filled round of tiles, or on all tiles when
+//    there are few).  Range c lies in one tile or straddles the boundary between two: it then has two work items
+//    (`piece` 0 and 1), the end of one tile and the start of the next, each run by a workgroup of its own.  When the
+//    chunk count is a multiple of the tile count every tile is cut into equal parts and no range straddles.
+//    `bid` = split_from + c.
+// kcnt = 0: there is no such piece.
 struct WorkItem {
-    int tile, slot, split, nsplit, kbeg, kcnt;
+    int tile, slot, split, nsplit, kbeg, kcnt;    // slot: the tile's index within the tail
 };
-__device__ __host__ __forceinline__ WorkItem locate_workgroup(int splitk, int split_from, int bid, int KT_all)
+__device__ __host__ __forceinline__ WorkItem locate_workgroup(int split_from, int tail_tiles, int tail_chunks, int bid, int piece,
+                                                              int KT_all)
 {
-    WorkItem w = {bid, 0, 0, 1, 0, KT_all};
-    if (splitk > 1 && bid >= split_from) {
-        const int v = bid - split_from;
-        w.nsplit = splitk;
-        w.slot = v / w.nsplit;
-        w.tile = split_from + w.slot;
-        w.split = v % w.nsplit;
-        w.kbeg = (int)((int64_t)KT_all * w.split / w.nsplit);
-        w.kcnt = (int)((int64_t)KT_all * (w.split + 1) / w.nsplit) - w.kbeg;
+    WorkItem w = {bid, 0, 0, 1, 0, piece == 0 ? KT_all : 0};
+    if (tail_chunks == 0 || bid < split_from) return w;
+    const int64_t KP = KT_all / 2, total = (int64_t)tail_tiles * KP, c = bid - split_from;
+    const int64_t s0 = c * total / tail_chunks, s1 = (c + 1) * total / tail_chunks;    // this chunk: pairs [s0, s1)
+    const int64_t a0 = s0 / KP;
+    int64_t a, lo, hi;
+    if (piece == 0) {
+        a = a0;
+        lo = s0 - a0 * KP;
+        hi = (s1 < (a0 + 1) * KP ? s1 : (a0 + 1) * KP) - a0 * KP;
+    } else {
+        a = a0 + 1;
+        lo = 0;
+        hi = s1 - (a0 + 1) * KP;
     }
+    w.kcnt = 0;
+    if (hi <= lo) return w;
+    // chunks that reach into tile a: from the one that holds its first pair to the one that holds its last pair
+    const int64_t c_lo = ((a * KP + 1) * tail_chunks + total - 1) / total - 1;
+    const int64_t c_hi = (((a + 1) * KP) * tail_chunks + total - 1) / total - 1;
+    w.tile = split_from + (int)a;
+    w.slot = (int)a;
+    w.nsplit = (int)(c_hi - c_lo + 1);
+    w.split = (int)(c - c_lo);
+    w.kbeg = (int)(2 * lo);
+    w.kcnt = (int)(2 * (hi - lo));
     return w;
+}
+
+// Launch geometry: blocks below split_from own whole tiles; block split_from + piece * tail_chunks + c owns piece
+// `piece` of range c of the shared tail (kcnt = 0: that range has no such piece).
+__device__ __host__ __forceinline__ WorkItem locate_block(int split_from, int tail_tiles, int tail_chunks, int bid, int KT_all)
+{
+    if (tail_chunks == 0 || bid < split_from) return WorkItem{bid, 0, 0, 1, 0, KT_all};
+    const int v = bid - split_from;
+    return locate_workgroup(split_from, tail_tiles, tail_chunks, split_from + v % tail_chunks, v / tail_chunks, KT_all);
 }
 
 // ---------------------------------------------------------------------------------
@@ -1093,8 +1125,8 @@ __device__ __host__ __forceinline__ WorkItem locate_workgroup(int splitk, int sp
 //           atomics of at most 8 bytes); wait until they are acknowledged (vmcnt 0); workgroup barrier; one thread
 //           takes the ticket with a device-scope atomic add, issued after the barrier, hence after every store of the
 //           workgroup has been performed;
-//   reader: the ticket it drew says that all other workgroups' tickets, and therefore their stores, were performed;
-//           its sc1 loads, issued after the ticket returned, then read those values.
+//   reader: the ticket it drew (or the counter it read on arrival) says that all other workgroups' tickets, and therefore
+//           their stores, were performed; its sc1 loads, issued after that value returned, then read those values.
 // ---------------------------------------------------------------------------------
 // 16-byte device-scope (sc1) store / load.  The loads are issued from inline asm, invisible to the compiler's waitcnt
 // insertion: the caller waits with coherent_wait8 before it touches the values.
@@ -1106,56 +1138,77 @@ __device__ __forceinline__ void coherent_load16(f32x4 &v, const f32x4 *src)
 {
     asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(src) : "memory");
 }
-// wait for all outstanding loads; the eight values are operands so that no use of them can be scheduled ahead of the wait
-__device__ __forceinline__ void coherent_wait8(f32x4 (&b)[8])
+// wait for all outstanding loads; the loaded values are operands so that no use of them can be scheduled ahead of the wait
+__device__ __forceinline__ void coherent_wait(f32x4 (&b)[8])
 {
     asm volatile("s_waitcnt vmcnt(0)"
                  : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(b[4]), "+v"(b[5]), "+v"(b[6]), "+v"(b[7])
                  :
                  : "memory");
 }
+__device__ __forceinline__ void coherent_wait(f32x4 (&b)[4])
+{
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]) : : "memory");
+}
 
 template <class C, class ACC>
-__device__ __forceinline__ bool splitk_exchange(ACC &acc, const GemmParams &p, int slot, int split, int nsplit, float *red, int tid)   // slot: the tile's index among the shared tiles
+__device__ __forceinline__ bool splitk_exchange(ACC &acc, const GemmParams &p, int slot, int split, int nsplit, float *red, int tid)   // slot: the tile's index within the tail
 {
-    // Partial tile -> workspace in register order: float4 q of thread t at [q][t], fully coalesced.  The layout is
+    // Partial tile <-> workspace in register order: float4 q of thread t at [q][t], fully coalesced.  The layout is
     // private to this exchange.
     constexpr int NQ = ACC::NB * ACC::NU;
     static_assert(NQ * 4 * C::NT == C::BM * C::BN && NQ % 8 == 0, "one float per output element, whole batches of loads");
-    f32x4 *part = reinterpret_cast<f32x4 *>(p.ws_part) + (size_t)slot * nsplit * NQ * C::NT;
-    f32x4 *mine = part + (size_t)split * NQ * C::NT + tid;
-#pragma unroll
-    for (int i = 0; i < ACC::NB; ++i)
-#pragma unroll
-        for (int u = 0; u < ACC::NU; ++u) coherent_store16(mine + (i * ACC::NU + u) * C::NT, acc.get(i, u));
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    f32x4 *part = reinterpret_cast<f32x4 *>(p.ws_part) + (size_t)slot * p.ws_stride * NQ * C::NT;
+    int *flag = reinterpret_cast<int *>(red);
+    // Has everybody else already left their part?  Then this workgroup finishes the tile and need not store its own
+    // (the usual case for the workgroup that takes the longest or the latest part of a tile: half of the exchange's
+    // traffic).  The counter only ever counts parts whose stores have been performed.
+    if (tid == 0) *flag = __hip_atomic_load(p.ws_cnt + slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(nsplit - 1);
     __syncthreads();
-    int *last = reinterpret_cast<int *>(red);
-    if (tid == 0) {
-        const unsigned ticket = __hip_atomic_fetch_add(p.ws_cnt + slot, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *last = ticket == (unsigned)(nsplit - 1);
-    }
+    int is_last = *flag;
     __syncthreads();
-    if (!*last) return false;        // uniform: the whole workgroup leaves; nobody waits for anybody
-    // fixed order: part 0 + part 1 + ... (this workgroup's own part is read back like the others: a copy of the
-    // accumulators kept aside for it would not fit the register file); eight loads in flight per thread
-    acc_zero(acc);
-    for (int sp = 0; sp < nsplit; ++sp) {
-        const f32x4 *src = part + (size_t)sp * NQ * C::NT + tid;
+    if (!is_last) {
+        f32x4 *mine = part + (size_t)split * NQ * C::NT + tid;
 #pragma unroll
-        for (int q0 = 0; q0 < NQ; q0 += 8) {
-            f32x4 b[8];
+        for (int i = 0; i < ACC::NB; ++i)
 #pragma unroll
-            for (int k = 0; k < 8; ++k) coherent_load16(b[k], src + (q0 + k) * C::NT);
-            coherent_wait8(b);
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int q = q0 + k;
-                acc.set(q / ACC::NU, q % ACC::NU, acc.get(q / ACC::NU, q % ACC::NU) + b[k]);
-            }
+            for (int u = 0; u < ACC::NU; ++u) coherent_store16(mine + (i * ACC::NU + u) * C::NT, acc.get(i, u));
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) {
+            const unsigned ticket = __hip_atomic_fetch_add(p.ws_cnt + slot, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *flag = ticket == (unsigned)(nsplit - 1);
         }
+        __syncthreads();
+        is_last = *flag;
+        __syncthreads();             // the flag lies in LDS that the epilogue, or the fill of a following piece, reuses
+        if (!is_last) return false;  // uniform: the whole workgroup leaves this tile; nobody waits for anybody
     }
-    __syncthreads();                 // `red` (the flag) is reused by the epilogue
+    // Sum of all parts in part order, P0 + P1 + ..., so that it does not depend on who came last; this workgroup's own
+    // part comes from its registers (the same values it stored, or would have).  QB float4 per thread at a time: the
+    // batch's running sum is built beside the accumulators and replaces them (eight in flight with the 16-row
+    // accumulator layout; the 32-row layout's 16-register blocks leave room for four).
+    constexpr int QB = ACC::LR == 16 ? 8 : 4;
+#pragma unroll
+    for (int q0 = 0; q0 < NQ; q0 += QB) {
+        f32x4 t[QB];
+        for (int sp = 0; sp < nsplit; ++sp) {
+            f32x4 b[QB];
+            if (sp == split) {
+#pragma unroll
+                for (int k = 0; k < QB; ++k) b[k] = acc.get((q0 + k) / ACC::NU, (q0 + k) % ACC::NU);
+            } else {
+                const f32x4 *src = part + (size_t)sp * NQ * C::NT + tid;
+#pragma unroll
+                for (int k = 0; k < QB; ++k) coherent_load16(b[k], src + (q0 + k) * C::NT);
+                coherent_wait(b);
+            }
+#pragma unroll
+            for (int k = 0; k < QB; ++k) t[k] = sp == 0 ? b[k] : t[k] + b[k];
+        }
+#pragma unroll
+        for (int k = 0; k < QB; ++k) acc.set((q0 + k) / ACC::NU, (q0 + k) % ACC::NU, t[k]);
+    }
     return true;
 }
 
@@ -1202,34 +1255,40 @@ __device__ __forceinline__ bf16x8 dl_frag16(const unsigned char *tile, int row_b
 // RAGGED: M, N or K is not a whole number of tiles.  Tiles on the edge of M or N clamp their operand fetches and run the
 // bounds-checked epilogue; K is rounded up to whole pairs of K-steps and the tile fill stores zeros at the positions
 // past K.
+// LDS plan of the bf16 kernel.  PAIRED (A K-contiguous): three pair slots of A (two K-steps each) followed by four
+// single-step slots of B -- or, when B is K-contiguous as well (PAIRB), by two pair slots of B -- 160 KB; otherwise four
+// slots of [A | B].  The epilogue stages through the first EPI_RING bytes either way; `red` (row-reduction exchange;
+// second half: sum-exp of the log-sum-exp partials) follows them and, when PAIRED, lies inside the B slots, which are
+// free once the mainloop is over.
+template <class C, bool AK, bool BKC>
+struct DlLds {
+    static constexpr bool PAIRED = AK, PAIRB = AK && BKC;
+    static constexpr int S = C::STAGES;
+    static constexpr int EPI_RING = S * C::STAGE_BYTES, RED_BYTES = 2 * C::WGN * C::BM * 4;
+    static constexpr int A_REGION = PAIRED ? 3 * 2 * C::A_BYTES : 0;
+    static constexpr int LDS_BYTES = PAIRED ? A_REGION + S * C::B_BYTES : EPI_RING + RED_BYTES;
+    static_assert(S == 4 && LDS_BYTES >= EPI_RING + RED_BYTES && LDS_BYTES <= 160 * 1024, "LDS plan");
+};
+
+// One work item: the K-steps [wi.kbeg, wi.kbeg + wi.kcnt) of tile wi.tile, then -- unless the tile is shared and another
+// workgroup finishes it -- the epilogue program.
 template <class C, bool AK, bool BKC, int EPI, bool RAGGED>
-__global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE))) void gemm_kernel_dl(const GemmParams p)
+__device__ __forceinline__ void gemm_item_dl(const GemmParams &p, const WorkItem &wi, const int KT_all, unsigned char *smem)
 {
     constexpr int BM = C::BM, BN = C::BN, BK = 32, S = C::STAGES;
     using ACC = Acc16<C>;
     constexpr int NI = ACC::NB, NJ = ACC::NU, HM = NI / 2;
     constexpr int LA = C::LA, LB = C::LB;
     static_assert(NI % 2 == 0, "two row halves");
-    // PAIRED (A K-contiguous): three pair slots of A (two K-steps each) followed by four single-step slots of B -- or, when
-    // B is K-contiguous as well (PAIRB), by two pair slots of B -- 160 KB; otherwise four slots of [A | B].  The epilogue stages through the first EPI_RING bytes either way; `red` (row-reduction
-    // exchange; second half: sum-exp of the log-sum-exp partials) follows them and, when PAIRED, lies inside the B slots, which
-    // are free once the mainloop is over.
-    constexpr bool PAIRED = AK;
-    constexpr int EPI_RING = S * C::STAGE_BYTES, RED_BYTES = 2 * C::WGN * C::BM * 4;
-    constexpr int A_REGION = PAIRED ? 3 * 2 * C::A_BYTES : 0;
-    constexpr bool PAIRB = AK && BKC;    // B K-contiguous as well: two pair slots of B instead of four single-step slots
-    constexpr int LDS_BYTES = PAIRED ? A_REGION + S * C::B_BYTES : EPI_RING + RED_BYTES;
-    static_assert(S == 4 && LDS_BYTES >= EPI_RING + RED_BYTES && LDS_BYTES <= 160 * 1024, "LDS plan");
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[LDS_BYTES];
+    using L = DlLds<C, AK, BKC>;
+    constexpr bool PAIRED = L::PAIRED, PAIRB = L::PAIRB;
+    constexpr int EPI_RING = L::EPI_RING, A_REGION = L::A_REGION;
     float *red = reinterpret_cast<float *>(smem + EPI_RING);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % C::WGM, wn = wave / C::WGM;
-    // this workgroup's part of the contraction: K-steps [kbeg, kbeg + KT); a ragged K is rounded up to whole pairs of
-    // K-steps, the positions past K are zero-filled by the tile fill
-    const int KT_all = RAGGED ? ((p.K + 2 * BK - 1) / (2 * BK)) * 2 : p.K / BK;
-    const WorkItem wi = locate_workgroup(p.splitk, p.split_from, (int)blockIdx.x, KT_all);
+    // this work item's part of the contraction: K-steps [kbeg, kbeg + KT)
     const int nsplit = wi.nsplit, kbeg = wi.kbeg, KT = wi.kcnt;
     int tm, tn;
     tile_coords(wi.tile, p.tiles_m * p.tiles_n, p.tiles_m, p.tiles_n, tm, tn);
@@ -1271,7 +1330,7 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     // together, so that panel sharing in its L2 is kept.  Measured +3 to +4 % on the SwiGLU backward and +2 % on the RMSNorm
     // backward (their epilogue bursts no longer coincide chip-wide), nothing on a plain store; the other layouts lose 1-2 %
     // with it and walk K from zero.  The order of the fp32 additions of a tile depends on its XCD, not on timing.
-    const int rot = (AK && BKC && !RAGGED && nsplit == 1) ? ((((int)blockIdx.x & 7) * (KT / 8)) & ~1) : 0;
+    const int rot = (AK && BKC && !RAGGED && nsplit == 1 && KT == KT_all) ? ((((int)blockIdx.x & 7) * (KT / 8)) & ~1) : 0;
     auto rotated = [&](int t) {   // position along K of the workgroup's t-th K-step (rot and KT are even: pairs stay pairs)
         int tg = t + rot;
         if (tg >= KT) tg -= KT;
@@ -1460,6 +1519,25 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
         run_epilogue<C, ACC, EPI, false, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
 }
 
+// The kernel: one work item per workgroup.  TAIL = false is the kernel of every launch without shared tiles (nothing of
+// the exchange is in it).  With shared tiles, workgroup split_from + piece * tail_chunks + c takes piece 0 or 1 of
+// range c of the tail; a range that lies in one tile has no second piece and that workgroup leaves at once.  (The two
+// pieces of a range are separate workgroups rather than a loop in one: the loop cost the kernels up to 350 spilled
+// registers, and the dispatcher hands the pieces to compute units as they free up, which balances them as well.)
+// A ragged K is rounded up to whole pairs of K-steps, the positions past K are zero-filled by the tile fill.
+template <class C, bool AK, bool BKC, int EPI, bool RAGGED, bool TAIL>
+__global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE))) void gemm_kernel_dl(const GemmParams p)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[DlLds<C, AK, BKC>::LDS_BYTES];
+    const int KT_all = RAGGED ? ((p.K + 63) / 64) * 2 : p.K / 32;
+    WorkItem wi = {(int)blockIdx.x, 0, 0, 1, 0, KT_all};
+    if (TAIL) {
+        wi = locate_block(p.split_from, p.tail_tiles, p.tail_chunks, (int)blockIdx.x, KT_all);
+        if ((int)blockIdx.x >= p.split_from && wi.kcnt == 0) return;
+    }
+    gemm_item_dl<C, AK, BKC, EPI, RAGGED>(p, wi, KT_all, smem);
+}
+
 // ---------------------------------------------------------------------------------
 // 8-bit operands (OCP E4M3), both stored with the contraction index contiguous: A [M x K], B [N x K] bytes.
 // One K-step is 64 elements = 64 bytes per row, so operand tiles, LDS slots and the direct-to-LDS fill have the byte
@@ -1505,26 +1583,29 @@ __device__ __forceinline__ i32x8 dl_frag_pair_f8(const unsigned char *tile, int 
 
 // RAGGED as in the bf16 kernel: clamped fetches and the bounds-checked epilogue on the edges of M and N; K (a multiple of
 // 16) is rounded up to whole pairs of K-steps, with zeros stored at the positions past it.
+template <class C>
+struct F8Lds {
+    // LDS plan of the bf16 A*B^T kernel: three pair slots of A, two pair slots of B, 160 KB; the epilogue stages through
+    // the first EPI_RING bytes and `red` follows them (inside B slots that are free by then).
+    static constexpr int S = C::STAGES;
+    static constexpr int EPI_RING = S * C::STAGE_BYTES, RED_BYTES = 2 * C::WGN * C::BM * 4;
+    static constexpr int A_REGION = 3 * 2 * C::A_BYTES, LDS_BYTES = A_REGION + S * C::B_BYTES;
+    static_assert(S == 4 && LDS_BYTES >= EPI_RING + RED_BYTES && LDS_BYTES <= 160 * 1024, "LDS plan");
+};
+
 template <class C, int EPI, bool RAGGED>
-__global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE))) void gemm_kernel_dl_f8(const GemmParams p)
+__device__ __forceinline__ void gemm_item_dl_f8(const GemmParams &p, const WorkItem &wi, const int KT_all, unsigned char *smem)
 {
     constexpr int BM = C::BM, BN = C::BN, BKB = 64, FM = C::FM, FN = C::FN, S = C::STAGES, HM = FM / 2;
     constexpr int LA = C::LA, LB = C::LB, LAP = 2 * LA, LBP = 2 * LB;
     static_assert(FM % 2 == 0, "two row halves");
-    // LDS plan of the bf16 A*B^T kernel: three pair slots of A, two pair slots of B, 160 KB; the epilogue stages through
-    // the first EPI_RING bytes and `red` follows them (inside B slots that are free by then).
-    constexpr int EPI_RING = S * C::STAGE_BYTES, RED_BYTES = 2 * C::WGN * C::BM * 4;
-    constexpr int A_REGION = 3 * 2 * C::A_BYTES, LDS_BYTES = A_REGION + S * C::B_BYTES;
-    static_assert(S == 4 && LDS_BYTES >= EPI_RING + RED_BYTES && LDS_BYTES <= 160 * 1024, "LDS plan");
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[LDS_BYTES];
+    constexpr int EPI_RING = F8Lds<C>::EPI_RING, A_REGION = F8Lds<C>::A_REGION;
     float *red = reinterpret_cast<float *>(smem + EPI_RING);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % C::WGM, wn = wave / C::WGM;
-    // this workgroup's K-steps [kbeg, kbeg + KT); the host guarantees an even, positive count
-    const int KT_all = RAGGED ? ((p.K + 2 * BKB - 1) / (2 * BKB)) * 2 : p.K / BKB;
-    const WorkItem wi = locate_workgroup(p.splitk, p.split_from, (int)blockIdx.x, KT_all);
+    // this work item's K-steps [kbeg, kbeg + KT): an even count
     const int nsplit = wi.nsplit, kbeg = wi.kbeg, KT = wi.kcnt;
     int tm, tn;
     tile_coords(wi.tile, p.tiles_m * p.tiles_n, p.tiles_m, p.tiles_n, tm, tn);
@@ -1659,6 +1740,20 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
     if (nsplit > 1 && !splitk_exchange<C>(acc, p, wi.slot, wi.split, nsplit, red, tid)) return;
 
     run_epilogue<C, ACC, EPI, RAGGED, S * C::STAGE_BYTES>(acc, p, m0, n0, tn, smem, red, tid);
+}
+
+// one work item per workgroup, as in the bf16 kernel
+template <class C, int EPI, bool RAGGED, bool TAIL>
+__global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE))) void gemm_kernel_dl_f8(const GemmParams p)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[F8Lds<C>::LDS_BYTES];
+    const int KT_all = RAGGED ? ((p.K + 127) / 128) * 2 : p.K / 64;
+    WorkItem wi = {(int)blockIdx.x, 0, 0, 1, 0, KT_all};
+    if (TAIL) {
+        wi = locate_block(p.split_from, p.tail_tiles, p.tail_chunks, (int)blockIdx.x, KT_all);
+        if ((int)blockIdx.x >= p.split_from && wi.kcnt == 0) return;
+    }
+    gemm_item_dl_f8<C, EPI, RAGGED>(p, wi, KT_all, smem);
 }
 
 // Host-side launcher, one per (operand layouts, epilogue mode, kernel kind).

@@ -10,12 +10,12 @@ using FastCfg = DlCfg<256, 256, 2, 4, 4>;       // direct-to-LDS ring of four K-
 constexpr int TILE_M = FastCfg::BM, TILE_N = FastCfg::BN;
 constexpr int TILE_K = 64;                      // the kernels walk K-steps of 32 in pairs
 
-// Workgroups of a fast-kernel launch: whole tiles below split_from, `splitk` workgroups per tile from there on.
+// Workgroups of a fast-kernel launch: one per whole tile below split_from, then one per piece of every range of the shared tail.
 inline unsigned fast_grid(const GemmParams &p)
 {
     const unsigned tiles = (unsigned)(p.tiles_m * p.tiles_n);
-    if (p.splitk <= 1) return tiles;
-    return (unsigned)p.split_from + (tiles - (unsigned)p.split_from) * (unsigned)p.splitk;
+    if (p.tail_chunks == 0) return tiles;
+    return (unsigned)p.split_from + (unsigned)p.tail_chunks * (unsigned)p.tail_pieces;
 }
 
 // `p` arrives without tile counts.
@@ -29,7 +29,10 @@ hipError_t launch_gemm(const GemmParams &p_in, hipStream_t stream)
     GemmParams p = p_in;
     p.tiles_m = (p.M + C::BM - 1) / C::BM;
     p.tiles_n = (p.N + C::BN - 1) / C::BN;
-    hipLaunchKernelGGL((gemm_kernel_dl<C, AK, BKC, EPI, KIND == KIND_RAGGED>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
+    if (p.tail_chunks > 0)
+        hipLaunchKernelGGL((gemm_kernel_dl<C, AK, BKC, EPI, KIND == KIND_RAGGED, true>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
+    else
+        hipLaunchKernelGGL((gemm_kernel_dl<C, AK, BKC, EPI, KIND == KIND_RAGGED, false>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -41,7 +44,10 @@ hipError_t launch_gemm_f8(const GemmParams &p_in, hipStream_t stream)
     GemmParams p = p_in;
     p.tiles_m = (p.M + C::BM - 1) / C::BM;
     p.tiles_n = (p.N + C::BN - 1) / C::BN;
-    hipLaunchKernelGGL((gemm_kernel_dl_f8<C, EPI, KIND == KIND_RAGGED>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
+    if (p.tail_chunks > 0)
+        hipLaunchKernelGGL((gemm_kernel_dl_f8<C, EPI, KIND == KIND_RAGGED, true>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
+    else
+        hipLaunchKernelGGL((gemm_kernel_dl_f8<C, EPI, KIND == KIND_RAGGED, false>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
     return hipGetLastError();
 }
 

@@ -8,51 +8,65 @@ namespace coda {
 
 constexpr int64_t PLAN_TILE_M = 256, PLAN_TILE_N = 256;   // the kernels' workgroup tile (checked against the kernel config where both are seen)
 
-// Split-K plan (tiles and K-steps counted with their ragged edges).  Two cases:
-//  * few tiles: at most 64 output tiles leave at least three quarters of the 256 compute units without one (measured:
-//    with 64 tiles 4 parts win 1.4x, with 128 tiles 2 parts lose to the exchange of partial tiles): every tile is shared;
-//  * partly filled last round: more than 256 tiles whose count is not a multiple of 256 and whose remainder fills at
-//    most half of the chip: only the tiles of that last round are shared, so that it takes 1/parts of a round.  Worth
-//    it when the contraction length a workgroup is spared clearly outweighs the exchange (about 35 us, the time of ~1400
-//    contraction elements of a bf16 tile; the partly filled round itself runs faster than a full one): measured +16 % at
-//    320 tiles and +2 % at 384 tiles with K = 8192, +5 % at 320 tiles with K = 4096.
-// Every part gets at least 32 K-steps of 32 bf16 (64 fp8) elements and an even number of K-steps.
-constexpr int64_t SPLITK_CUS = 256, SPLITK_MAX = 8, SPLITK_MIN_K = 1024, SPLITK_MAX_TILES = 64, SPLITK_TAIL_MIN_SPARED = 3072;
+// Plan of the shared tiles (tiles and K-steps counted with their ragged edges).  The tiles that would leave compute units
+// idle -- all of them when there are fewer than 256, else those of the last, partly filled round of 256 -- form the
+// "tail"; its K-steps, laid end to end, are cut into `chunks` equal contiguous ranges, one workgroup each, so that the
+// tail takes tail / chunks of a tile time instead of a whole one:
+//  * chunks = min(256, tail * parts), parts = min(8, K / 1024): every range gets at least 1024 contraction elements
+//    (32 K-steps of 32 bf16, 16 of 64 fp8 elements).  When tail * parts fits the chip every tile is cut into `parts`
+//    equal parts; otherwise the 256 ranges straddle tile boundaries (a balanced "stream-K" round);
+//  * only when it pays against the exchange of partial tiles through the workspace (256 KB per part, written once and
+//    read once: the full-chip exchange costs about 70 us): a workgroup must be spared at least SPLITK_MIN_SPARED_STEPS
+//    K-steps of a tile, and must be left with at most SPLITK_MAX_SHARE_NUM / _DEN of one.
+// Measured (residual + sum-of-squares program, bf16, against the same launch without workspace): K = 8192: 4 tiles
+// 2.7x, 16 tiles 2.4x, 64 tiles 1.7x, 72 tiles +18 %, 96 tiles +31 %, 128 tiles +23 %, 160 tiles +0 %; 272 tiles +36 %,
+// 320 tiles +20 %, 384 tiles +10 %, 576 tiles +13 %; K = 4096: 16 tiles +78 %, 64 tiles +21 %, 128 tiles +6 %, 320 tiles
+// +8 %, 384 tiles +4 %; K = 2048 (32 K-steps spared at best): 16 tiles +1 to +6 %, 64 tiles -2 %, 384 tiles -9 %.  Rounds
+// that are fuller than 5/8 lose -- 192 tiles -3 %, 208 tiles -29 % (ranges of 13/16 of a tile leave slivers of 1/16, each
+// with its own pipeline fill and exchange), 448 tiles -5 % at K = 8192 and -2 % at K = 16384, 496 tiles -19 % -- and run
+// unsplit.  Hence: spared >= 64 K-steps, share <= 9/16 (a round of up to 144 tiles).
+constexpr int64_t SPLITK_CUS = 256, SPLITK_MAX_PARTS = 8, SPLITK_MIN_K = 1024, SPLITK_MIN_SPARED_STEPS = 64;
+constexpr int64_t SPLITK_MAX_SHARE_NUM = 9, SPLITK_MAX_SHARE_DEN = 16;
 struct SplitPlan {
-    int parts;    // <= 1: no split
-    int first;    // tiles with id >= first are shared by `parts` workgroups each
-    int shared;   // number of shared tiles
+    int first;    // tiles below `first` run whole
+    int tail;     // number of shared tiles (ids first .. first + tail - 1)
+    int chunks;   // workgroups that share them; 0: nothing is shared
+    int stride;   // exchange slots per shared tile: the largest number of ranges that reach into one tile
+    int pieces;   // 1: every range lies in one tile; 2: ranges straddle tile boundaries (two workgroups per range)
 };
 inline SplitPlan plan_splitk(int64_t M, int64_t N, int64_t K, bool f8 = false)
 {
-    const SplitPlan none = {1, 0, 0};
+    const SplitPlan none = {0, 0, 0, 0, 1};
     if (M <= 0 || N <= 0 || K <= 0) return none;
     const int64_t tiles = ((M + PLAN_TILE_M - 1) / PLAN_TILE_M) * ((N + PLAN_TILE_N - 1) / PLAN_TILE_N);
     const int64_t scale = f8 ? 2 : 1;                         // an fp8 K-step covers twice the elements in the same time
-    const int64_t steps = (K + scale * 64 - 1) / (scale * 64) * 2;   // K-steps of 32 bf16 / 64 fp8 elements, in whole pairs
-    auto fit = [&](int64_t s) {
-        if (s > K / (scale * SPLITK_MIN_K)) s = K / (scale * SPLITK_MIN_K);
-        if (s > SPLITK_MAX) s = SPLITK_MAX;
-        // the kernels walk their K-steps in pairs: every part must get an even number
-        while (s >= 2 && steps % (2 * s)) --s;
-        return s >= 2 ? s : (int64_t)1;
-    };
-    if (tiles <= SPLITK_MAX_TILES) {
-        const int64_t s = fit(SPLITK_CUS / tiles);
-        return s >= 2 ? SplitPlan{(int)s, 0, (int)tiles} : none;
+    const int64_t pairs = (K + scale * 64 - 1) / (scale * 64);   // pairs of K-steps per tile (K-steps of 32 bf16 / 64 fp8 elements)
+    int64_t parts = K / (scale * SPLITK_MIN_K);
+    if (parts > SPLITK_MAX_PARTS) parts = SPLITK_MAX_PARTS;
+    if (parts < 2) return none;
+    const int64_t tail = tiles < SPLITK_CUS ? tiles : tiles % SPLITK_CUS;
+    if (tail == 0) return none;
+    int64_t chunks = tail * parts < SPLITK_CUS ? tail * parts : SPLITK_CUS;
+    if (chunks <= tail) return none;
+    // K-steps of the longest range against those of a whole tile
+    const int64_t longest = 2 * ((tail * pairs + chunks - 1) / chunks);
+    if (2 * pairs - longest < SPLITK_MIN_SPARED_STEPS / (f8 ? 2 : 1)) return none;
+    if (SPLITK_MAX_SHARE_DEN * tail > SPLITK_MAX_SHARE_NUM * chunks) return none;
+    // ranges per tile: tile a is reached by the ranges that hold its first and its last pair, and those in between
+    const int64_t total = tail * pairs;
+    int64_t stride = 1;
+    for (int64_t a = 0; a < tail; ++a) {
+        const int64_t c_lo = ((a * pairs + 1) * chunks + total - 1) / total - 1;
+        const int64_t c_hi = (((a + 1) * pairs) * chunks + total - 1) / total - 1;
+        if (c_hi - c_lo + 1 > stride) stride = c_hi - c_lo + 1;
     }
-    const int64_t rem = tiles % SPLITK_CUS;
-    if (tiles < SPLITK_CUS || rem == 0 || rem > SPLITK_CUS / 2) return none;
-    const int64_t s = fit(SPLITK_CUS / rem);
-    if (s < 2 || K - K / s < scale * SPLITK_TAIL_MIN_SPARED) return none;
-    return SplitPlan{(int)s, (int)(tiles - rem), (int)rem};
+    return SplitPlan{(int)(tiles - tail), (int)tail, (int)chunks, (int)stride, chunks % tail == 0 ? 1 : 2};
 }
-constexpr size_t SPLITK_CNT_BYTES = 1024;   // ticket counters (at most 128 shared tiles x 4 bytes), kept apart from the partials
+constexpr size_t SPLITK_CNT_BYTES = 1024;   // ticket counters (at most 255 shared tiles x 4 bytes), kept apart from the partials
 inline size_t splitk_bytes(const SplitPlan &pl)
 {
-    if (pl.parts <= 1) return 0;
-    return SPLITK_CNT_BYTES + (size_t)pl.shared * (size_t)pl.parts * PLAN_TILE_M * PLAN_TILE_N * sizeof(float);
+    if (pl.chunks == 0) return 0;
+    return SPLITK_CNT_BYTES + (size_t)pl.tail * (size_t)pl.stride * PLAN_TILE_M * PLAN_TILE_N * sizeof(float);
 }
-
 
 }  // namespace coda

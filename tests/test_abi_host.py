@@ -167,19 +167,20 @@ def test_splitk_workspace_planning_and_errors(coda):
     assert wb(512, 512, 4096) == 1024 + 4 * 4 * tile        # 4 tiles, K / 1024 = 4 parts
     assert wb(256, 256, 8192) == 1024 + 1 * 8 * tile        # 1 tile, capped at 8 parts
     assert wb(2048, 2048, 8192) == 1024 + 64 * 4 * tile     # 64 tiles: 4 parts fill the 256 compute units
-    assert wb(2048, 2048 + 256, 8192) == 0                  # 72 tiles: more than a quarter of the chip already busy
+    assert wb(2048, 2048 + 256, 8192) == 1024 + 72 * 5 * tile   # 72 tiles: 256 ranges of 9/32 of a tile, up to 5 reach into one tile
     assert wb(512, 512, 1024) == 0                          # contraction too short to split
-    assert wb(512, 512, 4096 + 32) == 0                     # 130 K-steps (ragged K rounds up to pairs): no even split
-    assert wb(512, 512, 4096 + 72) == 1024 + 4 * 3 * tile   # 132 K-steps: 3 parts of 44
+    assert wb(512, 512, 4096 + 32) == 1024 + 4 * 4 * tile   # 130 K-steps (ragged K rounds up to pairs): parts of 32 or 34
     assert wb(504, 264, 4096) == 1024 + 4 * 4 * tile        # ragged M and N: 2 x 2 tiles, shared like whole ones
-    assert wb(256, 256, 6 * 1024 + 128) == 1024 + 1 * 2 * tile  # 196 K-steps of 32: only 2 parts get an even number each
-    assert wb(256, 256, 6 * 1024 + 64) == 0                     # 194 K-steps: no part count gives every part an even number
-    # more than 256 tiles: only a partly filled last round (1 .. 128 tiles) is shared, and only when it pays
+    assert wb(256, 256, 6 * 1024 + 128) == 1024 + 1 * 6 * tile  # 196 K-steps: six parts of 32 or 34
+    # more than 256 tiles: only a partly filled last round is shared, and only when it pays
     assert wb(5120, 4096, 4096) == 1024 + 64 * 4 * tile     # 320 tiles: the last 64 shared by 4 workgroups each
     assert wb(6144, 4096, 8192) == 1024 + 128 * 2 * tile    # 384 tiles: the last 128 shared by 2
-    assert wb(6144, 4096, 4096) == 0                        # 2 parts would spare only 2048 of K: not worth the exchange
+    assert wb(6144, 4096, 4096) == 1024 + 128 * 2 * tile    # the same with K = 4096: each workgroup is spared 64 K-steps
+    assert wb(6144, 4096, 2048) == 0                        # ... with K = 2048 only 32: not worth the exchange
     assert wb(5120, 4096, 2048) == 0                        # contraction too short
-    assert wb(7168, 4096, 4096) == 0                        # 448 tiles: the last round is three quarters full
+    assert wb(2304, 4096, 8192) == 1024 + 144 * 3 * tile    # one round of 144 tiles: 256 ranges of 9/16 of a tile, up to 3 per tile
+    assert wb(2560, 4096, 8192) == 0                        # 160 tiles: measured to gain nothing
+    assert wb(7168, 4096, 8192) == 0                        # 448 tiles: the last round is three quarters full (measured: a loss)
     assert wb(8192, 4096, 4096) == 0                        # 512 tiles: whole rounds
     assert wb(0, 512, 4096) == 0 and wb(-1, 512, 4096) == 0
     A, B = _mat(coda, P, 512, 4096), _mat(coda, P, 4096, 512)

@@ -23,40 +23,47 @@ def kernels():
 def _gemm(kernels):
     out = {}
     for name, r in kernels.items():
-        m = re.search(r"gemm_kernel_dlINS_5DlCfg\w+?EEELb([01])ELb([01])ELi(\d)ELb([01])EEEv", name)
+        m = re.search(r"gemm_kernel_dlINS_5DlCfg\w+?EEELb([01])ELb([01])ELi(\d)ELb([01])ELb([01])EEEv", name)
         if m:
-            out[tuple(int(x) for x in m.groups())] = r          # (A K-contiguous, B K-contiguous, epilogue mode, ragged)
+            out[tuple(int(x) for x in m.groups())] = r   # (A K-contiguous, B K-contiguous, epilogue mode, ragged, shared tail)
+    return out
+
+
+def _gemm_f8(kernels):
+    out = {}
+    for name, r in kernels.items():
+        m = re.search(r"gemm_kernel_dl_f8INS_5DlCfg\w+?EEELi(\d)ELb([01])ELb([01])EEEv", name)
+        if m:
+            out[tuple(int(x) for x in m.groups())] = r   # (epilogue mode, ragged, shared tail)
     return out
 
 
 def test_every_instance_is_there_and_fits_the_compute_unit(kernels):
-    g = _gemm(kernels)
-    assert len(g) == 4 * 5 * 2, sorted(g)
-    f8 = [r for n, r in kernels.items() if "gemm_kernel_dl_f8" in n]
-    assert len(f8) == 5 * 2
-    for r in list(g.values()) + f8:
+    g, f8 = _gemm(kernels), _gemm_f8(kernels)
+    assert len(g) == 4 * 5 * 2 * 2, sorted(g)
+    assert len(f8) == 5 * 2 * 2
+    for r in list(g.values()) + list(f8.values()):
         assert r["vgpr"] <= 256 and r["agpr"] == 0          # two waves per SIMD
         assert r["lds"] <= 160 * 1024
 
 
-def test_spills_stay_out_of_the_step_kernels(kernels):
-    g = _gemm(kernels)
-    assert g[(1, 0, 1, 0)]["scratch"] == 0                      # up-projection: row scale + SwiGLU
-    assert g[(1, 0, 0, 0)]["scratch"] == 0                      # down-projection / QKV: linear programs
-    assert g[(0, 0, 3, 0)]["scratch"] == 0                      # weight gradient: fp32 accumulate
-    assert g[(1, 1, 2, 0)]["spill"] <= 4                        # SwiGLU backward: four epilogue-only spills
-    for key, r in g.items():
-        if key[2] == 4 and not key[3]:
-            assert r["scratch"] == 0, (key, r)                  # RMSNorm backward, whole tiles: nothing spilled
-        # the ragged instances carry both the bounds-checked and the plain epilogue (interior tiles take the plain one)
-        limit = 40 if key[3] else 20
+def test_whole_tile_kernels_do_not_spill(kernels):
+    """The kernels of every launch without shared tiles, on shapes that are whole multiples of the tile: all five epilogue
+    modes, all four layouts and the 8-bit kernel run without a single spilled register."""
+    for key, r in _gemm(kernels).items():
+        if not key[3] and not key[4]:
+            assert r["scratch"] == 0 and r["spill"] == 0, (key, r)
+    for key, r in _gemm_f8(kernels).items():
+        if not key[1] and not key[2]:
+            assert r["scratch"] == 0 and r["spill"] == 0, (key, r)
+
+
+def test_spills_of_the_other_instances_stay_small(kernels):
+    """Ragged instances carry both the bounds-checked and the plain epilogue (interior tiles take the plain one); the
+    instances for launches with shared tiles carry the exchange of partial tiles as well."""
+    for key, r in _gemm(kernels).items():
+        limit = 40 if key[3] else 0
         assert r["spill"] <= limit, (key, r)
-
-
-def test_spills_of_the_8bit_kernels(kernels):
-    for name, r in kernels.items():
-        m = re.search(r"gemm_kernel_dl_f8INS_5DlCfg\w+?EEELi(\d)ELb([01])EEEv", name)
-        if not m:
-            continue
-        mode, ragged = int(m.group(1)), int(m.group(2))
-        assert r["spill"] <= 24, (name, r)
+    for key, r in _gemm_f8(kernels).items():
+        limit = 40 if key[1] else 0
+        assert r["spill"] <= limit, (key, r)

@@ -38,10 +38,10 @@ def operands(g, M, N, K, transA, transB, a_std=1.0, b_std=0.05):
     return A, B
 
 
-# (M, N, K) -> parts: 4 tiles, K = 4096 -> 4;  1 tile, K = 8192 -> 8;  2 tiles, K = 2048 -> 2;
-# 1 tile, K = 6272 (196 K-steps of 32) -> 2, the only count that gives every part an even number of steps;
-# 2 x 2 tiles with a ragged edge in M and N, K = 4096 -> 4; the same with a ragged K = 4168 (132 K-steps) -> 3
-SHAPES = [(512, 512, 4096), (256, 256, 8192), (256, 512, 2048), (256, 256, 6272), (504, 264, 4096), (504, 264, 4168)]
+# (M, N, K) -> parts: 4 tiles, K = 4096 -> 4;  1 tile, K = 8192 -> 8;  2 tiles, K = 3072 -> 3;
+# 1 tile, K = 6272 (196 K-steps of 32) -> 6 parts of 32 or 34 steps;
+# 2 x 2 tiles with a ragged edge in M and N, K = 4096 -> 4; the same with a ragged K = 4168 (132 K-steps) -> 4 parts of 32 or 34
+SHAPES = [(512, 512, 4096), (256, 256, 8192), (256, 512, 3072), (256, 256, 6272), (504, 264, 4096), (504, 264, 4168)]
 
 
 @pytest.mark.parametrize("transA,transB", [(False, False), (False, True), (True, False)])
@@ -149,10 +149,9 @@ def test_splitk_workspace_rules(oracle):
     dA, dB = G.dev_bf16(A), G.dev_bf16(B)
     need = coda.coda_gemm_workspace_bytes(M, N, K, [])
     assert need == 1024 + 4 * 4 * 256 * 256 * 4          # counters + tiles x parts x one fp32 tile
-    # shapes that are not split ask for nothing: many tiles, short K, a K-step count that no part count divides evenly
+    # shapes that are not split ask for nothing: whole rounds of tiles, a short K
     assert coda.coda_gemm_workspace_bytes(8192, 8192, 8192, []) == 0
     assert coda.coda_gemm_workspace_bytes(512, 512, 1024, []) == 0
-    assert coda.coda_gemm_workspace_bytes(512, 512, 4096 + 8, []) == 0
     assert coda.coda_gemm_workspace_bytes(520, 512, 4096, []) == 1024 + 6 * 4 * 256 * 256 * 4   # ragged M: 3 x 2 tiles
     out = G.Guarded(M, N, torch.bfloat16)
     small = torch.empty(need - 16, dtype=torch.uint8, device="cuda")
@@ -212,3 +211,39 @@ def test_splitk_last_round_only(oracle, transB):
     eq = (outs[0][0].view(torch.int16) == outs[2][0].view(torch.int16)).view(M // 256, 256, N // 256, 256)
     same_tiles = eq.all(dim=3).all(dim=1).sum().item()
     assert same_tiles >= 256, "the tiles of the first round must run whole (bitwise equal to the unsplit launch): %d" % same_tiles
+
+
+@pytest.mark.parametrize("M,N,K,transA", [(2560, 1024, 8192, False), (2500, 1000, 8200, False), (2560, 1024, 8192, True)])
+def test_balanced_round_with_ranges_that_straddle_tiles(oracle, M, N, K, transA):
+    """40 output tiles with a long contraction: 8 parts each would need 320 workgroups, so the K-steps of all tiles, laid end
+    to end, are cut into 256 equal ranges; most ranges end in one tile and begin in the next (a workgroup then runs two
+    work items), and a tile is finished by whichever of its up to 8 contributors arrives last.  Whole and ragged shapes,
+    both A layouts; sampled rows of every tile row against the oracle, bitwise equal across repeats."""
+    g = np.random.Generator(np.random.PCG64(1200 + M + K + transA))
+    A, B = operands(g, M, N, K, transA, False, b_std=0.02)
+    C = synth.normal_bf16(g, (M, N), 1.0)
+    r = synth.uniform_f32(g, (M,), 0.5, 1.5)
+    need = coda.coda_gemm_workspace_bytes(M, N, K, [])
+    tiles = -(-M // 256) * -(-N // 256)
+    assert tiles == 40 and need > 1024 + tiles * 7 * 256 * 256 * 4, "expected the straddling plan (more slots than equal parts)"
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda").fill_(0xA5)
+    dA, dB, dC, dr = G.dev_bf16(A), G.dev_bf16(B), G.dev_bf16(C), G.dev_f32(r)
+    nblk = coda.coda_row_partial_blocks(N)
+    outs = []
+    for rep in range(2):
+        Y = G.Guarded(M, N, torch.bfloat16)
+        part = torch.full((nblk, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+        ss = torch.empty(M, dtype=torch.float32, device="cuda")
+        coda.coda_gemm(dA, dB, [coda.row_scale(dr), coda.add_tile(dC), coda.row_sumsq(part), coda.store(Y.t)], transA=transA, workspace=ws)
+        coda.coda_row_finalize(part, M, nblk, sum_out=ss, d=N, eps=0.0)
+        torch.cuda.synchronize()
+        Y.check_guards(); Y.written()
+        assert int((part == G.SENTINEL_F32).sum().item()) == 0
+        outs.append((Y.t.clone(), ss.clone()))
+    rows = synth.sample_rows_per_tile(M, 2, seed=77)
+    refD, refss = oracle.gemm_residual_sumsq(A, B, r=r.astype(np.float64), C=C, transA=transA, rows=rows)[:2]
+    idx = torch.from_numpy(rows).cuda()
+    G.assert_bf16_close(G.host_f64(outs[0][0][idx]), refD, "balanced round: row scale + residual")
+    G.assert_sumsq_close(G.host_f64(outs[0][1][idx]), refss, "balanced round: row sum of squares")
+    assert torch.equal(outs[0][0].view(torch.int16), outs[1][0].view(torch.int16)), "repeat differs: order-dependent sum"
+    assert torch.equal(outs[0][1], outs[1][1])

@@ -22,45 +22,56 @@ def hostlib(tmp_path_factory):
     lib.host_plan.restype = ctypes.c_size_t
     lib.host_plan.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
     lib.host_tile_map.restype = None
-    lib.host_tile_map.argtypes = [ctypes.c_int] * 6 + [ctypes.POINTER(ctypes.c_int)]
+    lib.host_tile_map.argtypes = [ctypes.c_int] * 7 + [ctypes.POINTER(ctypes.c_int)]
     return lib
 
 
 def launch_map(lib, M, N, K, f8=False, use_plan=True):
+    """Work items of every workgroup of the launch that has one: rows of (tile row, tile column, part, parts, first
+    K-step, K-steps, slot, tile id, range id or -1)."""
     tiles_m, tiles_n = -(-M // 256), -(-N // 256)
     step = 64 if f8 else 32
     kt_all = -(-K // (2 * step)) * 2                 # K-steps, in whole pairs
-    plan = (ctypes.c_int * 3)()
+    plan = (ctypes.c_int * 5)()
     need = lib.host_plan(M, N, K, int(f8), plan)
-    parts, first, shared = (plan[0], plan[1], plan[2]) if use_plan else (1, 0, 0)
+    first, tail, chunks, stride, pieces = (plan[0], plan[1], plan[2], plan[3], plan[4]) if use_plan else (0, 0, 0, 0, 1)
     tiles = tiles_m * tiles_n
-    nwg = tiles if parts <= 1 else first + (tiles - first) * parts
-    out = (ctypes.c_int * (7 * nwg))()
-    lib.host_tile_map(tiles_m, tiles_n, parts, first, kt_all, nwg, out)
-    return np.array(out, dtype=np.int64).reshape(nwg, 7), (tiles_m, tiles_n, kt_all, parts, first, shared, need)
+    nwg = tiles if chunks == 0 else first + chunks * pieces
+    out = (ctypes.c_int * (8 * nwg))()
+    lib.host_tile_map(tiles_m, tiles_n, first, tail, chunks, kt_all, nwg, out)
+    m = np.array(out, dtype=np.int64).reshape(nwg, 8)
+    bid = np.arange(nwg)
+    rng = np.where((bid >= first) & (chunks > 0), (bid - first) % max(chunks, 1), -1)
+    m = np.concatenate([m, rng[:, None]], axis=1)
+    empty = (m[:, 5] == 0) & (rng >= 0)
+    if chunks > 0:
+        assert pieces in (1, 2) and (pieces == 2 or not empty.any())
+        assert not empty[:first + chunks].any(), "the first piece of a range is never empty"
+    return m[~empty], (tiles_m, tiles_n, kt_all, first, tail, chunks, stride, need if use_plan else 0)
 
 
-# (M, N, K): the benchmark step, the 8B chain, the LM head, the 70B-style sweep point, split-K shapes (few tiles; a
-# partly filled last round: 320 and 384 tiles), ragged tile counts, a single tile
+# (M, N, K): the benchmark step, the 8B chain, the LM head, the 70B-style sweep point, shared-tile shapes (few tiles; a
+# partly filled last round of 16, 64, 128 and 192 tiles; a single round of 128 and 200 tiles), ragged tile counts, one tile
 SHAPES = [(8192, 16384, 2048), (8192, 2048, 8192), (8192, 8192, 2048), (16384, 6144, 4096), (16384, 28672, 4096),
           (16384, 4096, 14336), (8192, 32768, 4096), (8192, 57344, 8192), (512, 512, 8192), (1024, 1024, 8192),
-          (2048, 2048, 8192), (5120, 4096, 8192), (6144, 4096, 8192), (256, 256, 6272), (504, 264, 4168), (8200, 8192, 8192),
-          (8448, 2304, 200), (4000, 4000, 4000), (256, 256, 64), (8, 8, 8), (69632, 256, 8192)]
+          (2048, 2048, 8192), (5120, 4096, 8192), (6144, 4096, 8192), (7168, 4096, 8192), (2048, 4096, 8192), (3200, 4096, 16384), (2304, 4096, 8192), (6400, 4096, 16384),
+          (256, 256, 6272), (504, 264, 4168), (8200, 8192, 8192), (8448, 2304, 200), (4000, 4000, 4000), (256, 256, 64), (8, 8, 8),
+          (69632, 256, 8192), (7000, 3000, 5000)]
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
 @pytest.mark.parametrize("f8", [False, True])
 def test_every_tile_and_part_is_reached_exactly_once(hostlib, M, N, K, f8):
-    m, (tiles_m, tiles_n, kt_all, parts, first, shared, need) = launch_map(hostlib, M, N, K, f8)
+    m, (tiles_m, tiles_n, kt_all, first, tail, chunks, stride, need) = launch_map(hostlib, M, N, K, f8)
     tiles = tiles_m * tiles_n
     assert ((m[:, 0] >= 0) & (m[:, 0] < tiles_m) & (m[:, 1] >= 0) & (m[:, 1] < tiles_n)).all()
     keys = [(int(r[0]), int(r[1]), int(r[2])) for r in m]
-    assert len(set(keys)) == len(keys), "two workgroups share a (tile, part)"
+    assert len(set(keys)) == len(keys), "two work items share a (tile, part)"
     per_tile = {}
     for r in m:
         per_tile.setdefault((int(r[0]), int(r[1])), []).append(r)
     assert len(per_tile) == tiles, "some tile has no workgroup"
-    n_shared = 0
+    n_shared, longest = 0, 0
     for rows in per_tile.values():
         rows = sorted(rows, key=lambda r: r[2])
         nsplit = int(rows[0][3])
@@ -73,15 +84,46 @@ def test_every_tile_and_part_is_reached_exactly_once(hostlib, M, N, K, f8):
         assert k == kt_all
         if nsplit > 1:
             n_shared += 1
-            assert len({int(r[6]) for r in rows}) == 1 and 0 <= int(rows[0][6]) < shared   # one exchange slot per shared tile
-    assert n_shared == (shared if parts > 1 else 0)
-    if parts > 1:
-        slots = {int(r[6]) for r in m if r[3] > 1}
-        assert slots == set(range(shared)), "exchange slots are not a permutation"
-        assert need == 1024 + shared * parts * 256 * 256 * 4
-        assert shared <= 256, "ticket counters live in the first 1024 bytes of the workspace"
+            assert nsplit <= stride
+            assert len({int(r[6]) for r in rows}) == 1 and 0 <= int(rows[0][6]) < tail   # one exchange slot range per shared tile
+            assert int(rows[0][7]) == first + int(rows[0][6])
+        else:
+            assert int(rows[0][7]) < first or chunks == 0 or nsplit == 1
+    if chunks > 0:
+        assert n_shared == tail and first + tail == tiles and first % 256 == 0 and tail < 256
+        assert {int(r[6]) for r in m if r[3] > 1} == set(range(tail)), "exchange slots are not a permutation"
+        assert need == 1024 + tail * stride * 256 * 256 * 4
+        # every workgroup of the tail holds one chunk: consecutive K-steps of at most two consecutive tiles, and the
+        # chunks are balanced to within one pair of K-steps
+        work = {}
+        for r in m:
+            if r[8] >= 0:
+                work.setdefault(int(r[8]), []).append(r)
+        assert sorted(work) == list(range(chunks))
+        sizes = [sum(int(r[5]) for r in rs) for rs in work.values()]
+        assert max(sizes) - min(sizes) <= 2 and sum(sizes) == tail * kt_all
+        for rs in work.values():
+            assert len(rs) <= 2
+            if len(rs) == 2:
+                r0, r1 = rs
+                assert int(r1[7]) == int(r0[7]) + 1 and int(r0[4]) + int(r0[5]) == kt_all and int(r1[4]) == 0
     else:
-        assert need == 0
+        assert need == 0 and n_shared == 0
+
+
+def test_plan_covers_a_round_that_is_more_than_half_full(hostlib):
+    """400 tiles with a long contraction: the last round holds 144 tiles, cut into 256 ranges of 9/16 of a tile."""
+    m, (tiles_m, tiles_n, kt_all, first, tail, chunks, stride, need) = launch_map(hostlib, 6400, 4096, 8192)
+    assert (first, tail, chunks) == (256, 144, 256) and stride == 3
+    sizes = {}
+    for r in m:
+        if r[8] >= 0:
+            sizes[int(r[8])] = sizes.get(int(r[8]), 0) + int(r[5])
+    assert set(sizes.values()) == {kt_all * 9 // 16}
+    # a fuller round (448 tiles: 192 in the last round) and a short contraction are left alone: measured to lose
+    for shape in ((7168, 4096, 8192), (2560, 4096, 2048)):
+        _, (_, _, _, first, tail, chunks, _, need) = launch_map(hostlib, *shape)
+        assert chunks == 0 and need == 0
 
 
 def test_each_xcd_walks_a_compact_patch(hostlib):
