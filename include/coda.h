@@ -71,7 +71,7 @@ typedef struct coda_mat {
     const void *ptr; /* device */
     int64_t rows, cols, ld;
     int32_t trans;
-    int32_t dtype; /* coda_dtype; operands are CODA_BF16, or both CODA_F8E4M3 (see coda_gemm) */
+    int32_t dtype; /* coda_dtype; operands are both CODA_BF16 or both CODA_F8E4M3 (see coda_gemm) */
 } coda_mat;
 
 /*
@@ -189,13 +189,14 @@ typedef struct coda_epi_op {
  * element's position, never on timing; with CODA_REDUCE_PARTIALS every output of a call is bitwise identical from call
  * to call (CODA_REDUCE_ATOMIC sums may differ in their last bits).
  *
- * 8-bit operands: A and B may both be CODA_F8E4M3 (ld in elements = bytes, a multiple of 16).  The contraction
- * runs on the fp8 matrix cores with fp32 accumulation of the exact products, and every epilogue program
- * above applies unchanged (outputs stay bf16 / fp32; quantisation scales of the operands are the caller's
- * and fold into ROW_SCALE).  This variant exists for one layout: both operands stored with the contraction
- * index contiguous (A [M x K] with trans = 0, B [N x K] with trans = 1); K must be a multiple of 16 and N a
- * multiple of 8, M is free (edge tiles are predicated as for bf16).  Anything else is CODA_ERR_DTYPE (layout,
- * mixed dtypes) or CODA_ERR_SHAPE (sizes).
+ * 8-bit operands: A and B may both be CODA_F8E4M3 (ld in elements = bytes, a multiple of 16), in any of the four
+ * trans combinations: forward weights kept [in x out], the backward form A B^T and the weight-gradient form A^T B
+ * all run on the fp8 matrix cores.  The contraction accumulates the exact products in fp32, and every epilogue
+ * program above applies unchanged (outputs stay bf16 / fp32; quantisation scales of the operands are the caller's
+ * and fold into ROW_SCALE).  Operands move in 16-byte chunks along whichever index is contiguous in memory: K must
+ * be a multiple of 16; N must be a multiple of 16 when B is stored [K x N] (trans = 0), else of 8; M must be a
+ * multiple of 16 when A is stored [K x M] (trans = 1), else it is free.  Mixed operand dtypes are CODA_ERR_DTYPE,
+ * sizes that break these rules CODA_ERR_SHAPE.
  *
  * workspace / workspace_bytes (device memory, 16-byte aligned; may be NULL): scratch for sharing output tiles
  * among workgroups (split-K / stream-K).  A shape with fewer than 256 output tiles (256 x 256, counted with a ragged

@@ -31,7 +31,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-fvisibility=hidden", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 SOURCES = ["coda_api.hip", "aux_kernels.hip",
-           "gemm_inst_nn.hip", "gemm_inst_nt.hip", "gemm_inst_tn.hip", "gemm_inst_tt.hip", "gemm_inst_f8.hip"]
+           "gemm_inst_nn.hip", "gemm_inst_nt.hip", "gemm_inst_tn.hip", "gemm_inst_tt.hip",
+           "gemm_inst_f8_nn.hip", "gemm_inst_f8_nt.hip", "gemm_inst_f8_tn.hip", "gemm_inst_f8_tt.hip"]
 SOURCES_BENCH = ["baseline_kernels.hip", "calib_kernels.hip"]
 
 

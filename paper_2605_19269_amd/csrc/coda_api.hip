@@ -255,22 +255,23 @@ hipError_t dispatch_mode(int mode, int kind, const coda::GemmParams &p, hipStrea
     }
 }
 
-template <int EPI>
+template <bool AK, bool BKC, int EPI>
 hipError_t dispatch_kind_f8(int kind, const coda::GemmParams &p, hipStream_t s)
 {
     using namespace coda;
-    return kind == KIND_WHOLE ? launch_gemm_f8<EPI, KIND_WHOLE>(p, s) : launch_gemm_f8<EPI, KIND_RAGGED>(p, s);
+    return kind == KIND_WHOLE ? launch_gemm_f8<AK, BKC, EPI, KIND_WHOLE>(p, s) : launch_gemm_f8<AK, BKC, EPI, KIND_RAGGED>(p, s);
 }
 
+template <bool AK, bool BKC>
 hipError_t dispatch_mode_f8(int mode, int kind, const coda::GemmParams &p, hipStream_t s)
 {
     using namespace coda;
     switch (mode) {
-    case EPI_LINEAR: return dispatch_kind_f8<EPI_LINEAR>(kind, p, s);
-    case EPI_SWIGLU_FWD: return dispatch_kind_f8<EPI_SWIGLU_FWD>(kind, p, s);
-    case EPI_SWIGLU_BWD: return dispatch_kind_f8<EPI_SWIGLU_BWD>(kind, p, s);
-    case EPI_RMSNORM_BWD: return dispatch_kind_f8<EPI_RMSNORM_BWD>(kind, p, s);
-    default: return dispatch_kind_f8<EPI_ACCUM>(kind, p, s);
+    case EPI_LINEAR: return dispatch_kind_f8<AK, BKC, EPI_LINEAR>(kind, p, s);
+    case EPI_SWIGLU_FWD: return dispatch_kind_f8<AK, BKC, EPI_SWIGLU_FWD>(kind, p, s);
+    case EPI_SWIGLU_BWD: return dispatch_kind_f8<AK, BKC, EPI_SWIGLU_BWD>(kind, p, s);
+    case EPI_RMSNORM_BWD: return dispatch_kind_f8<AK, BKC, EPI_RMSNORM_BWD>(kind, p, s);
+    default: return dispatch_kind_f8<AK, BKC, EPI_ACCUM>(kind, p, s);
     }
 }
 
@@ -284,8 +285,9 @@ coda_status gemm_impl(void *stream, int64_t M, int64_t N, int64_t K, const coda_
     if ((st = check_operand(A, M, K)) != CODA_OK) return st;
     if ((st = check_operand(B, K, N)) != CODA_OK) return st;
     const bool f8 = A->dtype == CODA_F8E4M3 || B->dtype == CODA_F8E4M3;
-    if (f8 && (A->dtype != B->dtype || A->trans || !B->trans)) return CODA_ERR_DTYPE;   // both 8-bit, both K-contiguous
-    if (f8 && (K & 15)) return CODA_ERR_SHAPE;                                           // whole 16-byte chunks along K
+    if (f8 && A->dtype != B->dtype) return CODA_ERR_DTYPE;                               // both 8-bit
+    // 8-bit operands move in 16-byte chunks: 16 elements along whichever index is contiguous in memory
+    if (f8 && ((K & 15) || (A->trans && (M & 15)) || (!B->trans && (N & 15)))) return CODA_ERR_SHAPE;
     if ((K & 7) || (N & 7) || (A->trans && (M & 7))) return CODA_ERR_SHAPE;
     Parsed ps;
     if ((st = parse_program(prog, n_ops, N, ps)) != CODA_OK) return st;
@@ -325,8 +327,14 @@ coda_status gemm_impl(void *stream, int64_t M, int64_t N, int64_t K, const coda_
         }
     }
     if (f8) {
-        using namespace coda;
-        e = dispatch_mode_f8(ps.mode, kind, p, s);
+        if (ak && !bkc)
+            e = dispatch_mode_f8<true, false>(ps.mode, kind, p, s);
+        else if (ak && bkc)
+            e = dispatch_mode_f8<true, true>(ps.mode, kind, p, s);
+        else if (!ak && !bkc)
+            e = dispatch_mode_f8<false, false>(ps.mode, kind, p, s);
+        else
+            e = dispatch_mode_f8<false, true>(ps.mode, kind, p, s);
     } else if (ak && !bkc)
         e = dispatch_mode<true, false>(ps.mode, kind, p, s);
     else if (ak && bkc)

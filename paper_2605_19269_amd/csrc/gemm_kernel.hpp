@@ -1539,7 +1539,7 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 }
 
 // ---------------------------------------------------------------------------------
-// 8-bit operands (OCP E4M3), both stored with the contraction index contiguous: A [M x K], B [N x K] bytes.
+// 8-bit operands (OCP E4M3).  First the layout with both operands stored with the contraction index contiguous: A [M x K], B [N x K] bytes.
 // One K-step is 64 elements = 64 bytes per row, so operand tiles, LDS slots and the direct-to-LDS fill have the byte
 // geometry of the bf16 A*B^T kernel's 32-element step: both operands in pair slots (128-byte rows).
 // v_mfma_f32_32x32x64_f8f6f4 takes 32 bytes
@@ -1583,6 +1583,41 @@ __device__ __forceinline__ i32x8 dl_frag_pair_f8(const unsigned char *tile, int 
 
 // RAGGED as in the bf16 kernel: clamped fetches and the bounds-checked epilogue on the edges of M and N; K (a multiple of
 // 16) is rounded up to whole pairs of K-steps, with zeros stored at the positions past it.
+// An 8-bit operand whose OUTPUT index is contiguous in memory (A stored [K x M], B stored [K x N] bytes), a pair of
+// K-steps: [128 k][256 B] tiles (32 KB, the size of the K-contiguous pair tiles), filled k-row by k-row (a wave-load is
+// four k-rows of 256 bytes) and read with the transposing ds_read_b64_tr_b8: within 16 lanes, lane i supplies the
+// address of 8 bytes -- k-row i / 2, byte half i % 2 of a 16-byte chunk -- and receives byte i of each of the eight
+// k-rows, i.e. eight consecutive k of ONE output row / column (the hardware's documented transpose; checked by a
+// probe).  Four such reads give a lane the 32 consecutive k bytes that v_mfma_f32_32x32x64_f8f6f4 wants, in the byte
+// order of the K-contiguous fragment.  The 16-byte chunk c of k-row k sits at chunk position c ^ (2 * (k & 7)): the
+// eight k-rows of a read then fall into eight different bank groups and the two 16-lane groups that share a cycle
+// (adjacent chunks) into the even and the odd ones.
+__device__ __forceinline__ uint32_t dl_goffset_mn_f8(int j, int lane, int64_t ld, int valid)   // valid: a multiple of 16
+{
+    const int k = j * 4 + (lane >> 4);
+    const int c = (lane & 15) ^ (2 * (k & 7));
+    const int col = c * 16;
+    const int cg = col < valid ? col : valid - 16;
+    return (uint32_t)((int64_t)k * ld + cg);
+}
+// k-row, within the 128-wide pair, that lane `lane` of wave-load `j` fetches
+__device__ __forceinline__ int dl_chunk_k_mn_f8(int j, int lane) { return j * 4 + (lane >> 4); }
+// fragment of K-step hs (0 / 1) of the pair: lane -> output row / column col_base + lane % 32, k bytes 32 * (lane / 32) .. + 31
+__device__ __forceinline__ i32x8 dl_frag_mn_f8(const unsigned char *tile, int col_base, int lane, int hs)
+{
+    typedef int v2i __attribute__((ext_vector_type(2)));
+    typedef __attribute__((address_space(3))) v2i lds_v2i;
+    const int i = lane & 15, g = lane >> 4;
+    const int chunk = (col_base >> 4) + (g & 1);
+    const int k0 = 64 * hs + 32 * (g >> 1) + (i >> 1);                       // k-row of the first of the four reads
+    const unsigned char *a = tile + k0 * 256 + ((chunk ^ (2 * (k0 & 7))) << 4) + ((i & 1) << 3);
+    const v2i r0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(a));
+    const v2i r1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(a + 8 * 256));
+    const v2i r2 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(a + 16 * 256));
+    const v2i r3 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(a + 24 * 256));
+    return i32x8{r0[0], r0[1], r1[0], r1[1], r2[0], r2[1], r3[0], r3[1]};
+}
+
 template <class C>
 struct F8Lds {
     // LDS plan of the bf16 A*B^T kernel: three pair slots of A, two pair slots of B, 160 KB; the epilogue stages through
@@ -1593,7 +1628,9 @@ struct F8Lds {
     static_assert(S == 4 && LDS_BYTES >= EPI_RING + RED_BYTES && LDS_BYTES <= 160 * 1024, "LDS plan");
 };
 
-template <class C, int EPI, bool RAGGED>
+// AK / BKC: the operand is stored with the contraction index contiguous (A [M x K], B [N x K]); otherwise with the
+// output index contiguous (A [K x M], B [K x N]).
+template <class C, bool AK, bool BKC, int EPI, bool RAGGED>
 __device__ __forceinline__ void gemm_item_dl_f8(const GemmParams &p, const WorkItem &wi, const int KT_all, unsigned char *smem)
 {
     constexpr int BM = C::BM, BN = C::BN, BKB = 64, FM = C::FM, FN = C::FN, S = C::STAGES, HM = FM / 2;
@@ -1619,11 +1656,15 @@ __device__ __forceinline__ void gemm_item_dl_f8(const GemmParams &p, const WorkI
     const int valid_n = RAGGED ? (p.N - n0 < BN ? p.N - n0 : BN) : BN;
     uint32_t offa[LAP], offb[LBP];
 #pragma unroll
-    for (int i = 0; i < LAP; ++i) offa[i] = dl_goffset_pair_f8(wave * LAP + i, lane, p.lda, valid_m);
+    for (int i = 0; i < LAP; ++i)
+        offa[i] = AK ? dl_goffset_pair_f8(wave * LAP + i, lane, p.lda, valid_m) : dl_goffset_mn_f8(wave * LAP + i, lane, p.lda, valid_m);
 #pragma unroll
-    for (int i = 0; i < LBP; ++i) offb[i] = dl_goffset_pair_f8(wave * LBP + i, lane, p.ldb, valid_n);
-    const unsigned char *ga = reinterpret_cast<const unsigned char *>(p.A) + (int64_t)m0 * p.lda + (int64_t)kbeg * BKB;
-    const unsigned char *gb = reinterpret_cast<const unsigned char *>(p.B) + (int64_t)n0 * p.ldb + (int64_t)kbeg * BKB;
+    for (int i = 0; i < LBP; ++i)
+        offb[i] = BKC ? dl_goffset_pair_f8(wave * LBP + i, lane, p.ldb, valid_n) : dl_goffset_mn_f8(wave * LBP + i, lane, p.ldb, valid_n);
+    // byte advance per K-step and the tile's first byte
+    const int64_t stepa = AK ? (int64_t)BKB : (int64_t)BKB * p.lda, stepb = BKC ? (int64_t)BKB : (int64_t)BKB * p.ldb;
+    const unsigned char *ga = reinterpret_cast<const unsigned char *>(p.A) + (AK ? (int64_t)m0 * p.lda : (int64_t)m0) + kbeg * stepa;
+    const unsigned char *gb = reinterpret_cast<const unsigned char *>(p.B) + (BKC ? (int64_t)n0 * p.ldb : (int64_t)n0) + kbeg * stepb;
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
 
     auto a_slot = [&](int t) { return ((t >> 1) % 3) * (2 * C::A_BYTES); };      // the pair that contains K-step t
@@ -1631,7 +1672,7 @@ __device__ __forceinline__ void gemm_item_dl_f8(const GemmParams &p, const WorkI
     // loads of A for the pair of K-steps t, t + 1 (t even): `part` 0 / 1 = first / second half of the wave's loads, -1 = all
     auto issue_a = [&](int t, int part) {
         const int slot = a_slot(t);
-        const unsigned char *sa = ga + (int64_t)t * BKB;
+        const unsigned char *sa = ga + (int64_t)t * stepa;
         const int i0 = part == 1 ? LAP / 2 : 0, i1 = part == 0 ? LAP / 2 : LAP;
         if (RAGGED && (kbeg + t + 2) * BKB > p.K) {
             // the pair reaches past K: a lane whose chunk lies past K stores zeros at its LDS position instead of fetching
@@ -1640,7 +1681,7 @@ __device__ __forceinline__ void gemm_item_dl_f8(const GemmParams &p, const WorkI
             for (int i = 0; i < LAP; ++i) {
                 if (i < i0 || i >= i1) continue;
                 const int wl = wave * LAP + i;
-                if (dl_chunk_k_pair_f8(wl, lane) < k_left) dl_load16(offa[i], sa, lds0 + (uint32_t)(slot + wl * 1024));
+                if ((AK ? dl_chunk_k_pair_f8(wl, lane) : dl_chunk_k_mn_f8(wl, lane)) < k_left) dl_load16(offa[i], sa, lds0 + (uint32_t)(slot + wl * 1024));
                 else *reinterpret_cast<u32x4 *>(smem + slot + wl * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
             }
             return;
@@ -1652,13 +1693,13 @@ __device__ __forceinline__ void gemm_item_dl_f8(const GemmParams &p, const WorkI
     // loads of B for the pair of K-steps t, t + 1 (t even)
     auto issue_b = [&](int t) {
         const int slot = b_slot(t);
-        const unsigned char *sb = gb + (int64_t)t * BKB;
+        const unsigned char *sb = gb + (int64_t)t * stepb;
         if (RAGGED && (kbeg + t + 2) * BKB > p.K) {
             const int k_left = p.K - (kbeg + t) * BKB;
 #pragma unroll
             for (int i = 0; i < LBP; ++i) {
                 const int wl = wave * LBP + i;
-                if (dl_chunk_k_pair_f8(wl, lane) < k_left) dl_load16(offb[i], sb, lds0 + (uint32_t)(slot + wl * 1024));
+                if ((BKC ? dl_chunk_k_pair_f8(wl, lane) : dl_chunk_k_mn_f8(wl, lane)) < k_left) dl_load16(offb[i], sb, lds0 + (uint32_t)(slot + wl * 1024));
                 else *reinterpret_cast<u32x4 *>(smem + slot + wl * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
             }
             return;
@@ -1670,12 +1711,18 @@ __device__ __forceinline__ void gemm_item_dl_f8(const GemmParams &p, const WorkI
     auto read_a = [&](i32x8(&fa)[HM], int t, int half) {
         const unsigned char *sa = smem + a_slot(t);
 #pragma unroll
-        for (int i = 0; i < HM; ++i) fa[i] = dl_frag_pair_f8(sa, wm * C::WTM + (half * HM + i) * 32, lane, t & 1);
+        for (int i = 0; i < HM; ++i) {
+            const int row = wm * C::WTM + (half * HM + i) * 32;
+            fa[i] = AK ? dl_frag_pair_f8(sa, row, lane, t & 1) : dl_frag_mn_f8(sa, row, lane, t & 1);
+        }
     };
     auto read_b = [&](i32x8(&fb)[FN], int t) {
         const unsigned char *sb = smem + b_slot(t);
 #pragma unroll
-        for (int j = 0; j < FN; ++j) fb[j] = dl_frag_pair_f8(sb, wn * C::WTN + j * 32, lane, t & 1);
+        for (int j = 0; j < FN; ++j) {
+            const int col = wn * C::WTN + j * 32;
+            fb[j] = BKC ? dl_frag_pair_f8(sb, col, lane, t & 1) : dl_frag_mn_f8(sb, col, lane, t & 1);
+        }
     };
     auto mma = [&](const i32x8(&fa)[HM], const i32x8(&fb)[FN], int half) {
 #pragma unroll
@@ -1743,7 +1790,7 @@ __device__ __forceinline__ void gemm_item_dl_f8(const GemmParams &p, const WorkI
 }
 
 // one work item per workgroup, as in the bf16 kernel
-template <class C, int EPI, bool RAGGED, bool TAIL>
+template <class C, bool AK, bool BKC, int EPI, bool RAGGED, bool TAIL>
 __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE))) void gemm_kernel_dl_f8(const GemmParams p)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[F8Lds<C>::LDS_BYTES];
@@ -1753,7 +1800,7 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
         wi = locate_block(p.split_from, p.tail_tiles, p.tail_chunks, (int)blockIdx.x, KT_all);
         if ((int)blockIdx.x >= p.split_from && wi.kcnt == 0) return;
     }
-    gemm_item_dl_f8<C, EPI, RAGGED>(p, wi, KT_all, smem);
+    gemm_item_dl_f8<C, AK, BKC, EPI, RAGGED>(p, wi, KT_all, smem);
 }
 
 // Host-side launcher, one per (operand layouts, epilogue mode, kernel kind).

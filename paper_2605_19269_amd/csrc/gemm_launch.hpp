@@ -36,8 +36,8 @@ hipError_t launch_gemm(const GemmParams &p_in, hipStream_t stream)
     return hipGetLastError();
 }
 
-// 8-bit operands, both K-contiguous.  KIND_WHOLE: M, N multiples of 256 and K a multiple of 128.
-template <int EPI, int KIND>
+// 8-bit operands.  KIND_WHOLE: M, N multiples of 256 and K a multiple of 128.
+template <bool AK, bool BKC, int EPI, int KIND>
 hipError_t launch_gemm_f8(const GemmParams &p_in, hipStream_t stream)
 {
     using C = FastCfg;
@@ -45,15 +45,25 @@ hipError_t launch_gemm_f8(const GemmParams &p_in, hipStream_t stream)
     p.tiles_m = (p.M + C::BM - 1) / C::BM;
     p.tiles_n = (p.N + C::BN - 1) / C::BN;
     if (p.tail_chunks > 0)
-        hipLaunchKernelGGL((gemm_kernel_dl_f8<C, EPI, KIND == KIND_RAGGED, true>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
+        hipLaunchKernelGGL((gemm_kernel_dl_f8<C, AK, BKC, EPI, KIND == KIND_RAGGED, true>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
     else
-        hipLaunchKernelGGL((gemm_kernel_dl_f8<C, EPI, KIND == KIND_RAGGED, false>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
+        hipLaunchKernelGGL((gemm_kernel_dl_f8<C, AK, BKC, EPI, KIND == KIND_RAGGED, false>), dim3(fast_grid(p)), dim3(C::NT), 0, stream, p);
     return hipGetLastError();
 }
 
 #define CODA_INSTANTIATE_ONE(AK, BKC, EPI)                                                   \
     template hipError_t launch_gemm<AK, BKC, EPI, KIND_WHOLE>(const GemmParams &, hipStream_t);   \
     template hipError_t launch_gemm<AK, BKC, EPI, KIND_RAGGED>(const GemmParams &, hipStream_t);
+
+#define CODA_INSTANTIATE_ONE_F8(AK, BKC, EPI)                                                    \
+    template hipError_t launch_gemm_f8<AK, BKC, EPI, KIND_WHOLE>(const GemmParams &, hipStream_t);   \
+    template hipError_t launch_gemm_f8<AK, BKC, EPI, KIND_RAGGED>(const GemmParams &, hipStream_t);
+#define CODA_INSTANTIATE_LAYOUT_F8(AK, BKC)            \
+    CODA_INSTANTIATE_ONE_F8(AK, BKC, EPI_LINEAR)       \
+    CODA_INSTANTIATE_ONE_F8(AK, BKC, EPI_SWIGLU_FWD)   \
+    CODA_INSTANTIATE_ONE_F8(AK, BKC, EPI_SWIGLU_BWD)   \
+    CODA_INSTANTIATE_ONE_F8(AK, BKC, EPI_ACCUM)        \
+    CODA_INSTANTIATE_ONE_F8(AK, BKC, EPI_RMSNORM_BWD)
 
 #define CODA_INSTANTIATE_LAYOUT(AK, BKC)            \
     CODA_INSTANTIATE_ONE(AK, BKC, EPI_LINEAR)       \
@@ -78,16 +88,19 @@ CODA_EXTERN_LAYOUT(true, false)
 CODA_EXTERN_LAYOUT(true, true)
 CODA_EXTERN_LAYOUT(false, false)
 CODA_EXTERN_LAYOUT(false, true)
-extern template hipError_t launch_gemm_f8<EPI_LINEAR, KIND_WHOLE>(const GemmParams &, hipStream_t);
-extern template hipError_t launch_gemm_f8<EPI_LINEAR, KIND_RAGGED>(const GemmParams &, hipStream_t);
-extern template hipError_t launch_gemm_f8<EPI_SWIGLU_FWD, KIND_WHOLE>(const GemmParams &, hipStream_t);
-extern template hipError_t launch_gemm_f8<EPI_SWIGLU_FWD, KIND_RAGGED>(const GemmParams &, hipStream_t);
-extern template hipError_t launch_gemm_f8<EPI_SWIGLU_BWD, KIND_WHOLE>(const GemmParams &, hipStream_t);
-extern template hipError_t launch_gemm_f8<EPI_SWIGLU_BWD, KIND_RAGGED>(const GemmParams &, hipStream_t);
-extern template hipError_t launch_gemm_f8<EPI_ACCUM, KIND_WHOLE>(const GemmParams &, hipStream_t);
-extern template hipError_t launch_gemm_f8<EPI_ACCUM, KIND_RAGGED>(const GemmParams &, hipStream_t);
-extern template hipError_t launch_gemm_f8<EPI_RMSNORM_BWD, KIND_WHOLE>(const GemmParams &, hipStream_t);
-extern template hipError_t launch_gemm_f8<EPI_RMSNORM_BWD, KIND_RAGGED>(const GemmParams &, hipStream_t);
+#define CODA_EXTERN_ONE_F8(AK, BKC, EPI)                                                                \
+    extern template hipError_t launch_gemm_f8<AK, BKC, EPI, KIND_WHOLE>(const GemmParams &, hipStream_t);   \
+    extern template hipError_t launch_gemm_f8<AK, BKC, EPI, KIND_RAGGED>(const GemmParams &, hipStream_t);
+#define CODA_EXTERN_LAYOUT_F8(AK, BKC)            \
+    CODA_EXTERN_ONE_F8(AK, BKC, EPI_LINEAR)       \
+    CODA_EXTERN_ONE_F8(AK, BKC, EPI_SWIGLU_FWD)   \
+    CODA_EXTERN_ONE_F8(AK, BKC, EPI_SWIGLU_BWD)   \
+    CODA_EXTERN_ONE_F8(AK, BKC, EPI_ACCUM)        \
+    CODA_EXTERN_ONE_F8(AK, BKC, EPI_RMSNORM_BWD)
+CODA_EXTERN_LAYOUT_F8(true, false)
+CODA_EXTERN_LAYOUT_F8(true, true)
+CODA_EXTERN_LAYOUT_F8(false, false)
+CODA_EXTERN_LAYOUT_F8(false, true)
 #endif
 
 }  // namespace coda

@@ -80,10 +80,12 @@ def test_argument_errors_are_status_codes(coda):
     assert g(64, 60, 32, A, _mat(coda, P, 32, 60, ld=64), [store]) == coda.CODA_ERR_SHAPE   # N % 8
     assert g(64, 64, 32, A, B, [_op(coda, coda.CODA_EPI_STORE, out=None, ld_out=64)]) == coda.CODA_ERR_NULL
     assert g(64, 64, 32, A, B, [_op(coda, coda.CODA_EPI_STORE, out=P, ld_out=32)]) == coda.CODA_ERR_SHAPE
-    # 8-bit operands (dtype 2): both K-contiguous, K in whole 16-byte chunks; any M
+    # 8-bit operands (dtype 2): any layout; 16-byte chunks along K and along whichever output index is contiguous
     A8, B8 = _mat(coda, P, 64, 32, dtype=2), _mat(coda, P, 64, 32, trans=1, dtype=2)
     assert g(64, 64, 32, A8, _mat(coda, P, 64, 32, trans=1), [store]) == coda.CODA_ERR_DTYPE          # mixed
-    assert g(64, 64, 32, A8, _mat(coda, P, 32, 64, dtype=2), [store]) == coda.CODA_ERR_DTYPE          # B not K-contiguous
+    assert g(0, 64, 32, _mat(coda, P, 0, 32, dtype=2), _mat(coda, P, 32, 64, dtype=2), [store]) == coda.CODA_OK   # N-contiguous B
+    assert g(64, 72, 32, A8, _mat(coda, P, 32, 72, ld=80, dtype=2), [_op(coda, coda.CODA_EPI_STORE, out=P, ld_out=72)]) == coda.CODA_ERR_SHAPE   # N % 16
+    assert g(72, 64, 32, _mat(coda, P, 32, 72, ld=80, trans=1, dtype=2), B8, [store]) == coda.CODA_ERR_SHAPE      # A^T: M % 16
     assert g(64, 64, 24, _mat(coda, P, 64, 24, ld=32, dtype=2), _mat(coda, P, 64, 24, ld=32, trans=1, dtype=2), [store]) == coda.CODA_ERR_SHAPE
     assert g(0, 64, 32, _mat(coda, P, 0, 32, dtype=2), B8, [store]) == coda.CODA_OK
     # row pitches beyond 2^22 elements are refused (32-bit lane offsets in the kernels)

@@ -32,16 +32,16 @@ def _gemm(kernels):
 def _gemm_f8(kernels):
     out = {}
     for name, r in kernels.items():
-        m = re.search(r"gemm_kernel_dl_f8INS_5DlCfg\w+?EEELi(\d)ELb([01])ELb([01])EEEv", name)
+        m = re.search(r"gemm_kernel_dl_f8INS_5DlCfg\w+?EEELb([01])ELb([01])ELi(\d)ELb([01])ELb([01])EEEv", name)
         if m:
-            out[tuple(int(x) for x in m.groups())] = r   # (epilogue mode, ragged, shared tail)
+            out[tuple(int(x) for x in m.groups())] = r   # (A K-contiguous, B K-contiguous, epilogue mode, ragged, shared tail)
     return out
 
 
 def test_every_instance_is_there_and_fits_the_compute_unit(kernels):
     g, f8 = _gemm(kernels), _gemm_f8(kernels)
     assert len(g) == 4 * 5 * 2 * 2, sorted(g)
-    assert len(f8) == 5 * 2 * 2
+    assert len(f8) == 4 * 5 * 2 * 2
     for r in list(g.values()) + list(f8.values()):
         assert r["vgpr"] <= 256 and r["agpr"] == 0          # two waves per SIMD
         assert r["lds"] <= 160 * 1024
@@ -54,7 +54,7 @@ def test_whole_tile_kernels_do_not_spill(kernels):
         if not key[3] and not key[4]:
             assert r["scratch"] == 0 and r["spill"] == 0, (key, r)
     for key, r in _gemm_f8(kernels).items():
-        if not key[1] and not key[2]:
+        if not key[3] and not key[4]:
             assert r["scratch"] == 0 and r["spill"] == 0, (key, r)
 
 
@@ -65,5 +65,5 @@ def test_spills_of_the_other_instances_stay_small(kernels):
         limit = 40 if key[3] else 0
         assert r["spill"] <= limit, (key, r)
     for key, r in _gemm_f8(kernels).items():
-        limit = 40 if key[1] else 0
+        limit = 40 if key[3] else 0
         assert r["spill"] <= limit, (key, r)

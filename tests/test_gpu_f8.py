@@ -1,6 +1,7 @@
-"""GPU parity of the 8-bit-operand variant (OCP E4M3 A [M x K] and B [N x K], fp32 accumulation, the same epilogue
-programs) against the CPU oracle, which decodes the very same bytes by the format's definition and then applies its
-ordinary GEMM definitions.  Covers the decoding of every finite code, every epilogue mode, ragged shapes, and split-K."""
+"""GPU parity of the 8-bit-operand variant (OCP E4M3 operands in all four storage layouts, fp32 accumulation, the same
+epilogue programs) against the CPU oracle, which decodes the very same bytes by the format's definition and then applies
+its ordinary GEMM definitions.  Covers the decoding of every finite code, every epilogue mode, ragged shapes, split-K,
+and the layouts with an operand whose output index is contiguous (read through the 8-bit transposing LDS read)."""
 import numpy as np
 import pytest
 import torch
@@ -180,15 +181,99 @@ def test_f8_accumulate_rmsnorm_backward_rope_lse(oracle, M, N, K):
     assert (d <= 1e-3 * np.maximum(np.abs(reflse), 1.0)).all(), "lse max delta %.3g" % d.max()
 
 
+# shapes for the layouts with an output-index-contiguous operand: that index in whole 16-byte chunks (N, and M when A is
+# stored transposed, multiples of 16); whole tiles | ragged in M, N and K | one short and one long contraction
+LAYOUT_SHAPES = [(256, 256, 128), (512, 768, 384), (272, 528, 208), (208, 272, 144), (256, 512, 2048), (16, 16, 16)]
+
+
+@pytest.mark.parametrize("transA,transB", [(False, False), (True, False), (True, True)])
+@pytest.mark.parametrize("M,N,K", LAYOUT_SHAPES)
+def test_f8_other_operand_layouts(oracle, M, N, K, transA, transB):
+    """A stored [K x M] and / or B stored [K x N] in E4M3 (forward weights kept [in x out], the weight-gradient form
+    A^T B): row scale + residual + row sum of squares against the oracle on the decoded bytes."""
+    g = np.random.Generator(np.random.PCG64(1300 + M + K + 2 * transA + transB))
+    A8 = synth.normal_f8e4m3(g, (K, M) if transA else (M, K), 1.0)
+    B8 = synth.normal_f8e4m3(g, (N, K) if transB else (K, N), 1.0)
+    A16, B16 = oracle.f8e4m3_to_bf16_bits(A8), oracle.f8e4m3_to_bf16_bits(B8)
+    C = synth.normal_bf16(g, (M, N), 1.0)
+    r = synth.uniform_f32(g, (M,), 0.02, 0.06)
+    Y = G.Guarded(M, N, torch.bfloat16)
+    nblk = coda.coda_row_partial_blocks(N)
+    part = torch.full((nblk, M), G.SENTINEL_F32, dtype=torch.float32, device="cuda")
+    dr, dC = G.dev_f32(r), G.dev_bf16(C)
+    coda.coda_gemm(dev_u8(A8), dev_u8(B8), [coda.row_scale(dr), coda.add_tile(dC), coda.row_sumsq(part), coda.store(Y.t)],
+                   transA=transA, transB=transB)
+    ss = torch.empty(M, dtype=torch.float32, device="cuda")
+    coda.coda_row_finalize(part, M, nblk, sum_out=ss, d=N, eps=0.0)
+    torch.cuda.synchronize()
+    refD, refss = oracle.gemm_residual_sumsq(A16, B16, r=r.astype(np.float64), C=C, transA=transA, transB=transB)[:2]
+    Y.check_guards(); Y.written()
+    G.assert_bf16_close(G.host_f64(Y.t), refD, "f8 layout (%d, %d): row scale + residual" % (transA, transB))
+    G.assert_sumsq_close(G.host_f64(ss), refss, "f8 layout (%d, %d): row sum of squares" % (transA, transB))
+
+
+@pytest.mark.parametrize("transA,transB", [(False, False), (True, False), (True, True)])
+def test_f8_other_layouts_decode_every_code_exactly(oracle, transA, transB):
+    """The transposing read hands every byte to the right lane and k position: B (or A) selects single elements of the
+    other operand, which holds every finite code, so D holds the decoded values themselves: exact in fp32."""
+    M, N, K = 256, 256, 128
+    codes = (np.arange(M * K, dtype=np.int64) * 7 % 256).astype(np.uint8).reshape(M, K)
+    codes[(codes & 0x7F) == 0x7F] = 0
+    sel = np.zeros((N, K), np.uint8)
+    sel[np.arange(N), (np.arange(N) * 5 + 3) % K] = 0x38                # 1.0 at one k per column
+    A8 = np.ascontiguousarray(codes.T) if transA else codes
+    B8 = sel if transB else np.ascontiguousarray(sel.T)
+    out = G.Guarded(M, N, torch.float32, pad_cols=4)
+    coda.coda_gemm(dev_u8(A8), dev_u8(B8), [coda.store(out.t, f32=True)], transA=transA, transB=transB)
+    torch.cuda.synchronize()
+    out.check_guards(); out.written()
+    ref = oracle.gemm_rowscale(oracle.f8e4m3_to_bf16_bits(A8), oracle.f8e4m3_to_bf16_bits(B8), transA=transA, transB=transB)
+    got = G.host_f64(out.t)
+    assert np.array_equal(got, ref), "max |delta| %.3g" % np.abs(got - ref).max()
+
+
+def test_f8_weight_gradient_and_forward_weight_layouts_with_their_programs(oracle):
+    """The two uses the other layouts exist for: the forward up-projection with the weight kept [in x out] (row scale +
+    SwiGLU), and the weight gradient A^T B accumulated in fp32 with a split contraction."""
+    g = np.random.Generator(np.random.PCG64(1400))
+    M, N, K = 272, 512, 464
+    X8, W8 = synth.normal_f8e4m3(g, (M, K), 1.0), synth.normal_f8e4m3(g, (K, N), 1.0)
+    r = synth.uniform_f32(g, (M,), 0.02, 0.06)
+    H = G.Guarded(M, N // 2, torch.bfloat16)
+    Z = G.Guarded(M, N, torch.bfloat16)
+    dr = G.dev_f32(r)
+    coda.coda_gemm(dev_u8(X8), dev_u8(W8), [coda.row_scale(dr), coda.swiglu_fwd(Z.t), coda.store(H.t)])
+    torch.cuda.synchronize()
+    refH, refZ = oracle.gemm_rowscale_swiglu(oracle.f8e4m3_to_bf16_bits(X8), oracle.f8e4m3_to_bf16_bits(W8), r=r.astype(np.float64),
+                                             want_preact=True)
+    for t in (H, Z):
+        t.check_guards(); t.written()
+    G.assert_bf16_close(G.host_f64(H.t), refH, "f8 forward weight [in x out]: H")
+    G.assert_bf16_close(G.host_f64(Z.t), refZ, "f8 forward weight [in x out]: pre-activation")
+    # weight gradient: H^T dY over 4096 tokens into an existing fp32 buffer, with and without the workspace
+    T, F, d = 4096, 512, 272
+    H8, dY8 = synth.normal_f8e4m3(g, (T, F), 1.0), synth.normal_f8e4m3(g, (T, d + 0), 1.0)
+    G0 = synth.normal_f32(g, (F, d), 1.0)
+    need = coda.coda_gemm_workspace_bytes(F, d, T, [])
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda").fill_(0x5A)
+    ref = oracle.gemm_accumulate(oracle.f8e4m3_to_bf16_bits(H8), oracle.f8e4m3_to_bf16_bits(dY8), G0, transA=True)
+    for w in (None, ws):
+        Gb = G.dev_f32(G0)
+        coda.coda_gemm(dev_u8(H8), dev_u8(dY8), [coda.accum_f32(Gb)], transA=True, workspace=w)
+        torch.cuda.synchronize()
+        G.assert_f32_signed_close(G.host_f64(Gb), ref, "f8 weight gradient (workspace %s)" % (w is not None))
+
+
 def test_f8_argument_errors(oracle):
     M, N, K = 256, 256, 128
     A8 = torch.zeros((M, K), dtype=torch.uint8, device="cuda")
     B8 = torch.zeros((N, K), dtype=torch.uint8, device="cuda")
     Bb = torch.zeros((N, K), dtype=torch.bfloat16, device="cuda")
-    Bn = torch.zeros((K, N), dtype=torch.uint8, device="cuda")
+    Bn = torch.zeros((K, N + 16), dtype=torch.uint8, device="cuda")
     out = G.Guarded(M, N, torch.bfloat16)
     for a, b, kw, status in [(A8, Bb, dict(transB=True), "CODA_ERR_DTYPE"),            # mixed operand types
-                             (A8, Bn, dict(), "CODA_ERR_DTYPE"),                        # B not K-contiguous
+                             (A8, Bn[:, :N + 8], dict(), "CODA_ERR_SHAPE"),             # N-contiguous B: N not a multiple of 16
                              (A8[:, :72], B8[:, :72], dict(transB=True), "CODA_ERR_SHAPE")]:   # K not a multiple of 16
         with pytest.raises(coda.CodaError) as ei:
             coda.coda_gemm(a, b, [coda.store(out.t)], **kw)
