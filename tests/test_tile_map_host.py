@@ -135,3 +135,15 @@ def test_each_xcd_walks_a_compact_patch(hostlib):
             t = m[rnd + x:rnd + 256:8]
             assert len(t) == 32
             assert len(set(t[:, 0].tolist())) + len(set(t[:, 1].tolist())) <= 12 + 2, "patch of XCD %d in round %d is not compact" % (x, rnd // 256)
+
+
+def test_reported_workspace_covers_the_plan_of_either_operand_width(hostlib):
+    """coda_gemm plans with the operands' width (an 8-bit K-step covers twice the elements), the size query does not
+    know it: over a sweep of K and of tile counts the reported size covers both plans."""
+    from paper_2605_19269_amd import coda
+    plan = (ctypes.c_int * 5)()
+    for (M, N) in ((256, 256), (512, 512), (1024, 2048), (5120, 4096), (2304, 4096)):
+        for K in list(range(1024, 9300, 208)) + [4240, 8192, 16384]:
+            need16 = hostlib.host_plan(M, N, K, 0, plan)
+            need8 = hostlib.host_plan(M, N, K, 1, plan)
+            assert coda.coda_gemm_workspace_bytes(M, N, K, []) == max(need16, need8), (M, N, K)
