@@ -32,8 +32,8 @@ PEAK_HBM_TBS = 8.0          # MI355X HBM3E
 # by this run: rocprofv3 --pmc counters of profiles/gemm_epilogue_llama1b_mlp_block_hbm_traffic.md (FETCH_SIZE and
 # WRITE_SIZE in KiB per dispatch, each scaled by the factor that the same counter shows for a plain 256 MiB copy in the
 # same profiling run).  Algorithmic bytes are 234.9e6.
-TRAFFIC_FETCH_KIB, TRAFFIC_FETCH_FACTOR = 393597, 2.0
-TRAFFIC_WRITE_KIB, TRAFFIC_WRITE_FACTOR = 131330, 1.0
+TRAFFIC_FETCH_KIB, TRAFFIC_FETCH_FACTOR = 393575, 2.0
+TRAFFIC_WRITE_KIB, TRAFFIC_WRITE_FACTOR = 131108, 1.0
 MEASURED_TRAFFIC_BYTES = int(TRAFFIC_FETCH_KIB * 1024 * TRAFFIC_FETCH_FACTOR + TRAFFIC_WRITE_KIB * 1024 * TRAFFIC_WRITE_FACTOR)
 TRAFFIC_SOURCE = ("stored figure from profiles/gemm_epilogue_llama1b_mlp_block_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE x %.1f + "
                   "WRITE_SIZE x %.1f, factors from a plain 256 MiB copy in the same profiling run; counted at the L2 -> fabric "
@@ -55,8 +55,9 @@ SINGLE_KERNELS = ["llama1b_up", "llama1b_down", "llama1b_bwd_act", "llama1b_bwd_
                   "llama8b_qkv_bwd_rmsnorm_backward", "lm_head_logits_lse_partials", "copy256"]
 
 
-def single_kernel(name, steps, warmup):
-    """One named kernel launched `steps` times between a pair of HIP events: the launches a profiler run should see."""
+def single_kernel(name, steps, warmup, settle):
+    """One named kernel launched `steps` times between a pair of HIP events: the launches a profiler run should see.
+    `settle` untimed launches come first (clock ramp; pass --settle-steps 0 under counter collection)."""
     import torch
     from paper_2605_19269_amd import coda
     dev = "cuda"
@@ -131,7 +132,7 @@ def single_kernel(name, steps, warmup):
         what = "row scale + log-sum-exp partials + logits store (Kernels 3/8)"
     else:
         sys.exit("bench.py: unknown --kernel %r; one of %s" % (name, ", ".join(SINGLE_KERNELS)))
-    for _ in range(warmup):
+    for _ in range(settle + warmup):
         fn()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -143,7 +144,7 @@ def single_kernel(name, steps, warmup):
     ms = a.elapsed_time(b) / steps
     rec = roof_entry(what, shape, flop, nbytes, ms) if flop else {"kernel": what, "ms": round(ms, 4), "bytes": nbytes,
                                                                  "GBps": round(nbytes / ms * 1e-6, 1)}
-    rec.update({"name": name, "launches": steps, "warmup": warmup, "data": "synthetic"})
+    rec.update({"name": name, "launches": steps, "warmup": warmup, "settle": settle, "data": "synthetic"})
     print(json.dumps(rec))
 
 
@@ -183,7 +184,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
     if args.kernel:
-        return single_kernel(args.kernel, args.steps, args.warmup)
+        return single_kernel(args.kernel, args.steps, args.warmup, max(0, args.settle_steps))
     dev = "cuda"
     M, d, F = 8192, 2048, 8192
 
