@@ -523,8 +523,8 @@ def main():
         del x8, w8, h8, hh8, wd8, y8, a8, b8, c8, wn8, dy8, g8
 
         # shared tiles (split-K / balanced stream-K tail) on shapes with few output tiles, one partly filled round (40 and 144
-        # tiles: ranges that straddle tile boundaries) and a partly filled last round (320, 384 tiles); 448 tiles (last round
-        # three quarters full) is planned unsplit.  The same call with and without the workspace that enables the sharing
+        # tiles; the 40 tiles are cut into ranges that straddle tile boundaries, the 144 run unsplit: measured to lose) and a
+        # partly filled last round (320, 384 tiles); 448 tiles (last round three quarters full) is planned unsplit.  The same call with and without the workspace that enables the sharing
         spk = {}
         for (Ms, Ns, Ks) in ((512, 512, 8192), (1024, 1024, 8192), (2048, 2048, 8192), (2560, 1024, 8192), (2304, 4096, 8192),
                              (5120, 4096, 8192), (6144, 4096, 8192), (7168, 4096, 8192)):

@@ -201,7 +201,7 @@ typedef struct coda_epi_op {
  * workspace / workspace_bytes (device memory, 16-byte aligned; may be NULL): scratch for sharing output tiles
  * among workgroups (split-K / stream-K).  A shape with fewer than 256 output tiles (256 x 256, counted with a ragged
  * edge) leaves compute units idle, and a shape with more ends with a partly filled round of tiles.  When those
- * tiles (the "tail") number at most 144 and the contraction is long enough (K >= 2048, and every workgroup must be
+ * tiles (the "tail") number at most 128 and the contraction is long enough (K >= 2048, and every workgroup must be
  * spared at least 64 K-steps of 32 elements), coda_gemm_workspace_bytes returns a non-zero size, and a call that brings
  * that much workspace cuts the K-steps of the tail, laid end to end, into up to 256 equal contiguous ranges, one or two
  * workgroups each (a range may end in one tile and begin in the next): partial tiles go to the workspace in fp32, and

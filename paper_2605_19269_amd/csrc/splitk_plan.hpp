@@ -19,14 +19,15 @@ constexpr int64_t PLAN_TILE_M = 256, PLAN_TILE_N = 256;   // the kernels' workgr
 //    read once: the full-chip exchange costs about 70 us): a workgroup must be spared at least SPLITK_MIN_SPARED_STEPS
 //    K-steps of a tile, and must be left with at most SPLITK_MAX_SHARE_NUM / _DEN of one.
 // Measured (residual + sum-of-squares program, bf16, against the same launch without workspace): K = 8192: 4 tiles
-// 2.7x, 16 tiles 2.4x, 64 tiles 1.7x, 72 tiles +18 %, 96 tiles +31 %, 128 tiles +23 %, 160 tiles +0 %; 272 tiles +36 %,
+// 2.7x, 16 tiles 2.4x, 40 tiles +73 %, 64 tiles 1.7x, 72 tiles +18 %, 96 tiles +31 %, 128 tiles +23 %; 272 tiles +36 %,
 // 320 tiles +20 %, 384 tiles +10 %, 576 tiles +13 %; K = 4096: 16 tiles +78 %, 64 tiles +21 %, 128 tiles +6 %, 320 tiles
 // +8 %, 384 tiles +4 %; K = 2048 (32 K-steps spared at best): 16 tiles +1 to +6 %, 64 tiles -2 %, 384 tiles -9 %.  Rounds
-// that are fuller than 5/8 lose -- 192 tiles -3 %, 208 tiles -29 % (ranges of 13/16 of a tile leave slivers of 1/16, each
-// with its own pipeline fill and exchange), 448 tiles -5 % at K = 8192 and -2 % at K = 16384, 496 tiles -19 % -- and run
-// unsplit.  Hence: spared >= 64 K-steps, share <= 9/16 (a round of up to 144 tiles).
+// that are more than half full lose -- 144 tiles -17 %, 160 tiles +0 %, 192 tiles -3 %, 208 tiles -29 % (ranges of 13/16 of
+// a tile leave slivers of 1/16, each with its own pipeline fill and exchange), 448 tiles -5 % at K = 8192 and -2 % at
+// K = 16384, 496 tiles -19 % -- and run unsplit.  Hence: spared >= 64 K-steps, share <= 1/2 (a round of up to 128 tiles;
+// ranges straddle tile boundaries when tail * parts exceeds the chip, e.g. 40 tiles x 8 parts: +73 %).
 constexpr int64_t SPLITK_CUS = 256, SPLITK_MAX_PARTS = 8, SPLITK_MIN_K = 1024, SPLITK_MIN_SPARED_STEPS = 64;
-constexpr int64_t SPLITK_MAX_SHARE_NUM = 9, SPLITK_MAX_SHARE_DEN = 16;
+constexpr int64_t SPLITK_MAX_SHARE_NUM = 1, SPLITK_MAX_SHARE_DEN = 2;
 struct SplitPlan {
     int first;    // tiles below `first` run whole
     int tail;     // number of shared tiles (ids first .. first + tail - 1)

@@ -180,8 +180,8 @@ def test_splitk_workspace_planning_and_errors(coda):
     assert wb(6144, 4096, 4096) == 1024 + 128 * 2 * tile    # the same with K = 4096: each workgroup is spared 64 K-steps
     assert wb(6144, 4096, 2048) == 0                        # ... with K = 2048 only 32: not worth the exchange
     assert wb(5120, 4096, 2048) == 0                        # contraction too short
-    assert wb(2304, 4096, 8192) == 1024 + 144 * 3 * tile    # one round of 144 tiles: 256 ranges of 9/16 of a tile, up to 3 per tile
-    assert wb(2560, 4096, 8192) == 0                        # 160 tiles: measured to gain nothing
+    assert wb(2560, 1024, 8192) == 1024 + 40 * 8 * tile     # 40 tiles x 8 parts exceed the chip: 256 ranges that straddle tiles, up to 8 per tile
+    assert wb(2304, 4096, 8192) == 0                        # one round of 144 tiles: more than half full, measured to lose
     assert wb(7168, 4096, 8192) == 0                        # 448 tiles: the last round is three quarters full (measured: a loss)
     assert wb(8192, 4096, 4096) == 0                        # 512 tiles: whole rounds
     assert wb(0, 512, 4096) == 0 and wb(-1, 512, 4096) == 0

@@ -54,7 +54,7 @@ def launch_map(lib, M, N, K, f8=False, use_plan=True):
 # partly filled last round of 16, 64, 128 and 192 tiles; a single round of 128 and 200 tiles), ragged tile counts, one tile
 SHAPES = [(8192, 16384, 2048), (8192, 2048, 8192), (8192, 8192, 2048), (16384, 6144, 4096), (16384, 28672, 4096),
           (16384, 4096, 14336), (8192, 32768, 4096), (8192, 57344, 8192), (512, 512, 8192), (1024, 1024, 8192),
-          (2048, 2048, 8192), (5120, 4096, 8192), (6144, 4096, 8192), (7168, 4096, 8192), (2048, 4096, 8192), (3200, 4096, 16384), (2304, 4096, 8192), (6400, 4096, 16384),
+          (2048, 2048, 8192), (5120, 4096, 8192), (6144, 4096, 8192), (7168, 4096, 8192), (2048, 4096, 8192), (3200, 4096, 16384), (2304, 4096, 8192), (18944, 1024, 8192), (2560, 1024, 16384),
           (256, 256, 6272), (504, 264, 4168), (8200, 8192, 8192), (8448, 2304, 200), (4000, 4000, 4000), (256, 256, 64), (8, 8, 8),
           (69632, 256, 8192), (7000, 3000, 5000)]
 
@@ -111,17 +111,19 @@ def test_every_tile_and_part_is_reached_exactly_once(hostlib, M, N, K, f8):
         assert need == 0 and n_shared == 0
 
 
-def test_plan_covers_a_round_that_is_more_than_half_full(hostlib):
-    """400 tiles with a long contraction: the last round holds 144 tiles, cut into 256 ranges of 9/16 of a tile."""
-    m, (tiles_m, tiles_n, kt_all, first, tail, chunks, stride, need) = launch_map(hostlib, 6400, 4096, 8192)
-    assert (first, tail, chunks) == (256, 144, 256) and stride == 3
+def test_plan_with_ranges_that_straddle_tiles_and_its_limits(hostlib):
+    """296 tiles with a long contraction: the last round holds 40 tiles; 8 parts each would need 320 workgroups, so their
+    K-steps are cut into 256 equal ranges (5/32 of a tile each) that straddle tile boundaries."""
+    m, (tiles_m, tiles_n, kt_all, first, tail, chunks, stride, need) = launch_map(hostlib, 18944, 1024, 8192)
+    assert (first, tail, chunks) == (256, 40, 256) and stride == 8
     sizes = {}
     for r in m:
         if r[8] >= 0:
             sizes[int(r[8])] = sizes.get(int(r[8]), 0) + int(r[5])
-    assert set(sizes.values()) == {kt_all * 9 // 16}
-    # a fuller round (448 tiles: 192 in the last round) and a short contraction are left alone: measured to lose
-    for shape in ((7168, 4096, 8192), (2560, 4096, 2048)):
+    assert set(sizes.values()) == {kt_all * 5 // 32}
+    assert sum(1 for r in m if r[8] >= 0) > chunks, "some ranges must consist of two pieces"
+    # a round that is more than half full (144 and 192 tiles) and a short contraction are left alone: measured to lose
+    for shape in ((2304, 4096, 8192), (7168, 4096, 8192), (2560, 1024, 2048)):
         _, (_, _, _, first, tail, chunks, _, need) = launch_map(hostlib, *shape)
         assert chunks == 0 and need == 0
 
