@@ -28,6 +28,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace coda {
 
@@ -1239,19 +1240,30 @@ __device__ __forceinline__ bf16x8 dl_frag16(const unsigned char *tile, int row_b
 
 // bf16 kernel.  One K-step of 32 is ONE v_mfma_f32_16x16x32_bf16 per 16x16 block (this shape draws less power per
 // FLOP than 32x32x16 and sustains a higher clock on non-trivial operands); the wave's 128 x 64 tile is 8 x 4 blocks.
-// Per K-step the work is split in two halves of the wave's rows, so that the fragment reads of one half run under the
-// MFMAs of the other, with the workgroup barrier between them:
-//   A  issue loads of tile kt+S-1 into the slot freed by tile kt-1 (a K-contiguous A operand: half of the wave's loads
-//      of the PAIR of K-steps kt+S, kt+S+1 for even kt / the other half for odd kt, into the slot freed by the pair that
-//      ended with kt-1: 128-byte rows, whole cache lines per request; a K-contiguous B beside it is fetched in pairs too,
-//      the whole pair kt+3, kt+4 in odd steps right behind the barrier of step C)
-//   B  read the row fragments of the upper half of tile kt; MFMAs of the lower half (fragments already in VGPRs)
-//   C  wait until this wave's loads of tile kt+1 have landed; workgroup barrier
-//   D  read the lower-half row fragments and the column fragments of tile kt+1; MFMAs of the upper half
-// The barrier orders (i) every wave's reads of tile kt before the slot is refilled in step A of kt+1 and (ii) all
-// loads of tile kt+1 before step D.  The loads are issued from inline asm, invisible to the compiler's waitcnt
-// insertion; vmcnt is waited on explicitly (loads retire in order).  K-steps are walked in pairs so that the two
-// column-fragment buffers swap roles without copies: the host guarantees an even, positive count per workgroup.
+// A K-step of a wave is four phases, a workgroup barrier between them, alternately "memory" and "compute":
+//   M1  issue the loads of tile kt+S-1 into the slot freed by tile kt-1 (a K-contiguous A operand: half of the wave's
+//       loads of the PAIR of K-steps kt+S, kt+S+1 for even kt / the other half for odd kt, into the slot freed by the
+//       pair that ended with kt-1: 128-byte rows, whole cache lines per request; a K-contiguous B beside it is fetched
+//       in pairs too, the whole pair kt+3, kt+4 in phase M2 of odd steps); read the row fragments of the upper half
+//       of tile kt; wait until this wave's loads of tile kt+1 have landed
+//   C1  the MFMAs of the lower half of the rows (fragments read in M2 of the step before)
+//   M2  read the lower-half row fragments and the column fragments of tile kt+1
+//   C2  the MFMAs of the upper half
+// The two waves of a SIMD (waves w and w + 4) run ONE PHASE APART -- the second group passes one barrier more ahead of the
+// loop, the first one more behind it -- so while one computes the other is in a memory phase ("ping-pong").  A compute
+// phase runs at raised priority: the matrix pipe then takes its MFMAs back to back and the partner's LDS, load and scalar
+// instructions fill the other issue slots; it also forms the LDS addresses of the wave's next memory phase (one add each:
+// loop-invariant lane parts plus the slot's scalar offset), since a vector instruction issued from a memory phase has to
+// wait for a slot that the computing partner leaves free (measured: ~25 cycles each, which made the phases uneven).
+// With all eight waves in step instead (one barrier per K-step, every wave reading and computing at the same time) the
+// waves of a SIMD were stalled on LDS at the same moments and one of them reached the barrier ~400 cycles ahead of the
+// other; this schedule measures +3 to +4 % on all four kernels of the benchmark step.
+// The barriers order (i) every wave's reads of tile kt before that slot is refilled and (ii) all loads of tile kt+1 before
+// anybody's phase M2 of step kt; a wave waits for what it has read from LDS at the end of each compute phase (issued a
+// whole phase before: no stall), so reads never race a refill.  The loads are issued from inline asm, invisible to the
+// compiler's waitcnt insertion; vmcnt is waited on explicitly (loads retire in order).  K-steps are walked in pairs so
+// that the two column-fragment buffers swap roles without copies: the host guarantees an even, positive count per
+// workgroup.
 // RAGGED: M, N or K is not a whole number of tiles.  Tiles on the edge of M or N clamp their operand fetches and run the
 // bounds-checked epilogue; K is rounded up to whole pairs of K-steps and the tile fill stores zeros at the positions
 // past K.
@@ -1395,6 +1407,87 @@ __device__ __forceinline__ void gemm_item_dl(const GemmParams &p, const WorkItem
             fa[i] = PAIRED ? dl_frag16_pair(sa, row, lane, t & 1) : dl_frag16<BM, AK>(sa, row, lane);
         }
     };
+    // The same fragment reads with the address arithmetic split off: the per-lane LDS byte offsets of a group of fragments
+    // (one offset when the operand is K-contiguous -- the blocks of a group then lie a constant apart -- else one per
+    // block) are worked out in a compute phase, where the wave's vector instructions slot in between its own MFMAs, and
+    // the memory phase behind it issues nothing but the reads.  (In a memory phase every vector instruction waits for a
+    // slot that the computing wave of the same SIMD, at raised priority, leaves free: measured at ~25 cycles each.)
+    constexpr int NAA = AK ? 1 : HM, NAB = BKC ? 1 : NJ;
+    auto frag_off = [&](auto kcont, auto paired, auto rows, int slot_off, int row0, int t) -> uint32_t {
+        // offset of the 16-row fragment that starts at row row0 of the operand tile of K-step t
+        if constexpr (decltype(paired)::value) {
+            const int r = row0 + (lane & 15), c = (t & 1) * 4 + (lane >> 4);
+            return (uint32_t)(slot_off + r * 128 + ((c ^ (r & 7)) << 4));
+        } else if constexpr (decltype(kcont)::value) {
+            const int r = row0 + (lane & 15);
+            return (uint32_t)(slot_off + r * 64 + (((lane >> 4) ^ kc16_swz(r)) << 4));
+        } else {
+            const int i = lane & 15, kq = lane >> 4;
+            return (uint32_t)slot_off + lds_mn<decltype(rows)::value>(8 * kq + (i >> 2), row0 >> 4) + (uint32_t)((i & 3) << 3);
+        }
+    };
+    auto pin = [](uint32_t &x) { asm volatile("" : "+v"(x)); };
+    // Loop-invariant lane parts, computed once: per K-step parity for a K-contiguous operand fetched in pairs (the
+    // step's position inside the 128-byte rows), per 16-row block for an MN-contiguous one (the XOR swizzle permutes the
+    // blocks lane by lane).  In the loop an address is one add of the slot's (scalar) offset.
+    constexpr int NLA = AK ? 2 : 2 * HM, NLB = BKC ? (PAIRB ? 2 : 1) : NJ;
+    uint32_t la[NLA], lb[NLB];
+#pragma unroll
+    for (int q = 0; q < NLA; ++q) {
+        la[q] = frag_off(std::integral_constant<bool, AK>{}, std::integral_constant<bool, PAIRED>{}, std::integral_constant<int, BM>{},
+                         0, AK ? wm * C::WTM : wm * C::WTM + q * 16, AK ? q : 0);
+        pin(la[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < NLB; ++q) {
+        lb[q] = frag_off(std::integral_constant<bool, BKC>{}, std::integral_constant<bool, PAIRB>{}, std::integral_constant<int, BN>{},
+                         0, BKC ? wn * C::WTN : wn * C::WTN + q * 16, PAIRB ? q : 0);
+        pin(lb[q]);
+    }
+    // `par`: parity of K-step t (known where the call is written)
+    // (the slot offset is pinned in a scalar register so that the sum is formed here, as one add, and not re-associated
+    // into pieces that land elsewhere)
+    auto prep_a = [&](uint32_t(&x)[NAA], int t, int par, int half) {
+        uint32_t so = (uint32_t)(a_slot(t) + (AK ? half * HM * 16 * 128 : 0));
+        asm volatile("" : "+s"(so));
+#pragma unroll
+        for (int i = 0; i < NAA; ++i) {
+            x[i] = (AK ? la[par] : la[AK ? 0 : half * HM + i]) + so;
+            pin(x[i]);
+        }
+    };
+    auto prep_b = [&](uint32_t(&x)[NAB], int t, int par) {
+        uint32_t so = (uint32_t)b_slot(t);
+        asm volatile("" : "+s"(so));
+#pragma unroll
+        for (int j = 0; j < NAB; ++j) {
+            x[j] = (BKC ? lb[PAIRB ? par : 0] : lb[BKC ? 0 : j]) + so;
+            pin(x[j]);
+        }
+    };
+    auto load_frag = [&](auto kcont, auto rows, uint32_t off) -> bf16x8 {
+        if constexpr (decltype(kcont)::value) {
+            return *reinterpret_cast<const bf16x8 *>(smem + off);
+        } else {
+            typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+            typedef __attribute__((ext_vector_type(8))) short s16x8;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(smem + off));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(smem + off + 4 * decltype(rows)::value * 2));
+            return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+    };
+    auto load_a = [&](bf16x8(&fa)[HM], const uint32_t(&x)[NAA]) {
+#pragma unroll
+        for (int i = 0; i < HM; ++i)
+            fa[i] = load_frag(std::integral_constant<bool, AK>{}, std::integral_constant<int, BM>{},
+                              AK ? x[0] + (uint32_t)(i * 16 * (PAIRED ? 128 : 64)) : x[AK ? 0 : i]);
+    };
+    auto load_b = [&](bf16x8(&fb)[NJ], const uint32_t(&x)[NAB]) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+            fb[j] = load_frag(std::integral_constant<bool, BKC>{}, std::integral_constant<int, BN>{},
+                              BKC ? x[0] + (uint32_t)(j * 16 * (PAIRB ? 128 : 64)) : x[BKC ? 0 : j]);
+    };
     auto read_b = [&](bf16x8(&fb)[NJ], int t) {
         const unsigned char *sb = smem + b_slot(t);
 #pragma unroll
@@ -1410,6 +1503,20 @@ __device__ __forceinline__ void gemm_item_dl(const GemmParams &p, const WorkItem
             for (int j = 0; j < NJ; ++j)
                 acc.a[half * HM + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc.a[half * HM + i][j], 0, 0, 0);
     };
+    // Phase boundary: a workgroup barrier that no instruction may be moved across.  The barrier instruction alone: what a
+    // wave has read from LDS it has waited for at the end of the compute phase before (below), and what it has loaded into
+    // LDS it has waited for (vmcnt) in its memory phase.
+    auto phase_barrier = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // Each compute phase runs with the wave's priority raised (its SIMD partner is in a memory phase meanwhile) and works
+    // out the addresses of the memory phase that follows; at its end everything this wave has read from LDS so far has
+    // arrived (issued a whole phase ago: no stall), so that a slot is never refilled while a read of it is still queued.
+    uint32_t xah[NAA], xal[NAA], xb[NAB];
     // Refill issued in step kt: B of K-step kt+S-1 into the slot freed by kt-1; A of K-step kt+S-1 likewise, or (PAIRED) half
     // of the loads of the pair kt+S, kt+S+1 (kt even; the other half in step kt+1) into the slot freed by the pair kt-2, kt-1.
     // Either way every step issues LA+LB loads per wave, A first, and (S-2)*(LA+LB) loads of later K-steps are in flight when
@@ -1438,10 +1545,9 @@ __device__ __forceinline__ void gemm_item_dl(const GemmParams &p, const WorkItem
             }
             exact = refill && (!RAGGED || (kbeg + kt + S) * BK <= p.K);
         }
-        read_a(fah, kt, 1);                                              // B
-        mma(fal, fbc, 0);
+        load_a(fah, xah);                                                // memory phase 1 (behind the loads issued above)
         if (!last) {
-            // C: K-step kt+1 must have landed, the loads of kt+2 and kt+3 may be in flight
+            // K-step kt+1 must have landed before anybody's memory phase 2, the loads of kt+2 and kt+3 may be in flight
             if (PAIRB) {
                 if (!even) {
                     if (exact) {
@@ -1455,12 +1561,29 @@ __device__ __forceinline__ void gemm_item_dl(const GemmParams &p, const WorkItem
             } else {
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             }
-            __syncthreads();
-            if (PAIRB && !even && (steady || kt + S < KT)) issue_b(kt + S - 1);
-            read_a(fal, kt + 1, 0);                                      // D
-            read_b(fbn, kt + 1);
         }
+        phase_barrier();
+        __builtin_amdgcn_s_setprio(1);                                   // compute phase 1
+        mma(fal, fbc, 0);
+        if (!last) {
+            prep_b(xb, kt + 1, even ? 1 : 0);
+            prep_a(xal, kt + 1, even ? 1 : 0, 0);
+        }
+        __builtin_amdgcn_s_setprio(0);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        phase_barrier();
+        if (!last) {                                                     // memory phase 2
+            if (PAIRB && !even && (steady || kt + S < KT)) issue_b(kt + S - 1);
+            load_b(fbn, xb);
+            load_a(fal, xal);
+        }
+        phase_barrier();
+        __builtin_amdgcn_s_setprio(1);                                   // compute phase 2
         mma(fah, fbc, 1);
+        if (!last) prep_a(xah, kt + 1, even ? 1 : 0, 1);
+        __builtin_amdgcn_s_setprio(0);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        phase_barrier();
     };
 
     if (KT > 0) {
@@ -1496,6 +1619,9 @@ __device__ __forceinline__ void gemm_item_dl(const GemmParams &p, const WorkItem
         __syncthreads();
         read_a(fal, 0, 0);
         read_b(fb0, 0);
+        prep_a(xah, 0, 0, 1);
+        // The second wave of every SIMD runs one phase behind the first: while one computes, the other is in a memory phase.
+        if (wave >= C::WGM * C::WGN / 2) phase_barrier();
         int kt = 0;
         for (; kt + S + (PAIRED ? 1 : 0) < KT; kt += 2) {   // every refill of both steps exists: branch-free body
             step(kt, fb0, fb1, false, true, true);
@@ -1507,6 +1633,7 @@ __device__ __forceinline__ void gemm_item_dl(const GemmParams &p, const WorkItem
         }
         step(KT - 2, fb0, fb1, false, false, true);
         step(KT - 1, fb1, fb0, true, false, false);
+        if (wave < C::WGM * C::WGN / 2) phase_barrier();   // every wave passes the same number of barriers
     }
     __syncthreads();  // every wave is done with the operand ring before the epilogue reuses it
 
