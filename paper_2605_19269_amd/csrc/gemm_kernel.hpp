@@ -1859,28 +1859,121 @@ __device__ __forceinline__ void gemm_item_dl_f8(const GemmParams &p, const WorkI
                 acc.a[half * HM + i][j] =
                     __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j], fa[i], acc.a[half * HM + i][j], 0, 0, 0, 0, 0, 0);
     };
-    // refills and waits as in the bf16 A*B^T kernel: half of A's pair kt+S, kt+S+1 before the waits of every step, B's whole
-    // pair kt+3, kt+4 behind the barrier of every odd step; only odd steps wait, for all but A's newest pair
+    // Fragment reads with the address arithmetic split off, as in the bf16 kernel: loop-invariant lane parts (K-contiguous:
+    // the two 16-byte halves of a lane's 32 bytes, whose order the XOR swizzle decides lane by lane; output-contiguous: one
+    // per 32-row block, which the swizzle permutes lane by lane), the slot's scalar offset added in a compute phase.
+    // K-step parity h adds 64 bytes (K-contiguous: rows of 128) or 64 k-rows of 256 bytes.
+    constexpr int NXA = AK ? 2 : HM, NXB = BKC ? 2 : FN, NLA8 = AK ? 2 : 2 * HM;
+    auto pin = [](uint32_t &x) { asm volatile("" : "+v"(x)); };
+    auto lane_pair = [&](int row0, int which) -> uint32_t {            // which: 0 = low 16 bytes, 1 = high
+        const int r = row0 + (lane & 31), c = 2 * (lane >> 5) + which, sw = (r >> 1) & 7;
+        return (uint32_t)(r * 128 + ((c ^ sw) << 4));
+    };
+    auto lane_mn = [&](int col0) -> uint32_t {
+        const int i = lane & 15, g = lane >> 4;
+        const int chunk = (col0 >> 4) + (g & 1), k0 = 32 * (g >> 1) + (i >> 1);
+        return (uint32_t)(k0 * 256 + ((chunk ^ (2 * (k0 & 7))) << 4) + ((i & 1) << 3));
+    };
+    uint32_t la8[NLA8], lb8[NXB];
+#pragma unroll
+    for (int q = 0; q < NLA8; ++q) {
+        la8[q] = AK ? lane_pair(wm * C::WTM, q) : lane_mn(wm * C::WTM + q * 32);
+        pin(la8[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < NXB; ++q) {
+        lb8[q] = BKC ? lane_pair(wn * C::WTN, q) : lane_mn(wn * C::WTN + q * 32);
+        pin(lb8[q]);
+    }
+    // K-contiguous swizzle check: with c even, (c + 4h) ^ sw = (c ^ sw) ^ 4h when bit 2 of c is clear (c < 4), so parity h
+    // flips bit 6 of the byte position -- lane-dependent sign, hence it goes into the lane part below via XOR
+    auto prep_a8 = [&](uint32_t(&x)[NXA], int t, int par, int half) {
+        uint32_t so = (uint32_t)(a_slot(t) + (AK ? half * HM * 32 * 128 : par * 64 * 256));
+        asm volatile("" : "+s"(so));
+#pragma unroll
+        for (int i = 0; i < NXA; ++i) {
+            x[i] = (AK ? (la8[i] ^ (uint32_t)(par * 64)) : la8[AK ? 0 : half * HM + i]) + so;
+            pin(x[i]);
+        }
+    };
+    auto prep_b8 = [&](uint32_t(&x)[NXB], int t, int par) {
+        uint32_t so = (uint32_t)(b_slot(t) + (BKC ? 0 : par * 64 * 256));
+        asm volatile("" : "+s"(so));
+#pragma unroll
+        for (int j = 0; j < NXB; ++j) {
+            x[j] = (BKC ? (lb8[j] ^ (uint32_t)(par * 64)) : lb8[j]) + so;
+            pin(x[j]);
+        }
+    };
+    auto load_pair8 = [&](uint32_t lo, uint32_t hi) -> i32x8 {
+        const u32x4 a = *reinterpret_cast<const u32x4 *>(smem + lo), b = *reinterpret_cast<const u32x4 *>(smem + hi);
+        return i32x8{(int)a[0], (int)a[1], (int)a[2], (int)a[3], (int)b[0], (int)b[1], (int)b[2], (int)b[3]};
+    };
+    auto load_mn8 = [&](uint32_t off) -> i32x8 {
+        typedef int v2i __attribute__((ext_vector_type(2)));
+        typedef __attribute__((address_space(3))) v2i lds_v2i;
+        const unsigned char *a = smem + off;
+        const v2i r0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(a));
+        const v2i r1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(a + 8 * 256));
+        const v2i r2 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(a + 16 * 256));
+        const v2i r3 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(a + 24 * 256));
+        return i32x8{r0[0], r0[1], r1[0], r1[1], r2[0], r2[1], r3[0], r3[1]};
+    };
+    auto load_a8 = [&](i32x8(&fa)[HM], const uint32_t(&x)[NXA]) {
+#pragma unroll
+        for (int i = 0; i < HM; ++i)
+            fa[i] = AK ? load_pair8(x[0] + (uint32_t)(i * 32 * 128), x[AK ? 1 : 0] + (uint32_t)(i * 32 * 128)) : load_mn8(x[AK ? 0 : i]);
+    };
+    auto load_b8 = [&](i32x8(&fb)[FN], const uint32_t(&x)[NXB]) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+            fb[j] = BKC ? load_pair8(x[0] + (uint32_t)(j * 32 * 128), x[BKC ? 1 : 0] + (uint32_t)(j * 32 * 128)) : load_mn8(x[BKC ? 0 : j]);
+    };
+    auto phase_barrier = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    uint32_t xah[NXA], xal[NXA], xb[NXB];
+    // The K-step as four phases with the two waves of a SIMD one phase apart, as in the bf16 kernel; refills and waits as in
+    // the bf16 A*B^T kernel: half of A's pair kt+S, kt+S+1 at the head of every step, B's whole pair kt+3, kt+4 in memory
+    // phase 2 of every odd step; only odd steps wait, for all but A's newest pair.
     auto step = [&](int kt, const i32x8(&fbc)[FN], i32x8(&fbn)[FN], bool last, bool steady, bool even) {
         const int tp = (kt & ~1) + S;                                    // first K-step of the pair being fetched
-        if (steady || tp + 1 < KT) issue_a(tp, even ? 0 : 1);            // A
+        if (steady || tp + 1 < KT) issue_a(tp, even ? 0 : 1);            // memory phase 1
         const bool exact = steady && (!RAGGED || (kbeg + (kt | 1) + S + 1) * BKB <= p.K);
-        read_a(fah, kt, 1);                                              // B
+        load_a8(fah, xah);
+        if (!last && !even) {
+            if (exact) {
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LA) : "memory");
+            } else {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+        }
+        phase_barrier();
+        __builtin_amdgcn_s_setprio(1);                                   // compute phase 1
         mma(fal, fbc, 0);
         if (!last) {
-            if (!even) {                                                 // C
-                if (exact) {
-                    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LA) : "memory");
-                } else {
-                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                }
-            }
-            __syncthreads();
-            if (!even && (steady || kt + S < KT)) issue_b(kt + S - 1);
-            read_a(fal, kt + 1, 0);                                      // D
-            read_b(fbn, kt + 1);
+            prep_b8(xb, kt + 1, even ? 1 : 0);
+            prep_a8(xal, kt + 1, even ? 1 : 0, 0);
         }
+        __builtin_amdgcn_s_setprio(0);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        phase_barrier();
+        if (!last) {                                                     // memory phase 2
+            if (!even && (steady || kt + S < KT)) issue_b(kt + S - 1);
+            load_b8(fbn, xb);
+            load_a8(fal, xal);
+        }
+        phase_barrier();
+        __builtin_amdgcn_s_setprio(1);                                   // compute phase 2
         mma(fah, fbc, 1);
+        if (!last) prep_a8(xah, kt + 1, even ? 1 : 0, 1);
+        __builtin_amdgcn_s_setprio(0);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        phase_barrier();
     };
 
     if (KT > 0) {
@@ -1896,6 +1989,8 @@ __device__ __forceinline__ void gemm_item_dl_f8(const GemmParams &p, const WorkI
         __syncthreads();
         read_a(fal, 0, 0);
         read_b(fb0, 0);
+        prep_a8(xah, 0, 0, 1);
+        if (wave >= C::WGM * C::WGN / 2) phase_barrier();   // the second wave of every SIMD runs one phase behind
         // two K-steps per trip, so that the two column-fragment buffers swap roles without copies
         int kt = 0;
         for (; kt + S + 1 < KT; kt += 2) {        // every refill of both steps exists
@@ -1908,6 +2003,7 @@ __device__ __forceinline__ void gemm_item_dl_f8(const GemmParams &p, const WorkI
         }
         step(KT - 2, fb0, fb1, false, false, true);
         step(KT - 1, fb1, fb0, true, false, false);
+        if (wave < C::WGM * C::WGN / 2) phase_barrier();    // every wave passes the same number of barriers
     }
     __syncthreads();  // every wave is done with the operand ring before the epilogue reuses it
 
