@@ -1358,12 +1358,13 @@ __device__ __forceinline__ void gemm_item_dl(const GemmParams &p, const WorkItem
     // chunk lies past K stores zeros at its LDS position instead of fetching.
     // PAIRED: `part` 0 / 1 issues the first / second half of the wave's loads of the pair, so that every K-step issues the
     // same number of loads; -1 issues all of them.
-    auto issue_a = [&](int t, int part) {
+    // `inside`: the caller knows that the K-steps fetched lie within K (no test, no zero fill)
+    auto issue_a = [&](int t, int part, bool inside = false) {
         constexpr int L = PAIRED ? LAP : LA, SPAN = PAIRED ? 2 : 1;
         const int slot = a_slot(t);
         const unsigned char *sa = ga + (int64_t)rotated(t) * stepa;
         const int i0 = part == 1 ? L / 2 : 0, i1 = part == 0 ? L / 2 : L;
-        if (RAGGED && (kbeg + t + SPAN) * BK > p.K) {
+        if (RAGGED && !inside && (kbeg + t + SPAN) * BK > p.K) {
             const int k_left = p.K - (kbeg + t) * BK;              // contraction elements from t on that exist (may be <= 0)
 #pragma unroll
             for (int i = 0; i < L; ++i) {
@@ -1380,11 +1381,11 @@ __device__ __forceinline__ void gemm_item_dl(const GemmParams &p, const WorkItem
             if (i >= i0 && i < i1) dl_load16(offa[i], sa, lds0 + (uint32_t)(slot + (wave * L + i) * 1024));
     };
     // B of K-step t (PAIRB: of the pair t, t + 1, t even)
-    auto issue_b = [&](int t) {
+    auto issue_b = [&](int t, bool inside = false) {
         constexpr int L = PAIRB ? LBP : LB, SPAN = PAIRB ? 2 : 1;
         const int slot = b_slot(t);
         const unsigned char *sb = gb + (int64_t)rotated(t) * stepb;
-        if (RAGGED && (kbeg + t + SPAN) * BK > p.K) {
+        if (RAGGED && !inside && (kbeg + t + SPAN) * BK > p.K) {
             const int k_left = p.K - (kbeg + t) * BK;
 #pragma unroll
             for (int i = 0; i < L; ++i) {
@@ -1531,17 +1532,17 @@ __device__ __forceinline__ void gemm_item_dl(const GemmParams &p, const WorkItem
             // ended with K-step kt, read for the last time in part D of step kt-1.  Two loads per step before the waits;
             // even steps need no wait at all (both operands of kt+1 are in the pairs already in use)
             const int tp = (kt & ~1) + S;
-            if (steady || tp + 1 < KT) issue_a(tp, even ? 0 : 1);         // A
+            if (steady || tp + 1 < KT) issue_a(tp, even ? 0 : 1, steady);  // A
             exact = steady && (!RAGGED || (kbeg + (kt | 1) + S + 1) * BK <= p.K);
         } else if (PAIRED) {
             const int tp = (kt & ~1) + S;                                 // first K-step of the pair being fetched
-            if (steady || tp + 1 < KT) issue_a(tp, even ? 0 : 1);         // A
-            if (refill) issue_b(kt + S - 1);
+            if (steady || tp + 1 < KT) issue_a(tp, even ? 0 : 1, steady);  // A
+            if (refill) issue_b(kt + S - 1, steady);
             exact = steady && (!RAGGED || (kbeg + (kt | 1) + S + 1) * BK <= p.K);
         } else {
             if (refill) {
-                issue_a(kt + S - 1, -1);                                  // A
-                issue_b(kt + S - 1);
+                issue_a(kt + S - 1, -1, steady);                          // A
+                issue_b(kt + S - 1, steady);
             }
             exact = refill && (!RAGGED || (kbeg + kt + S) * BK <= p.K);
         }
@@ -1573,7 +1574,7 @@ __device__ __forceinline__ void gemm_item_dl(const GemmParams &p, const WorkItem
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         phase_barrier();
         if (!last) {                                                     // memory phase 2
-            if (PAIRB && !even && (steady || kt + S < KT)) issue_b(kt + S - 1);
+            if (PAIRB && !even && (steady || kt + S < KT)) issue_b(kt + S - 1, steady);
             load_b(fbn, xb);
             load_a(fal, xal);
         }
@@ -1623,7 +1624,9 @@ __device__ __forceinline__ void gemm_item_dl(const GemmParams &p, const WorkItem
         // The second wave of every SIMD runs one phase behind the first: while one computes, the other is in a memory phase.
         if (wave >= C::WGM * C::WGN / 2) phase_barrier();
         int kt = 0;
-        for (; kt + S + (PAIRED ? 1 : 0) < KT; kt += 2) {   // every refill of both steps exists: branch-free body
+        // every refill of both steps exists -- and, in a ragged launch, lies within K (only the last pair of K-steps can
+        // reach past it): branch-free body
+        for (; kt + S + (PAIRED ? 1 : 0) + (RAGGED ? 2 : 0) < KT; kt += 2) {
             step(kt, fb0, fb1, false, true, true);
             step(kt + 1, fb1, fb0, false, true, false);
         }
@@ -1797,11 +1800,12 @@ __device__ __forceinline__ void gemm_item_dl_f8(const GemmParams &p, const WorkI
     auto a_slot = [&](int t) { return ((t >> 1) % 3) * (2 * C::A_BYTES); };      // the pair that contains K-step t
     auto b_slot = [&](int t) { return A_REGION + ((t >> 1) & 1) * (2 * C::B_BYTES); };   // the pair that contains K-step t
     // loads of A for the pair of K-steps t, t + 1 (t even): `part` 0 / 1 = first / second half of the wave's loads, -1 = all
-    auto issue_a = [&](int t, int part) {
+    // `inside`: the caller knows that the pair lies within K (no test, no zero fill)
+    auto issue_a = [&](int t, int part, bool inside = false) {
         const int slot = a_slot(t);
         const unsigned char *sa = ga + (int64_t)t * stepa;
         const int i0 = part == 1 ? LAP / 2 : 0, i1 = part == 0 ? LAP / 2 : LAP;
-        if (RAGGED && (kbeg + t + 2) * BKB > p.K) {
+        if (RAGGED && !inside && (kbeg + t + 2) * BKB > p.K) {
             // the pair reaches past K: a lane whose chunk lies past K stores zeros at its LDS position instead of fetching
             const int k_left = p.K - (kbeg + t) * BKB;
 #pragma unroll
@@ -1818,10 +1822,10 @@ __device__ __forceinline__ void gemm_item_dl_f8(const GemmParams &p, const WorkI
             if (i >= i0 && i < i1) dl_load16(offa[i], sa, lds0 + (uint32_t)(slot + (wave * LAP + i) * 1024));
     };
     // loads of B for the pair of K-steps t, t + 1 (t even)
-    auto issue_b = [&](int t) {
+    auto issue_b = [&](int t, bool inside = false) {
         const int slot = b_slot(t);
         const unsigned char *sb = gb + (int64_t)t * stepb;
-        if (RAGGED && (kbeg + t + 2) * BKB > p.K) {
+        if (RAGGED && !inside && (kbeg + t + 2) * BKB > p.K) {
             const int k_left = p.K - (kbeg + t) * BKB;
 #pragma unroll
             for (int i = 0; i < LBP; ++i) {
@@ -1942,7 +1946,7 @@ __device__ __forceinline__ void gemm_item_dl_f8(const GemmParams &p, const WorkI
     // phase 2 of every odd step; only odd steps wait, for all but A's newest pair.
     auto step = [&](int kt, const i32x8(&fbc)[FN], i32x8(&fbn)[FN], bool last, bool steady, bool even) {
         const int tp = (kt & ~1) + S;                                    // first K-step of the pair being fetched
-        if (steady || tp + 1 < KT) issue_a(tp, even ? 0 : 1);            // memory phase 1
+        if (steady || tp + 1 < KT) issue_a(tp, even ? 0 : 1, steady);    // memory phase 1
         const bool exact = steady && (!RAGGED || (kbeg + (kt | 1) + S + 1) * BKB <= p.K);
         load_a8(fah, xah);
         if (!last && !even) {
@@ -1963,7 +1967,7 @@ __device__ __forceinline__ void gemm_item_dl_f8(const GemmParams &p, const WorkI
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         phase_barrier();
         if (!last) {                                                     // memory phase 2
-            if (!even && (steady || kt + S < KT)) issue_b(kt + S - 1);
+            if (!even && (steady || kt + S < KT)) issue_b(kt + S - 1, steady);
             load_b8(fbn, xb);
             load_a8(fal, xal);
         }
@@ -1993,7 +1997,7 @@ __device__ __forceinline__ void gemm_item_dl_f8(const GemmParams &p, const WorkI
         if (wave >= C::WGM * C::WGN / 2) phase_barrier();   // the second wave of every SIMD runs one phase behind
         // two K-steps per trip, so that the two column-fragment buffers swap roles without copies
         int kt = 0;
-        for (; kt + S + 1 < KT; kt += 2) {        // every refill of both steps exists
+        for (; kt + S + 1 + (RAGGED ? 2 : 0) < KT; kt += 2) {   // every refill of both steps exists and lies within K
             step(kt, fb0, fb1, false, true, true);
             step(kt + 1, fb1, fb0, false, true, false);
         }
