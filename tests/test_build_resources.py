@@ -60,10 +60,11 @@ def test_whole_tile_kernels_do_not_spill(kernels):
 
 def test_spills_of_the_other_instances_stay_small(kernels):
     """Ragged instances carry both the bounds-checked and the plain epilogue (interior tiles take the plain one); the
-    instances for launches with shared tiles carry the exchange of partial tiles as well."""
+    instances for launches with shared tiles carry the exchange of partial tiles as well.  Only the ragged bf16 instances of
+    the two pairwise SwiGLU programs (staging of two tile-shaped operands with bounds checks) spill more than a few
+    registers; the 8-bit kernels spill nowhere."""
     for key, r in _gemm(kernels).items():
-        limit = 40 if key[3] else 0
+        limit = (40 if key[2] in (1, 2) else 10) if key[3] else 0
         assert r["spill"] <= limit, (key, r)
     for key, r in _gemm_f8(kernels).items():
-        limit = 40 if key[3] else 0
-        assert r["spill"] <= limit, (key, r)
+        assert r["spill"] == 0 and r["scratch"] == 0, (key, r)
