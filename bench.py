@@ -32,8 +32,8 @@ PEAK_HBM_TBS = 8.0          # MI355X HBM3E
 # by this run: rocprofv3 --pmc counters of profiles/gemm_epilogue_llama1b_mlp_block_hbm_traffic.md (FETCH_SIZE and
 # WRITE_SIZE in KiB per dispatch, each scaled by the factor that the same counter shows for a plain 256 MiB copy in the
 # same profiling run).  Algorithmic bytes are 234.9e6.
-TRAFFIC_FETCH_KIB, TRAFFIC_FETCH_FACTOR = 393585, 2.0
-TRAFFIC_WRITE_KIB, TRAFFIC_WRITE_FACTOR = 131176, 1.0
+TRAFFIC_FETCH_KIB, TRAFFIC_FETCH_FACTOR = 393598, 2.0
+TRAFFIC_WRITE_KIB, TRAFFIC_WRITE_FACTOR = 131201, 1.0
 MEASURED_TRAFFIC_BYTES = int(TRAFFIC_FETCH_KIB * 1024 * TRAFFIC_FETCH_FACTOR + TRAFFIC_WRITE_KIB * 1024 * TRAFFIC_WRITE_FACTOR)
 TRAFFIC_SOURCE = ("stored figure from profiles/gemm_epilogue_llama1b_mlp_block_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE x %.1f + "
                   "WRITE_SIZE x %.1f, factors from a plain 256 MiB copy in the same profiling run; counted at the L2 -> fabric "
