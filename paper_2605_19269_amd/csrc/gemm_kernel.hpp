@@ -1528,8 +1528,8 @@ __device__ __forceinline__ void gemm_item_dl(const GemmParams &p, const WorkItem
         const bool refill = steady || kt + S - 1 < KT;
         bool exact;
         if (PAIRB) {
-            // B's pair kt+3, kt+4 is issued in odd steps only, behind the barrier (part D): its slot held the pair that
-            // ended with K-step kt, read for the last time in part D of step kt-1.  Two loads per step before the waits;
+            // B's pair kt+3, kt+4 is issued in odd steps only, in memory phase 2: its slot held the pair that ended with
+            // K-step kt, read for the last time in memory phase 2 of step kt-1.  Two loads per step before the waits;
             // even steps need no wait at all (both operands of kt+1 are in the pairs already in use)
             const int tp = (kt & ~1) + S;
             if (steady || tp + 1 < KT) issue_a(tp, even ? 0 : 1, steady);  // A
@@ -1676,13 +1676,13 @@ __global__ __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C
 // per lane and operand: lane (row = lane % 32, half = lane / 32) holds bytes 32*half .. 32*half+31 of its row's 64;
 // both operands are loaded with the same rule, so every product pairs bytes of equal k.  The accumulator layout is
 // that of v_mfma_f32_32x32x16_bf16 (Acc32), and the epilogues are shared.
-// Per K-step (one MFMA per 32x32 block) the work is split in two halves of the wave's rows, so that the
-// fragment reads of one half run under the MFMAs of the other, with the workgroup barrier between them:
-//   A  issue half of A's loads of the pair kt+S, kt+S+1 (kt even) / the other half (kt odd); B's pair kt+3, kt+4 follows
-//      behind the barrier of odd steps
-//   B  read the row fragments of the upper half of tile kt; MFMAs of the lower half
-//   C  wait for this wave's loads of tile kt+1; barrier
-//   D  read the lower-half row fragments and the column fragments of tile kt+1; MFMAs of the upper half
+// Per K-step (one MFMA per 32x32 block, eight per wave) the schedule is the bf16 kernel's: four phases with a workgroup
+// barrier between them, the two waves of a SIMD one phase apart, compute phases (four 64-cycle MFMAs) at raised priority:
+//   M1  issue half of A's loads of the pair kt+S, kt+S+1 (kt even) / the other half (kt odd); read the row fragments of
+//       the upper half of tile kt; odd steps wait for all loads but A's newest pair
+//   C1  MFMAs of the lower half; LDS addresses of M2
+//   M2  odd steps: issue B's pair kt+3, kt+4; read the lower-half row fragments and the column fragments of tile kt+1
+//   C2  MFMAs of the upper half; LDS addresses of the next M1
 // ---------------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 
