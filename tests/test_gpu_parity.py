@@ -52,6 +52,24 @@ def test_plain_gemm_store_bf16(oracle, M, N, K, transA, transB):
     G.assert_bf16_close(G.host_f64(out.t), ref, "plain gemm")
 
 
+@pytest.mark.parametrize("transA,transB", LAYOUTS)
+@pytest.mark.parametrize("K", [128, 192, 256, 320, 384, 448, 512, 640, 704])
+def test_k_loop_lengths_whole_tiles(oracle, K, transA, transB):
+    """K-step counts 4 .. 22 on whole tiles: the ring fill alone, the run-dry steps alone, and one to several trips of the
+    steady loop with its waves a phase apart, in all four layouts; fp32 output, so no rounding hides a dropped K-step."""
+    M, N = 256, 512
+    g = rng(7000 + K)
+    A, B = operands(g, M, N, K, transA, transB)
+    out = G.Guarded(M, N, torch.float32, pad_cols=4)
+    coda.coda_gemm(G.dev_bf16(A), G.dev_bf16(B), [coda.store(out.t, f32=True)], transA=transA, transB=transB)
+    torch.cuda.synchronize()
+    ref = oracle.gemm_rowscale(A, B, transA=transA, transB=transB)
+    out.check_guards(); out.written()
+    got = G.host_f64(out.t)
+    scale = np.sqrt(K) * 0.5
+    assert np.abs(got - ref).max() <= 2e-5 * scale * 8, "max |delta| %.3g" % np.abs(got - ref).max()
+
+
 def _random_ragged_cases(n, seed):
     """Seeded shapes around the tile boundaries: M any (a multiple of 8 when A is stored transposed), N and K multiples
     of 8; K below, at and just past multiples of the 32 / 64-element K-steps; one layout and one pitch padding each."""
