@@ -312,3 +312,40 @@ def test_transposed_operand_beyond_4_gib_with_k_tail(oracle):
 
     ref = oracle.gemm_accumulate(bits(A[:, dcols]), bits(B), G0[dcols].cpu().numpy(), transA=True)
     G.assert_f32_signed_close(G.host_f64(Gw[dcols]), ref, "A^T beyond 4 GiB")
+
+
+def test_full_size_launches_repeat_bitwise_with_every_cu_busy():
+    """The three mainloop layouts of the benchmark step at their real shapes, twenty launches each with every compute unit
+    busy and several rounds of tiles: each repeat must reproduce the first launch bit for bit (a read of an LDS ring slot
+    that races its refill, or a wait that is one load short, shows up as a difference here long before it shows in a
+    sampled comparison), and the operands must be untouched."""
+    dev = "cuda"
+    g = torch.Generator(device=dev); g.manual_seed(31)
+    def bf(shape, std):
+        return (torch.randn(shape, generator=g, device=dev) * std).to(torch.bfloat16)
+    M, d, F = 8192, 2048, 8192
+    X, W = bf((M, d), 1.0), bf((d, 2 * F), 0.02)
+    r = torch.rand(M, generator=g, device=dev) + 0.5
+    dY, Wd = bf((M, d), 1e-2), bf((F, d), 0.02)          # dY * Wd^T: both K-contiguous
+    Z = bf((M, 2 * F), 1.0)
+    H = bf((M, F), 1.0)                                  # H^T dY: both token-major, contraction over tokens
+    cases = [
+        ("up-projection A*B", lambda out: coda.coda_gemm(X, W, [coda.row_scale(r), coda.swiglu_fwd(), coda.store(out)]), (M, F), torch.bfloat16, [X, W]),
+        ("SwiGLU backward A*B^T", lambda out: coda.coda_gemm(dY, Wd, [coda.swiglu_bwd(Z), coda.store(out)], transB=True), (M, 2 * F), torch.bfloat16, [dY, Wd, Z]),
+        ("weight gradient A^T*B", lambda out: coda.coda_gemm(H, dY, [coda.store(out, f32=True)], transA=True), (F, d), torch.float32, [H, dY]),
+    ]
+    for name, launch, shape, dt, inputs in cases:
+        before = [t.clone() for t in inputs]
+        first = torch.empty(shape, dtype=dt, device=dev)
+        launch(first)
+        torch.cuda.synchronize()
+        again = torch.empty(shape, dtype=dt, device=dev)
+        for rep in range(20):
+            again.view(torch.uint8).fill_(0xA5)
+            launch(again)
+            torch.cuda.synchronize()
+            assert torch.equal(again.view(torch.uint8), first.view(torch.uint8)), "%s: launch %d differs from the first" % (name, rep + 2)
+        for t, t0 in zip(inputs, before):
+            assert torch.equal(t.view(torch.uint8), t0.view(torch.uint8)), "%s: an operand was modified" % name
+        del first, again, before
+    torch.cuda.empty_cache()
