@@ -25,6 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 FLOP/clk x 2.4 GHz
+PEAK_F8_TFLOPS = 5033.2     # MI355X dense fp8 MFMA: twice that
 
 PEAK_HBM_TBS = 8.0          # MI355X HBM3E
 
@@ -40,19 +41,22 @@ TRAFFIC_SOURCE = ("stored figure from profiles/gemm_epilogue_llama1b_mlp_block_h
                   "boundary, in front of the 256 MB Infinity Cache); not measured by this run" % (TRAFFIC_FETCH_FACTOR, TRAFFIC_WRITE_FACTOR))
 
 
-def roof_entry(kernel, shape, flop, alg_bytes, ms):
-    """Roofline record of one GEMM+epilogue launch: bf16 MFMA peak is the bound of every kernel here (arithmetic intensity
-    455 ... 4587 FLOP/B against a ridge of 315); the HBM floor is the algorithmic bytes at 8 TB/s."""
+def roof_entry(kernel, shape, flop, alg_bytes, ms, peak=None):
+    """Roofline record of one GEMM+epilogue launch: the MFMA peak of its operand type (bf16 unless `peak` says otherwise) is
+    the bound of every kernel here (arithmetic intensity 455 ... 4587 FLOP/B against a ridge of 315); the HBM floor is the
+    algorithmic bytes at 8 TB/s."""
+    peak = peak or PEAK_BF16_TFLOPS
     tf = flop / (ms * 1e-3) * 1e-12
-    return {"kernel": kernel, "shape": shape, "bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS,
-            "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "ms": round(ms, 4),
+    return {"kernel": kernel, "shape": shape, "bound": "mfma", "achieved": round(tf, 1), "peak": peak,
+            "unit": "TFLOP/s", "frac": round(tf / peak, 4), "ms": round(ms, 4),
             "algorithmic_bytes": int(alg_bytes), "hbm_floor_us": round(alg_bytes / (PEAK_HBM_TBS * 1e12) * 1e6, 1),
-            "mfma_floor_us": round(flop / (PEAK_BF16_TFLOPS * 1e12) * 1e6, 1)}
+            "mfma_floor_us": round(flop / (peak * 1e12) * 1e6, 1)}
 
 
 SINGLE_KERNELS = ["llama1b_up", "llama1b_down", "llama1b_bwd_act", "llama1b_bwd_wgt", "llama8b_qkv_rowscale",
                   "llama8b_qkv_rowscale_rope", "llama8b_up_rowscale_swiglu", "llama8b_down_residual_sumsq",
-                  "llama8b_qkv_bwd_rmsnorm_backward", "lm_head_logits_lse_partials", "copy256"]
+                  "llama8b_qkv_bwd_rmsnorm_backward", "lm_head_logits_lse_partials", "f8_llama1b_up", "f8_swiglu_8192_cubed",
+                  "copy256"]
 
 
 def single_kernel(name, steps, warmup, settle):
@@ -70,6 +74,7 @@ def single_kernel(name, steps, warmup, settle):
     def vec(n, lo=0.5, hi=1.5):
         return torch.rand(n, device=dev, generator=g) * (hi - lo) + lo
 
+    peak = None
     if name == "copy256":
         src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -79,6 +84,15 @@ def single_kernel(name, steps, warmup, settle):
         X, W, r, H = rnd((M, K)), rnd((K, N), 0.02), vec(M), torch.empty((M, N // 2), **b16)
         fn = lambda: coda.coda_gemm(X, W, [coda.row_scale(r), coda.swiglu_fwd(), coda.store(H)])
         shape, flop, nbytes, what = [M, N, K], 2.0 * M * N * K, 2 * (M * K + K * N + M * N // 2) + 4 * M, "row scale + SwiGLU (Kernel 6)"
+    elif name in ("f8_llama1b_up", "f8_swiglu_8192_cubed"):
+        # OCP E4M3 operands, both K-contiguous (weights stored [out x in]); same program as the bf16 up-projection
+        M, K, N = (8192, 2048, 16384) if name == "f8_llama1b_up" else (8192, 8192, 8192)
+        x8 = torch.randn((M, K), device=dev, generator=g).to(torch.float8_e4m3fn).view(torch.uint8)
+        w8 = torch.randn((N, K), device=dev, generator=g).to(torch.float8_e4m3fn).view(torch.uint8)
+        r, H = vec(M, 0.01, 0.03), torch.empty((M, N // 2), **b16)
+        fn = lambda: coda.coda_gemm(x8, w8, [coda.row_scale(r), coda.swiglu_fwd(), coda.store(H)], transB=True)
+        shape, flop, nbytes, what = [M, N, K], 2.0 * M * N * K, (M * K + K * N) + 2 * (M * N // 2) + 4 * M, "8-bit operands: row scale + SwiGLU"
+        peak = PEAK_F8_TFLOPS
     elif name in ("llama1b_down", "llama8b_down_residual_sumsq"):
         M, K, N = (8192, 8192, 2048) if name == "llama1b_down" else (16384, 14336, 4096)
         Hh, W, R, Y = rnd((M, K)), rnd((K, N), 0.02), rnd((M, N)), torch.empty((M, N), **b16)
@@ -142,7 +156,7 @@ def single_kernel(name, steps, warmup, settle):
     b.record()
     torch.cuda.synchronize()
     ms = a.elapsed_time(b) / steps
-    rec = roof_entry(what, shape, flop, nbytes, ms) if flop else {"kernel": what, "ms": round(ms, 4), "bytes": nbytes,
+    rec = roof_entry(what, shape, flop, nbytes, ms, peak) if flop else {"kernel": what, "ms": round(ms, 4), "bytes": nbytes,
                                                                  "GBps": round(nbytes / ms * 1e-6, 1)}
     rec.update({"name": name, "launches": steps, "warmup": warmup, "settle": settle, "data": "synthetic"})
     print(json.dumps(rec))
